@@ -1,0 +1,352 @@
+"""Pins for the cyclic-code half of the CPU oracle (no GPU).
+
+Expected values come from the paper and from mathematics, not from the oracle:
+Definition 2 / Theorem 4 by exhaustive enumeration of adversary subsets, the
+caption of Fig. 1 (4 gradients, r = 3, any 2 updates, 6 pairs), Lemma 1
+(support of W, 1_P in the column span), Lemma 4 (clean messages have zero
+syndrome), the identity t = f N from the proof of Lemma 2, a locator written
+from the definition, the Lagrange closed form of b, unitarity of the IDFT
+matrix, and the s = 0 special case (plain sum)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import draco_oracle as o
+
+TINY = [(4, 1), (5, 1), (7, 2), (7, 3), (8, 3), (9, 4)]
+
+
+def _grads(P, d, seed, sigma=1.0):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((P, d)) * sigma).astype(np.float32)
+
+
+def _f(h, seed):
+    rng = np.random.default_rng(seed + 99)
+    return (rng.standard_normal(h) + 1.0).astype(np.float32)
+
+
+def _attack64(R, j, kind, rng):
+    """Edits of an fp64 wire message row (interleaved re/im)."""
+    if kind == "noise":
+        R[j] = rng.standard_normal(R.shape[1]) * 100
+    elif kind == "signflip":
+        R[j] = -100.0 * R[j]
+    elif kind == "offset":
+        R[j] = R[j] + 1e3
+    elif kind == "constant":
+        R[j] = -100.0
+    elif kind == "one_coord":
+        R[j, int(rng.integers(R.shape[1]))] += 1.0
+    else:
+        raise ValueError(kind)
+
+
+# ------------------------------------------------------------------ plan ----
+@pytest.mark.parametrize("P,s", TINY + [(15, 2), (15, 7), (45, 3)])
+def test_assignment_is_the_unit_shift_circle(P, s):
+    A = o.assign_cyclic(P, s)
+    r = 2 * s + 1
+    assert int(A.sum()) == P * r                               # Definition 1
+    assert (A.sum(0) == r).all() and (A.sum(1) == r).all()     # every gradient held r times
+    for j in range(P):
+        assert sorted(np.flatnonzero(A[j])) == sorted((j + t) % P for t in range(r))
+    assert len({tuple(row) for row in A}) == P or r == P       # P distinct sequences on the circle
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 7, 15, 45])
+def test_idft_matrix_is_unitary_and_symmetric(P):
+    C = o.idft_matrix(P)
+    assert np.allclose(C @ C.conj().T, np.eye(P), atol=1e-13)
+    assert np.allclose(C, C.T)
+    # it IS numpy's inverse FFT up to the 1/sqrt(P) convention
+    x = np.random.default_rng(P).standard_normal(P) + 1j * np.random.default_rng(P + 1).standard_normal(P)
+    assert np.allclose(C @ x, np.fft.ifft(x) * np.sqrt(P), atol=1e-12)
+
+
+@pytest.mark.parametrize("P,s", TINY + [(15, 2), (15, 7), (6, 0)])
+def test_weights_solve_equals_closed_form(P, s):
+    """q_j is unique (Sec. 3): the paper's linear solve and the product formula
+    must be the same matrix."""
+    W1 = o.cyclic_weights_solve(P, s)
+    W2 = o.cyclic_weights(P, s)
+    assert np.allclose(W1, W2, rtol=0, atol=1e-11 * np.abs(W2).max())
+
+
+def test_weights_solve_equals_closed_form_P45():
+    W1 = o.cyclic_weights_solve(45, 3)
+    W2 = o.cyclic_weights(45, 3)
+    assert np.abs(W1 - W2).max() <= 1e-8 * np.abs(W2).max()    # the solve loses digits here
+
+
+@pytest.mark.parametrize("P,s", TINY + [(15, 2), (45, 3), (45, 5)])
+def test_lemma1_support_and_lemma4_zero_syndrome(P, s):
+    W = o.cyclic_weights(P, s)
+    A = o.assign_cyclic(P, s)
+    # Z = G W: row k multiplies gradient k, so W[k][j] != 0 only if node j holds k
+    assert np.all((W != 0) == (A.T != 0))
+    C = o.idft_matrix(P)
+    CL, CR = C[:P - 2 * s], C[P - 2 * s:]
+    # rows of W lie in the row space of C_L  <=>  W C_R^dagger = 0  (Lemma 4)
+    assert np.abs(W @ CR.conj().T).max() <= 1e-13 * np.abs(W).max() * P
+    # W = [Q 1] C_L has coefficient 1 on the last row of C_L: W C_L^dagger e_last = 1_P
+    coeff = W @ CL.conj().T
+    assert np.allclose(coeff[:, -1], 1.0, atol=1e-12 * np.abs(W).max() * P)
+
+
+@pytest.mark.parametrize("P,s", TINY)
+def test_lemma1_ones_in_span_for_every_honest_set(P, s):
+    """For EVERY set U of at least P-2s nodes, W_{.,U} b = 1_P is solvable, with
+    either choice of b; and 'first' equals the Lagrange closed form
+    b_j = sqrt(P) / prod_{m in U, m != j} (w^j - w^m)."""
+    W = o.cyclic_weights(P, s)
+    x = np.exp(2j * np.pi * np.arange(P) / P)
+    for size in range(P - 2 * s, P + 1):
+        for U in itertools.combinations(range(P), size):
+            for mode in ("first", "min_norm"):
+                b = o.solve_b(P, s, list(U), mode)
+                assert np.all(b[[j for j in range(P) if j not in U]] == 0)
+                assert np.abs(W @ b - 1.0).max() <= 1e-10
+            Ub = list(U)[:P - 2 * s]
+            lag = np.zeros(P, dtype=complex)
+            for j in Ub:
+                lag[j] = np.sqrt(P) / np.prod([x[j] - x[m] for m in Ub if m != j])
+            assert np.allclose(o.solve_b(P, s, list(U), "first"), lag, atol=1e-10)
+            bmin = o.solve_b(P, s, list(U), "min_norm")
+            assert np.linalg.norm(bmin) <= np.linalg.norm(lag) * (1 + 1e-9)
+
+
+def test_lemma1_at_P45_with_clustered_adversaries():
+    P, s = 45, 3
+    W = o.cyclic_weights(P, s)
+    for V in [(), (7,), (3, 4, 5), (0, 44, 20), (10, 11, 30)]:
+        U = [j for j in range(P) if j not in V]
+        b = o.solve_b(P, s, U, "min_norm")
+        assert np.abs(W @ b - 1.0).max() <= 1e-8
+
+
+# --------------------------------------------------------------- packing ----
+@pytest.mark.parametrize("d", [1, 2, 7, 8])
+@pytest.mark.parametrize("pairing", ["interleaved", "halves"])
+def test_pack_unpack_roundtrip(d, pairing):
+    X = np.random.default_rng(d).standard_normal((3, d))
+    Xc = o.pack_complex(X, pairing)
+    assert Xc.shape == (3, (d + 1) // 2)
+    assert np.array_equal(o.unpack_complex(Xc, d, pairing), X)
+    if pairing == "halves" and d > 1:                           # the paper's pairing: i with ceil(d/2)+i
+        h = (d + 1) // 2
+        assert Xc[0, 0] == X[0, 0] + 1j * X[0, h]
+    assert np.array_equal(o.wire_to_complex(o.complex_to_wire(Xc)), Xc)
+
+
+def test_decoded_sum_does_not_depend_on_the_pairing():
+    P, s, d = 7, 2, 21
+    G = _grads(P, d, 4)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    for pairing in ("interleaved", "halves"):
+        Gc = o.pack_complex(G, pairing)
+        Zc = o.encode_cyclic_complex(Gc, s)
+        Zc[2] = -100 * Zc[2]
+        u_hat, mask, st = o.decode_cyclic_complex(Zc, _f(Gc.shape[1], 1), s)
+        assert st == o.OK and list(np.flatnonzero(mask)) == [2]
+        assert np.allclose(o.unpack_complex(u_hat, d, pairing), ref, atol=1e-9)
+
+
+# ----------------------------------------------------------- s = 0 case -----
+def test_s0_reduces_to_plain_sum():
+    P, d = 6, 40
+    G = _grads(P, d, 8)
+    W = o.cyclic_weights(P, 0)
+    assert np.all((W != 0) == np.eye(P, dtype=bool))            # A = I: one gradient per node
+    Z = o.encode_cyclic(G, 0)
+    u, mask, st = o.decode_cyclic(Z, _f(d // 2, 0), 0, d)
+    assert st == o.OK and not mask.any()
+    assert np.allclose(u, np.sum(G.astype(np.float64), axis=0), atol=1e-12)
+
+
+def test_full_replication_is_a_scaled_sum():
+    """P = 2s+1: every node holds every gradient; C_L is the single constant row,
+    so every message is (1/sqrt P) * G 1_P."""
+    P, s, d = 5, 2, 10
+    G = _grads(P, d, 9)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    ref = o.pack_complex(np.sum(G.astype(np.float64), axis=0)) / np.sqrt(P)
+    for j in range(P):
+        assert np.allclose(Zc[j], ref, atol=1e-13)
+
+
+# ------------------------------------------------------------ Fig. 1 --------
+def test_fig1_four_point_example(golden_dir):
+    """Caption of Fig. 1: with 4 gradients and replication 3 the sum can be
+    recovered from ANY 2 of the 4 updates, so one adversary is out-voted by a
+    majority over all 6 pairs."""
+    gold = {}
+    with open(os.path.join(golden_dir, "fig1_four_point_example.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                gold[k] = int(v)
+    P, r = gold["points"], gold["replication"]
+    s = gold["adversaries"]
+    assert r == 2 * s + 1 and P - 2 * s == gold["sufficient"]
+    d = 12
+    G = _grads(P, d, 42)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    assert int(o.assign_cyclic(P, s).sum()) == P * r
+    pairs = list(itertools.combinations(range(P), gold["sufficient"]))
+    assert len(pairs) == gold["pairs"]
+    # clean: every pair of updates gives the sum
+    for U in pairs:
+        b = o.solve_b(P, s, list(U), "first")
+        u = o.unpack_complex(sum(b[j] * Zc[j] for j in U), d)
+        assert np.allclose(u, ref, atol=1e-12)
+    # one adversary, each position: exactly the C(3,2) = 3 clean pairs agree, and they hold the sum
+    for adv in range(P):
+        Rc = Zc.copy()
+        Rc[adv] = Rc[adv] * -100.0 + 5.0
+        outs = []
+        for U in pairs:
+            b = o.solve_b(P, s, list(U), "first")
+            outs.append(o.unpack_complex(sum(b[j] * Rc[j] for j in U), d))
+        good = [np.allclose(u, ref, atol=1e-10) for u in outs]
+        assert sum(good) == 3
+        assert good == [adv not in U for U in pairs]
+        bad = [u for u, g in zip(outs, good) if not g]
+        for a, b_ in itertools.combinations(bad, 2):
+            assert not np.allclose(a, b_, atol=1e-6)             # the wrong answers do not form a rival majority
+        u, mask, st = o.decode_cyclic(o.complex_to_wire(Rc), _f(d // 2, adv), s, d)
+        assert st == o.OK and list(np.flatnonzero(mask)) == [adv]
+        assert np.allclose(u, ref, atol=1e-10)
+
+
+# -------------------------------------------------------------- locator -----
+@pytest.mark.parametrize("P,s", TINY)
+def test_lemma2_t_equals_f_times_N(P, s):
+    """Proof of Lemma 2: t = C h = gamma = (f N)^T exactly, for every adversary set."""
+    d = 24
+    G = _grads(P, d, P + s)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    f = _f(d // 2, P)
+    rng = np.random.default_rng(P * 31 + s)
+    for a in range(1, s + 1):
+        for V in itertools.combinations(range(P), a):
+            N = np.zeros_like(Zc)
+            for j in V:
+                N[j] = rng.standard_normal(d // 2) * 10 + 1j * rng.standard_normal(d // 2)
+            gamma = o.project(Zc + N, f)
+            mask, t, st = o.phi_from_projection(gamma, s)
+            fN = o.project(N, f)
+            assert st == o.OK
+            assert np.allclose(t, fN, atol=1e-8 * np.abs(fN).max())
+            assert sorted(np.flatnonzero(mask)) == sorted(V)
+            # Lemma 4: the syndromes of R are those of N alone
+            assert np.allclose(o.syndromes(gamma, s), o.syndromes(fN, s), atol=1e-9 * np.abs(fN).max())
+            # and the definition-level locator agrees
+            assert np.array_equal(o.phi_bruteforce(gamma, s), mask)
+
+
+def test_syndromes_are_the_high_dft_bins():
+    P, s = 9, 2
+    gamma = np.random.default_rng(0).standard_normal(P) + 1j * np.random.default_rng(1).standard_normal(P)
+    full = np.fft.fft(gamma) / np.sqrt(P)                       # h = C^dagger gamma
+    assert np.allclose(o.syndromes(gamma, s), full[P - 2 * s:], atol=1e-13)
+
+
+# ------------------------------------------------------ Definition 2 --------
+@pytest.mark.parametrize("P,s", TINY)
+@pytest.mark.parametrize("kind", ["noise", "signflip", "offset", "constant", "one_coord"])
+def test_definition2_every_adversary_subset(P, s, kind):
+    """Theorem 4: every adversary set of size <= s, fp64 wire: decode = G 1_P and
+    the mask is exactly the set of liars."""
+    d = 19                                                       # odd: exercises the zero pad
+    G = _grads(P, d, 5 * P + s)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Z = o.encode_cyclic(G, s)
+    f = _f(Z.shape[1] // 2, P + 7)
+    rng = np.random.default_rng(P * 17 + s)
+    for a in range(0, s + 1):
+        for V in itertools.combinations(range(P), a):
+            R = Z.copy()
+            for j in V:
+                _attack64(R, j, kind, rng)
+            for b_mode in ("min_norm", "first"):
+                u, mask, st = o.decode_cyclic(R, f, s, d, b_mode)
+                assert st == o.OK
+                assert sorted(np.flatnonzero(mask)) == sorted(V)
+                assert np.linalg.norm(u - ref) <= 1e-9 * np.linalg.norm(ref)
+
+
+def test_more_than_s_adversaries_is_reported():
+    P, s, d = 9, 2, 40
+    G = _grads(P, d, 77)
+    Z = o.encode_cyclic(G, s)
+    rng = np.random.default_rng(5)
+    R = Z.copy()
+    for j in (0, 3, 6):
+        R[j] = rng.standard_normal(R.shape[1]) * 100
+    _, _, st = o.decode_cyclic(R, _f(d // 2, 3), s, d)
+    assert st == o.LOCATE_FAILED
+
+
+# ------------------------------------------------- fp32 wire behaviour ------
+@pytest.mark.parametrize("P,s,d,sigma,advs,tol", [
+    (15, 2, 40_000, 1.0, [(3, "offset"), (9, "offset")], 5e-6),
+    (15, 2, 40_000, 1.0, [(3, "offset"), (4, "signflip")], 5e-6),
+    (15, 2, 40_000, 1.0, [], 5e-6),
+    (45, 3, 40_000, 1e-2, [(3, "noise"), (4, "signflip"), (20, "noise")], 1e-3),
+    (45, 3, 40_000, 1e-2, [(44, "signflip"), (0, "noise")], 1e-3),
+    (45, 3, 40_000, 1e-2, [], 1e-3),
+])
+def test_fp32_wire_locates_exactly_and_error_is_the_wire_floor(P, s, d, sigma, advs, tol):
+    """With messages rounded to fp32 the clean syndrome is no longer exactly zero;
+    the thresholds must still give the exact mask, and the end-to-end error is
+    the quantisation floor of the code (grows with max|W|: ~1e-6 at (15,2),
+    ~2e-4 at (45,3))."""
+    rng = np.random.default_rng(P + s + len(advs))
+    G = (rng.standard_normal((P, d)) * sigma).astype(np.float32)
+    R = o.encode_cyclic(G, s).astype(np.float32)
+    for j, kind in advs:
+        if kind == "noise":
+            R[j] = (rng.standard_normal(R.shape[1]) * 100).astype(np.float32)
+        elif kind == "signflip":
+            R[j] = R[j] * np.float32(-100)
+        elif kind == "offset":
+            R[j] = R[j] + np.float32(1e3)
+    f = _f(R.shape[1] // 2, 5)
+    u, mask, st = o.decode_cyclic(R, f, s, d)
+    assert st == o.OK
+    assert sorted(np.flatnonzero(mask)) == sorted(j for j, _ in advs)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    assert np.linalg.norm(u - ref) <= tol * np.linalg.norm(ref)
+
+
+def test_planted_mistakes_are_caught():
+    """Plausible slips, each planted in a copy of the oracle's steps, must break a pin."""
+    P, s, d = 7, 2, 16
+    G = _grads(P, d, 3)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    W = o.cyclic_weights(P, s)
+    Gc = o.pack_complex(G)
+    # (1) transposed operand: node j using ROW j of W
+    Zbad = np.zeros_like(Gc)
+    for j in range(P):
+        for k in range(P):
+            Zbad[j] += W[j, k] * Gc[k]
+    U = list(range(P))
+    b = o.solve_b(P, s, U)
+    assert not np.allclose(o.unpack_complex(sum(b[j] * Zbad[j] for j in U), d), ref, atol=1e-6)
+    # (2) conjugate dropped in the syndrome: clean messages no longer have zero syndrome
+    Zc = o.encode_cyclic_complex(Gc, s)
+    gamma = o.project(Zc, _f(d // 2, 1))
+    C = o.idft_matrix(P)
+    assert np.abs(o.syndromes(gamma, s)).max() <= 1e-12 * np.abs(gamma).max()
+    assert np.abs(C[P - 2 * s:] @ gamma).max() > 1e-3 * np.abs(gamma).max()
+    # (3) e_first instead of e_last as the right-hand side for b
+    CL = C[:P - 2 * s]
+    e0 = np.zeros(P - 2 * s, dtype=complex)
+    e0[0] = 1
+    b0 = np.linalg.lstsq(CL, e0, rcond=None)[0]
+    assert np.abs(W @ b0 - 1).max() > 1e-3
