@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the DRACO encode/decode hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i]
+
+A step is one pass of the whole hot path over one batch of synthetic gradient
+slabs already resident in HBM: the encoder of all P nodes (G -> Z), then the
+parameter-server decoder on the received messages R (Z with the workload's
+adversarial rows), through the synchronous C-ABI entry points (sum left on the
+device, mask and status on the host).  The metric is the benchmark contract's
+"decoded gradient GB/s consumed": P*d*4 bytes per step divided by the step
+time.  One JSON line is printed; it also carries the roofline of the dominant
+kernel (HIP-event durations recorded by the library on the launch stream) and
+the CPU oracle timed on a bounded sample on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+KIND_NAMES = ["encode", "vote", "project", "recombine"]
+
+
+def algorithmic_bytes(w, mlen, n_honest):
+    """Bytes each kernel must move per launch (every input read once, every output written once)."""
+    P, d, h = w.P, w.d, (w.d + 1) // 2
+    return {
+        "encode": (P * d + P * mlen) * 4,
+        "vote": (P * d + d) * 4,
+        "project": (P * mlen + h) * 4,
+        "recombine": (n_honest * mlen + d) * 4,
+    }
+
+
+def cpu_baseline(w):
+    """The oracle as it stands, on a slice of the same workload sized for ~10-30 s."""
+    import numpy as np
+    import psutil
+    import torch
+
+    from oracle import draco_oracle as o
+    from paper_1803_09877_amd import synth
+
+    d_s = min(w.d, 4_000_000 if w.code == "cyc" else 8_000_000)
+    ws = synth.scaled(w, d_s)
+    G = synth.make_gradients(ws.P, d_s, ws.sigma, ws.seed, device="cpu")[:, :d_s].numpy()
+    f = synth.make_projection((d_s + 1) // 2, ws.seed).numpy()
+    proc = psutil.Process()
+    c0, t0 = proc.cpu_times(), time.perf_counter()
+    if ws.code == "rep":
+        Z = o.encode_repetition(G, ws.s).astype(np.float32)
+    else:
+        Z = o.encode_cyclic(G, ws.s).astype(np.float32)
+    t_enc = time.perf_counter() - t0
+    R = torch.from_numpy(Z)
+    synth.apply_attacks(R, Z.shape[1], ws.adversaries(), ws.seed)
+    t1 = time.perf_counter()
+    t_dec = 0.0
+    if ws.decode:
+        if ws.code == "rep":
+            _, mask, st = o.decode_repetition(R.numpy(), ws.s)
+        else:
+            _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s)
+        t_dec = time.perf_counter() - t1
+        assert st == 0 and sorted(np.flatnonzero(mask)) == sorted(j for j, _ in ws.adversaries())
+    c1 = proc.cpu_times()
+    wall = t_enc + t_dec
+    busy = (c1.user + c1.system) - (c0.user + c0.system)
+    return {
+        "value": ws.P * d_s * 4 / wall / 1e9,
+        "unit": "GB/s",
+        "cores": max(1, round(busy / max(wall, 1e-9))),
+        "cores_available": len(os.sched_getaffinity(0)),
+        "kind": "oracle",
+        "sample": f"same recipe at d={d_s} (of {w.d}), P={ws.P}, s={ws.s}; encode {t_enc:.2f} s + decode {t_dec:.2f} s",
+        "encode_s": t_enc,
+        "decode_s": t_dec,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into the five benchmark workloads (default 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the P nodes are message slabs in one GPU's HBM); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1803_09877_amd import binding as B
+    from paper_1803_09877_amd import synth
+    from paper_1803_09877_amd.runner import Case
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = synth.WORKLOADS[args.config]
+    c = Case(w, "cuda:0")
+    c.encode()
+    c.receive()
+    torch.cuda.synchronize()
+    n_honest = w.P - len(c.adversaries)
+    if w.decode:
+        mask, status = c.decode()
+        assert status == 0 and np.array_equal(mask, c.expected_mask()), "decode did not find the planted adversaries"
+
+    for _ in range(args.warmup):
+        c.step()
+    c.plan.set_timing(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        c.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    abytes = algorithmic_bytes(w, c.mlen, n_honest)
+    kernels = {}
+    for kind, name in enumerate(KIND_NAMES):
+        total_ms, n = c.plan.kernel_time(kind)
+        if n:
+            avg = total_ms / n
+            kernels[name] = {"avg_ms": avg, "launches": n, "algorithmic_bytes": abytes[name],
+                             "GBps": abytes[name] / avg / 1e6, "frac_hbm_peak": abytes[name] / avg / 1e6 / HBM_PEAK_GBS}
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    roof = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": kernels[dominant]["GBps"] / HBM_PEAK_GBS, "traffic": None}
+
+    consumed = w.P * w.d * 4
+    out = {
+        "metric": "decoded gradient GB/s consumed (P x d fp32)",
+        "value": consumed / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.code == "rep" else "f64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "code": w.code, "P": w.P, "s": w.s, "d": w.d,
+                   "adversaries": [[int(j), a] for j, a in c.adversaries],
+                   "step": "encode(all nodes) + decode" if w.decode else "encode(all nodes)"},
+        "pct_hbm_peak_consumed": consumed / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100,
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    c.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

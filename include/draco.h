@@ -1,0 +1,190 @@
+/*
+ * draco.h -- C ABI of the MI355X (gfx950) implementation of DRACO's
+ * data-parallel hot path (arXiv 1803.09877): the node-side encoder and the
+ * parameter-server decoder, for the repetition code and the cyclic code.
+ *
+ * The P compute nodes of the paper are simulated on ONE GPU: a "slab" is a
+ * row-major fp32 matrix in device memory with one row per node (messages) or
+ * per unit gradient (inputs; B = P as in Sec. 3), coordinates contiguous.
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; pointers
+ *     named *_host are HOST pointers owned by the caller.  The library keeps
+ *     none of them after the call returns.
+ *   - `ld*` is a row stride in floats.  Every slab base pointer must be
+ *     16-byte aligned and every stride a multiple of 4 floats and at least
+ *     the row length; otherwise DRACO_EALIGN is returned.
+ *   - `stream` is a hipStream_t (NULL = the null stream).  Kernels are
+ *     enqueued on it.  Entry points that return data to the host
+ *     (draco_decode_repetition, draco_decode_cyclic) wait for `stream`
+ *     before returning; the *_async forms and draco_encode* do not wait.
+ *   - Return value 0 (DRACO_OK) on success.  Negative values are caller or
+ *     runtime errors and leave the outputs untouched or unspecified.
+ *     Positive values mean the decoder ran but the input violated the
+ *     method's contract (more than s adversaries): the sum is then not to be
+ *     trusted and the mask is a best effort.
+ *   - No exceptions cross the boundary.  Calls on distinct plans may run
+ *     concurrently; calls on ONE plan must not overlap (a plan owns scratch
+ *     memory that its decode calls reuse).
+ *   - The device that is current when a plan first touches the GPU
+ *     (draco_plan_prepare or the first encode/decode) owns the plan.
+ */
+#ifndef DRACO_H
+#define DRACO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct draco_plan draco_plan;
+
+enum draco_code {
+    DRACO_CODE_REPETITION = 0, /* Sec. 3, "Fractional Repetition Code" */
+    DRACO_CODE_CYCLIC = 1      /* Sec. 3, "Cyclic Code" */
+};
+
+enum draco_status {
+    DRACO_OK = 0,
+    DRACO_NO_MAJORITY = 1,   /* repetition: a group has more than s nodes that differ from its vote */
+    DRACO_LOCATE_FAILED = 2, /* cyclic: no set of at most s nodes accounts for the syndromes */
+    DRACO_EINVAL = -1,       /* null pointer, P < 1, s < 0, 2s+1 > P, (2s+1) does not divide P (repetition), d < 1, P > DRACO_MAX_NODES, wrong code for the call */
+    DRACO_EALIGN = -2,       /* pointer or stride alignment (see above) */
+    DRACO_EHIP = -3,         /* a HIP runtime call failed (no device, out of memory, launch failure) */
+    DRACO_ENOMEM = -4        /* host allocation failed */
+};
+
+#define DRACO_MAX_NODES 256
+
+/* ---- plan ------------------------------------------------------------- */
+
+/* Build the code for P nodes tolerating s adversaries on d-dimensional
+ * gradients: the allocation matrix A (A^Rep: P/r all-ones r x r diagonal
+ * blocks, r = 2s+1; A^Cyc: node j holds gradients j..j+2s mod P) and, for the
+ * cyclic code, the encoding matrix W = [Q 1] C_L of Sec. 3 (computed in
+ * closed form on the host in extended precision).  Conditions checked:
+ * Theorem 1's corollary 2s+1 <= P, and (2s+1) | P for the repetition code.
+ * Host-only: works without a GPU.  *out is set only on success. */
+int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d);
+
+/* Allocate the plan's device-side tables and scratch on the current device
+ * (a few MB: per-node coefficients, per-wave partial projections, flag
+ * words).  Called implicitly by the first encode/decode if omitted; after it
+ * no entry point allocates device memory. */
+int draco_plan_prepare(draco_plan* plan);
+
+/* Free the plan and everything it owns (waits for the device if prepared). */
+void draco_plan_destroy(draco_plan* plan);
+
+/* Floats per message row: d for the repetition code; 2*ceil(d/2) for the
+ * cyclic code (ceil(d/2) complex numbers, real and imaginary part interleaved;
+ * complex coordinate i packs real coordinates 2i and 2i+1 -- the packing at
+ * the end of Sec. 3 with adjacent instead of half-apart pairs).  < 0 on a
+ * null plan. */
+int64_t draco_message_len(const draco_plan* plan);
+
+/* A_host[j*P + k] = 1 if node j is assigned gradient k, else 0 (P*P bytes). */
+int draco_plan_assign(const draco_plan* plan, uint8_t* A_host);
+
+/* W_host[(k*P + j)*2 + {0,1}] = real, imaginary part of W[k][j]: the weight of
+ * gradient k in node j's message (Z = G W).  Repetition code: A^T as 0/1. */
+int draco_plan_weights(const draco_plan* plan, double* W_host);
+
+/* ---- encoder (node side) ---------------------------------------------- */
+
+/* All P nodes at once: messages[j] = E_j(Y_j).
+ * Repetition (E^Rep): z_j = sum of the r gradients of node j's group, added in
+ * ascending k in fp32; computed once per group and stored r times, so the r
+ * copies are bit-identical.
+ * Cyclic (E^Cyc): z_j = sum_{k in S_j} W[k][j] * g^_k on packed complex
+ * gradients, accumulated in fp64 and rounded once to fp32.
+ *   grads_dev     [P][ld_g]  fp32, row k = gradient k, first d floats used
+ *                  (cyclic with odd d: coordinate d is taken as 0, it need not
+ *                  be stored as 0)
+ *   messages_dev  [P][ld_m]  fp32, first draco_message_len() floats written
+ * Asynchronous on `stream`. */
+int draco_encode(draco_plan* plan, const float* grads_dev, int64_t ld_g,
+                 float* messages_dev, int64_t ld_m, void* stream);
+
+/* One node, as a real compute node would run it: node_grads_dev holds ONLY
+ * that node's r = 2s+1 assigned gradients, [r][ld_g], in assignment order
+ * (repetition: ascending k within the group; cyclic: k = node, node+1, ...,
+ * node+2s mod P).  Writes one message row.  Same arithmetic and order as
+ * draco_encode, so the result is bit-identical to row `node` of it. */
+int draco_encode_node(draco_plan* plan, int node, const float* node_grads_dev,
+                      int64_t ld_g, float* message_dev, void* stream);
+
+/* ---- decoder (parameter server) --------------------------------------- */
+
+/* D^Rep: per group of r consecutive nodes, majority vote (Algorithm 2, the
+ * streaming vote, applied per coordinate on bit patterns, then a count), sum
+ * of the P/r winners in ascending group order in fp32.
+ *   messages_dev [P][ld_m] fp32 as received (R = Z + N)
+ *   sum_dev      [d]       fp32 out: u = G 1_P
+ *   mask_host    [ceil(P/64)] out: bit (j%64) of word j/64 set iff node j's
+ *                message differs from its group's vote in any coordinate
+ * Returns DRACO_NO_MAJORITY if some group has more than s such nodes.
+ * Waits for `stream`. */
+int draco_decode_repetition(draco_plan* plan, const float* messages_dev, int64_t ld_m,
+                            float* sum_dev, uint64_t* mask_host, void* stream);
+
+/* Same, stream-ordered: mask_dev [ceil(P/64)] and status_dev [1] (a
+ * draco_status value) are DEVICE outputs valid once `stream` reaches the end
+ * of the call.  Does not wait. */
+int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, int64_t ld_m,
+                                  float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
+                                  void* stream);
+
+/* D^Cyc (Algorithm 1): V = phi(R) (random projection f R, syndromes
+ * f R C_R^dagger, the s x s system for beta, the recurrence for the remaining
+ * h_l, IDFT), U = complement, b with W_{.,U} b = 1_P (minimum-norm), and
+ * u = R_{.,U} b, unpacked to d reals.
+ *   messages_dev [P][ld_m] fp32, complex interleaved (see draco_message_len)
+ *   f_dev        [ceil(d/2)] fp32: the random vector f ~ N(1, I) of phi, one
+ *                entry per complex coordinate, drawn by the caller
+ *   sum_dev      [d] fp32 out
+ *   mask_host    as above: the located set V
+ * Returns DRACO_LOCATE_FAILED if no set of at most s nodes explains the
+ * syndromes, or if a projection is not finite.  Waits for `stream` (the
+ * small linear algebra of phi and b runs on the host between two kernels). */
+int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_m,
+                        const float* f_dev, float* sum_dev, uint64_t* mask_host,
+                        void* stream);
+
+/* ---- host-side pieces of D^Cyc, exposed for inspection and testing ----- */
+
+/* phi, steps 2-4, on the P projections gamma'_j = f . r_j given as
+ * gamma_host[2j], gamma_host[2j+1] (re, im).  Writes the mask words and, if
+ * t_host != NULL, the vector t (2P doubles).  Returns DRACO_OK or
+ * DRACO_LOCATE_FAILED.  Host-only. */
+int draco_cyclic_locate(const draco_plan* plan, const double* gamma_host,
+                        uint64_t* mask_host, double* t_host);
+
+/* The minimum-norm b with C_L[:, U] b_U = e_last (proof of Lemma 1) for
+ * U = nodes whose mask bit is clear; b_host[2j], b_host[2j+1] = re, im of b_j,
+ * zero on masked nodes.  Needs at most 2s masked nodes.  Host-only. */
+int draco_cyclic_recombination_vector(const draco_plan* plan, const uint64_t* mask_host,
+                                      double* b_host);
+
+/* ---- misc -------------------------------------------------------------- */
+
+/* Static, NUL-terminated description of a status value. */
+const char* draco_strerror(int status);
+
+/* Kernel timing with HIP events recorded on the stream each kernel is launched
+ * on.  draco_plan_set_timing(plan, n) gives every kernel kind n event pairs
+ * (n = 0 switches timing off); from then on each launch of a kind uses the next
+ * free pair (launches beyond n are not timed) and nothing waits.
+ * draco_plan_kernel_time waits for the recorded kernels of one kind, returns
+ * their summed duration in milliseconds and their number, and frees the pairs
+ * for reuse.  kind: 0 encode, 1 repetition vote, 2 cyclic projection (with its
+ * small reduction), 3 cyclic recombination. */
+int draco_plan_set_timing(draco_plan* plan, int max_records);
+int draco_plan_kernel_time(draco_plan* plan, int kind, double* total_ms, int* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DRACO_H */

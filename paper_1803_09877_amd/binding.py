@@ -1,0 +1,248 @@
+"""ctypes binding of ``libdraco.so`` (declared in ``include/draco.h``).
+
+Argument marshalling only: every step of the encode/decode path runs in the
+library's HIP kernels and host algebra.  Device memory is passed as torch
+tensors (``data_ptr()``), streams as ``torch.cuda.Stream`` objects or ``None``
+for torch's current stream.  If the shared library has not been built the
+import fails with instructions; there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+LIB_PATH = os.path.join(_HERE, "libdraco.so")
+SOURCES = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hip", "api.hip", "host_math.cpp")]
+HEADERS = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hpp", "host_math.hpp")] + [
+    os.path.join(_ROOT, "include", "draco.h")]
+
+CODE_REPETITION, CODE_CYCLIC = 0, 1
+OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
+EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
+KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE = 0, 1, 2, 3
+MAX_NODES = 256
+
+EXPORTS = [
+    "draco_plan_create", "draco_plan_prepare", "draco_plan_destroy", "draco_message_len",
+    "draco_plan_assign", "draco_plan_weights", "draco_encode", "draco_encode_node",
+    "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
+    "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
+    "draco_plan_set_timing", "draco_plan_kernel_time",
+]
+
+
+def build(verbose: bool = False) -> str:
+    """Compile the library for gfx950 in-tree with hipcc (cross-compiles without a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I" + os.path.join(_ROOT, "include"), *SOURCES, "-o", LIB_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(" ".join(cmd))
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libdraco.so")
+    return LIB_PATH
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no non-HIP fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    L.draco_plan_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64]
+    L.draco_plan_create.restype = i32
+    L.draco_plan_prepare.argtypes = [vp]
+    L.draco_plan_prepare.restype = i32
+    L.draco_plan_destroy.argtypes = [vp]
+    L.draco_plan_destroy.restype = None
+    L.draco_message_len.argtypes = [vp]
+    L.draco_message_len.restype = i64
+    L.draco_plan_assign.argtypes = [vp, vp]
+    L.draco_plan_assign.restype = i32
+    L.draco_plan_weights.argtypes = [vp, vp]
+    L.draco_plan_weights.restype = i32
+    L.draco_encode.argtypes = [vp, vp, i64, vp, i64, vp]
+    L.draco_encode.restype = i32
+    L.draco_encode_node.argtypes = [vp, i32, vp, i64, vp, vp]
+    L.draco_encode_node.restype = i32
+    L.draco_decode_repetition.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.draco_decode_repetition.restype = i32
+    L.draco_decode_repetition_async.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.draco_decode_repetition_async.restype = i32
+    L.draco_decode_cyclic.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.draco_decode_cyclic.restype = i32
+    L.draco_cyclic_locate.argtypes = [vp, vp, vp, vp]
+    L.draco_cyclic_locate.restype = i32
+    L.draco_cyclic_recombination_vector.argtypes = [vp, vp, vp]
+    L.draco_cyclic_recombination_vector.restype = i32
+    L.draco_strerror.argtypes = [i32]
+    L.draco_strerror.restype = ctypes.c_char_p
+    L.draco_plan_set_timing.argtypes = [vp, i32]
+    L.draco_plan_set_timing.restype = i32
+    L.draco_plan_kernel_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    L.draco_plan_kernel_time.restype = i32
+    _lib = L
+    return L
+
+
+class DracoError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"draco status {status}: {lib().draco_strerror(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status < 0:
+        raise DracoError(status)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def mask_words(P: int) -> int:
+    return (P + 63) // 64
+
+
+def mask_to_bool(words: np.ndarray, P: int) -> np.ndarray:
+    return np.array([(int(words[j >> 6]) >> (j & 63)) & 1 for j in range(P)], dtype=bool)
+
+
+def bool_to_mask(mask, P: int) -> np.ndarray:
+    words = np.zeros(mask_words(P), dtype=np.uint64)
+    for j in range(P):
+        if mask[j]:
+            words[j >> 6] |= np.uint64(1) << np.uint64(j & 63)
+    return words
+
+
+class Plan:
+    """One (code, P, s, d) instance of the library's plan object."""
+
+    def __init__(self, code: int, P: int, s: int, d: int):
+        self._h = ctypes.c_void_p()
+        status = lib().draco_plan_create(ctypes.byref(self._h), code, P, s, d)
+        if status != OK:
+            self._h = None
+            raise DracoError(status)
+        self.code, self.P, self.s, self.d = code, P, s, d
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().draco_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    # ---- host-only ----
+    @property
+    def message_len(self) -> int:
+        return int(lib().draco_message_len(self._h))
+
+    def assign(self) -> np.ndarray:
+        A = np.zeros((self.P, self.P), dtype=np.uint8)
+        _check(lib().draco_plan_assign(self._h, A.ctypes.data))
+        return A
+
+    def weights(self) -> np.ndarray:
+        W = np.zeros((self.P, self.P, 2), dtype=np.float64)
+        _check(lib().draco_plan_weights(self._h, W.ctypes.data))
+        return W[..., 0] + 1j * W[..., 1]
+
+    def cyclic_locate(self, gamma: np.ndarray):
+        """(mask bool[P], t complex[P], status) from the P projections."""
+        g = np.ascontiguousarray(np.stack([gamma.real, gamma.imag], axis=-1), dtype=np.float64)
+        words = np.zeros(mask_words(self.P), dtype=np.uint64)
+        t = np.zeros((self.P, 2), dtype=np.float64)
+        status = lib().draco_cyclic_locate(self._h, g.ctypes.data, words.ctypes.data, t.ctypes.data)
+        _check(status)
+        return mask_to_bool(words, self.P), t[:, 0] + 1j * t[:, 1], status
+
+    def cyclic_recombination_vector(self, mask) -> np.ndarray:
+        words = bool_to_mask(mask, self.P)
+        b = np.zeros((self.P, 2), dtype=np.float64)
+        status = lib().draco_cyclic_recombination_vector(self._h, words.ctypes.data, b.ctypes.data)
+        if status != OK:
+            raise DracoError(status)
+        return b[:, 0] + 1j * b[:, 1]
+
+    # ---- device ----
+    def prepare(self) -> None:
+        _check(lib().draco_plan_prepare(self._h))
+
+    def encode(self, grads, messages, stream=None) -> None:
+        _check(lib().draco_encode(self._h, grads.data_ptr(), grads.stride(0), messages.data_ptr(),
+                                  messages.stride(0), _stream_ptr(stream)))
+
+    def encode_node(self, node: int, node_grads, message, stream=None) -> None:
+        _check(lib().draco_encode_node(self._h, node, node_grads.data_ptr(), node_grads.stride(0),
+                                       message.data_ptr(), _stream_ptr(stream)))
+
+    def decode_repetition(self, messages, out_sum, stream=None):
+        """-> (mask bool[P], status); the sum is written to ``out_sum``."""
+        words = np.zeros(mask_words(self.P), dtype=np.uint64)
+        status = lib().draco_decode_repetition(self._h, messages.data_ptr(), messages.stride(0),
+                                               out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
+        _check(status)
+        return mask_to_bool(words, self.P), status
+
+    def decode_repetition_async(self, messages, out_sum, mask_dev, status_dev, stream=None) -> None:
+        _check(lib().draco_decode_repetition_async(self._h, messages.data_ptr(), messages.stride(0),
+                                                   out_sum.data_ptr(), mask_dev.data_ptr(),
+                                                   status_dev.data_ptr(), _stream_ptr(stream)))
+
+    def decode_cyclic(self, messages, f, out_sum, stream=None):
+        words = np.zeros(mask_words(self.P), dtype=np.uint64)
+        status = lib().draco_decode_cyclic(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+                                           out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
+        _check(status)
+        return mask_to_bool(words, self.P), status
+
+    def set_timing(self, max_records: int) -> None:
+        _check(lib().draco_plan_set_timing(self._h, max_records))
+
+    def kernel_time(self, kind: int):
+        """(total_ms, launches) of the timed kernels of one kind since the last query."""
+        ms, n = ctypes.c_double(), ctypes.c_int()
+        _check(lib().draco_plan_kernel_time(self._h, kind, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+
+# Names of the C entry points, module-level, same spelling as the header.
+def draco_encode(plan: Plan, grads, messages, stream=None) -> None:
+    plan.encode(grads, messages, stream)
+
+
+def draco_encode_node(plan: Plan, node: int, node_grads, message, stream=None) -> None:
+    plan.encode_node(node, node_grads, message, stream)
+
+
+def draco_decode_repetition(plan: Plan, messages, out_sum, stream=None):
+    return plan.decode_repetition(messages, out_sum, stream)
+
+
+def draco_decode_cyclic(plan: Plan, messages, f, out_sum, stream=None):
+    return plan.decode_cyclic(messages, f, out_sum, stream)

@@ -1,0 +1,427 @@
+// C ABI of the library (see include/draco.h): argument checks, the plan object
+// with its device tables and scratch, and the sequencing of kernels and host
+// algebra for each entry point.
+#include "../../include/draco.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <complex>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "host_math.hpp"
+#include "kernels.hpp"
+
+using namespace draco;
+
+namespace {
+
+enum Kind { kEncode = 0, kVote = 1, kProject = 2, kRecombine = 3, kKinds = 4 };
+
+// Ring of HIP event pairs bracketing the kernels of one kind.
+struct Timer {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+};
+
+}  // namespace
+
+struct draco_plan {
+    int code = 0, P = 0, s = 0;
+    int64_t d = 0;
+    CyclicCode cyc;
+
+    // device side (valid once prepared)
+    bool prepared = false;
+    int device = -1;
+    double2* taps_dev = nullptr;     // 2s+1
+    double2* rot_dev = nullptr;      // P
+    double2* partial_dev = nullptr;  // project_tiles(d) * P
+    double2* gamma_dev = nullptr;    // P
+    double2* b_dev = nullptr;        // P
+    int32_t* idx_dev = nullptr;      // P
+    uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
+    uint64_t* mask_dev = nullptr;    // kMaskWords
+    int32_t* status_dev = nullptr;   // 1
+    // pinned host staging
+    double* gamma_pin = nullptr;     // 2P
+    double* b_pin = nullptr;         // 2P
+    int32_t* idx_pin = nullptr;      // P
+    uint64_t* mask_pin = nullptr;    // kMaskWords + 1 (status in the last word)
+
+    Timer timers[kKinds];
+};
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_slab(const void* p, int64_t ld, int64_t row_len) {
+    if (p == nullptr) return DRACO_EINVAL;
+    if (!aligned16(p) || (ld & 3) != 0 || ld < row_len) return DRACO_EALIGN;
+    return DRACO_OK;
+}
+
+int64_t message_len(const draco_plan* p) {
+    return p->code == DRACO_CODE_REPETITION ? p->d : 2 * ((p->d + 1) / 2);
+}
+
+#define HIP_TRY(expr)                           \
+    do {                                        \
+        if ((expr) != hipSuccess) {             \
+            (void)hipGetLastError();            \
+            return DRACO_EHIP;                  \
+        }                                       \
+    } while (0)
+
+int prepare(draco_plan* p) {
+    if (p->prepared) return DRACO_OK;
+    HIP_TRY(hipGetDevice(&p->device));
+    const int P = p->P, r = 2 * p->s + 1;
+    HIP_TRY(hipMalloc(&p->flags_dev, kMaskWords * sizeof(uint64_t)));
+    HIP_TRY(hipMemset(p->flags_dev, 0, kMaskWords * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&p->mask_dev, kMaskWords * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&p->status_dev, sizeof(int32_t)));
+    HIP_TRY(hipHostMalloc(&p->mask_pin, (kMaskWords + 1) * sizeof(uint64_t), hipHostMallocDefault));
+    if (p->code == DRACO_CODE_CYCLIC) {
+        HIP_TRY(hipMalloc(&p->taps_dev, r * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->rot_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(p->d) * P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->gamma_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->b_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->idx_dev, P * sizeof(int32_t)));
+        HIP_TRY(hipHostMalloc(&p->gamma_pin, 2 * P * sizeof(double), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&p->b_pin, 2 * P * sizeof(double), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&p->idx_pin, P * sizeof(int32_t), hipHostMallocDefault));
+        std::vector<double> tmp(2 * std::max(P, r));
+        for (int t = 0; t < r; ++t) {
+            tmp[2 * t] = (double)p->cyc.taps[t].real();
+            tmp[2 * t + 1] = (double)p->cyc.taps[t].imag();
+        }
+        HIP_TRY(hipMemcpy(p->taps_dev, tmp.data(), r * sizeof(double2), hipMemcpyHostToDevice));
+        for (int k = 0; k < P; ++k) {
+            tmp[2 * k] = (double)p->cyc.rot[k].real();
+            tmp[2 * k + 1] = (double)p->cyc.rot[k].imag();
+        }
+        HIP_TRY(hipMemcpy(p->rot_dev, tmp.data(), P * sizeof(double2), hipMemcpyHostToDevice));
+    }
+    p->prepared = true;
+    return DRACO_OK;
+}
+
+// Brackets the kernels launched in its scope with the next free event pair.
+struct Timed {
+    Timer* t;
+    hipStream_t st;
+    bool on;
+    Timed(draco_plan* plan, Kind k, hipStream_t stream) : t(&plan->timers[k]), st(stream) {
+        on = t->used < (int)t->start.size();
+        if (on) (void)hipEventRecord(t->start[t->used], st);
+    }
+    ~Timed() {
+        if (on) {
+            (void)hipEventRecord(t->stop[t->used], st);
+            ++t->used;
+        }
+    }
+};
+
+void words_from_mask(const std::vector<uint8_t>& mask, uint64_t* words, int P) {
+    for (int w = 0; w < (P + 63) / 64; ++w) words[w] = 0;
+    for (int j = 0; j < P; ++j)
+        if (mask[j]) words[j >> 6] |= 1ull << (j & 63);
+}
+
+}  // namespace
+
+extern "C" {
+
+int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d) {
+    if (out == nullptr) return DRACO_EINVAL;
+    if (code != DRACO_CODE_REPETITION && code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
+    if (P < 1 || P > DRACO_MAX_NODES || s < 0 || d < 1) return DRACO_EINVAL;
+    if (2 * (int64_t)s + 1 > P) return DRACO_EINVAL;                               // corollary to Theorem 1
+    if (code == DRACO_CODE_REPETITION && P % (2 * s + 1) != 0) return DRACO_EINVAL; // "Suppose 2s+1 divides P"
+    draco_plan* p = new (std::nothrow) draco_plan();
+    if (p == nullptr) return DRACO_ENOMEM;
+    p->code = code;
+    p->P = P;
+    p->s = s;
+    p->d = d;
+    if (code == DRACO_CODE_CYCLIC) p->cyc.build(P, s);
+    *out = p;
+    return DRACO_OK;
+}
+
+int draco_plan_prepare(draco_plan* plan) {
+    if (plan == nullptr) return DRACO_EINVAL;
+    return prepare(plan);
+}
+
+void draco_plan_destroy(draco_plan* p) {
+    if (p == nullptr) return;
+    if (p->device >= 0) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(p->taps_dev);
+        (void)hipFree(p->rot_dev);
+        (void)hipFree(p->partial_dev);
+        (void)hipFree(p->gamma_dev);
+        (void)hipFree(p->b_dev);
+        (void)hipFree(p->idx_dev);
+        (void)hipFree(p->flags_dev);
+        (void)hipFree(p->mask_dev);
+        (void)hipFree(p->status_dev);
+        (void)hipHostFree(p->gamma_pin);
+        (void)hipHostFree(p->b_pin);
+        (void)hipHostFree(p->idx_pin);
+        (void)hipHostFree(p->mask_pin);
+        for (auto& t : p->timers) {
+            for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
+            for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
+        }
+    }
+    delete p;
+}
+
+int64_t draco_message_len(const draco_plan* plan) {
+    if (plan == nullptr) return DRACO_EINVAL;
+    return message_len(plan);
+}
+
+int draco_plan_assign(const draco_plan* p, uint8_t* A) {
+    if (p == nullptr || A == nullptr) return DRACO_EINVAL;
+    const int P = p->P, r = 2 * p->s + 1;
+    std::memset(A, 0, (size_t)P * P);
+    for (int j = 0; j < P; ++j)
+        for (int t = 0; t < r; ++t) {
+            const int k = (p->code == DRACO_CODE_REPETITION) ? (j / r) * r + t : (j + t) % P;
+            A[(size_t)j * P + k] = 1;
+        }
+    return DRACO_OK;
+}
+
+int draco_plan_weights(const draco_plan* p, double* W) {
+    if (p == nullptr || W == nullptr) return DRACO_EINVAL;
+    const int P = p->P, r = 2 * p->s + 1;
+    for (int k = 0; k < P; ++k)
+        for (int j = 0; j < P; ++j) {
+            double re = 0.0, im = 0.0;
+            if (p->code == DRACO_CODE_REPETITION) {
+                re = (k / r == j / r) ? 1.0 : 0.0;
+            } else {
+                const cplx_t w = p->cyc.W(k, j);
+                re = (double)w.real();
+                im = (double)w.imag();
+            }
+            W[((size_t)k * P + j) * 2] = re;
+            W[((size_t)k * P + j) * 2 + 1] = im;
+        }
+    return DRACO_OK;
+}
+
+int draco_encode(draco_plan* p, const float* grads_dev, int64_t ld_g, float* messages_dev, int64_t ld_m,
+                 void* stream) {
+    if (p == nullptr) return DRACO_EINVAL;
+    int rc = check_slab(grads_dev, ld_g, p->d);
+    if (rc != DRACO_OK) return rc;
+    rc = check_slab(messages_dev, ld_m, message_len(p));
+    if (rc != DRACO_OK) return rc;
+    rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Timed timed(p, kEncode, st);
+    if (p->code == DRACO_CODE_REPETITION)
+        HIP_TRY(launch_encode_rep(grads_dev, ld_g, messages_dev, ld_m, p->P, p->s, p->d, st));
+    else
+        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, messages_dev, ld_m, p->taps_dev, p->rot_dev, p->P, p->s, p->d, st));
+    return DRACO_OK;
+}
+
+int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
+                      void* stream) {
+    if (p == nullptr || node < 0 || node >= p->P) return DRACO_EINVAL;
+    int rc = check_slab(node_grads_dev, ld_g, p->d);
+    if (rc != DRACO_OK) return rc;
+    if (message_dev == nullptr) return DRACO_EINVAL;
+    if (!aligned16(message_dev)) return DRACO_EALIGN;
+    rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Timed timed(p, kEncode, st);
+    if (p->code == DRACO_CODE_REPETITION)
+        HIP_TRY(launch_encode_rep_node(node_grads_dev, ld_g, message_dev, p->s, p->d, st));
+    else
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, p->taps_dev, p->rot_dev, node, p->P, p->s,
+                                       p->d, st));
+    return DRACO_OK;
+}
+
+int draco_decode_repetition_async(draco_plan* p, const float* messages_dev, int64_t ld_m, float* sum_dev,
+                                  uint64_t* mask_dev, int32_t* status_dev, void* stream) {
+    if (p == nullptr || p->code != DRACO_CODE_REPETITION) return DRACO_EINVAL;
+    if (sum_dev == nullptr || mask_dev == nullptr || status_dev == nullptr) return DRACO_EINVAL;
+    int rc = check_slab(messages_dev, ld_m, p->d);
+    if (rc != DRACO_OK) return rc;
+    if (!aligned16(sum_dev)) return DRACO_EALIGN;
+    rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        Timed timed(p, kVote, st);
+        HIP_TRY(launch_decode_rep_vote(messages_dev, ld_m, sum_dev, p->flags_dev, p->P, p->s, p->d, st));
+    }
+    HIP_TRY(launch_decode_rep_finish(p->flags_dev, mask_dev, status_dev, p->P, p->s, st));
+    return DRACO_OK;
+}
+
+int draco_decode_repetition(draco_plan* p, const float* messages_dev, int64_t ld_m, float* sum_dev,
+                            uint64_t* mask_host, void* stream) {
+    if (p == nullptr || mask_host == nullptr) return DRACO_EINVAL;
+    int rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    rc = draco_decode_repetition_async(p, messages_dev, ld_m, sum_dev, p->mask_dev, p->status_dev, stream);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int words = (p->P + 63) / 64;
+    HIP_TRY(hipMemcpyAsync(p->mask_pin, p->mask_dev, words * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(p->mask_pin + kMaskWords, p->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int w = 0; w < words; ++w) mask_host[w] = p->mask_pin[w];
+    int32_t status;
+    std::memcpy(&status, p->mask_pin + kMaskWords, sizeof(status));
+    return status;
+}
+
+int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev,
+                        uint64_t* mask_host, void* stream) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
+    if (f_dev == nullptr || sum_dev == nullptr || mask_host == nullptr) return DRACO_EINVAL;
+    int rc = check_slab(messages_dev, ld_m, message_len(p));
+    if (rc != DRACO_OK) return rc;
+    if (!aligned16(sum_dev) || (reinterpret_cast<uintptr_t>(f_dev) & 3u) != 0) return DRACO_EALIGN;
+    rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int P = p->P, s = p->s;
+    {
+        Timed timed(p, kProject, st);
+        HIP_TRY(launch_cyc_project(messages_dev, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+    }
+    HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    std::vector<std::complex<double>> gamma(P), t;
+    for (int j = 0; j < P; ++j) gamma[j] = std::complex<double>(p->gamma_pin[2 * j], p->gamma_pin[2 * j + 1]);
+    std::vector<uint8_t> mask;
+    const bool located = cyclic_locate(P, s, gamma.data(), mask, t);
+    words_from_mask(mask, mask_host, P);
+    std::vector<cplx_t> b;
+    if (!cyclic_recombination_vector(P, s, mask, b)) return DRACO_LOCATE_FAILED;
+    int nu = 0;
+    for (int j = 0; j < P; ++j) {
+        if (mask[j]) continue;
+        p->idx_pin[nu] = j;
+        p->b_pin[2 * nu] = (double)b[j].real();
+        p->b_pin[2 * nu + 1] = (double)b[j].imag();
+        ++nu;
+    }
+    HIP_TRY(hipMemcpyAsync(p->b_dev, p->b_pin, nu * sizeof(double2), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, nu * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    {
+        Timed timed(p, kRecombine, st);
+        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, nu, sum_dev, p->d, st));
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    return located ? DRACO_OK : DRACO_LOCATE_FAILED;
+}
+
+int draco_cyclic_locate(const draco_plan* p, const double* gamma_host, uint64_t* mask_host, double* t_host) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC || gamma_host == nullptr || mask_host == nullptr)
+        return DRACO_EINVAL;
+    const int P = p->P;
+    std::vector<std::complex<double>> gamma(P), t;
+    for (int j = 0; j < P; ++j) gamma[j] = std::complex<double>(gamma_host[2 * j], gamma_host[2 * j + 1]);
+    std::vector<uint8_t> mask;
+    const bool ok = cyclic_locate(P, p->s, gamma.data(), mask, t);
+    words_from_mask(mask, mask_host, P);
+    if (t_host != nullptr)
+        for (int j = 0; j < P; ++j) {
+            t_host[2 * j] = t[j].real();
+            t_host[2 * j + 1] = t[j].imag();
+        }
+    return ok ? DRACO_OK : DRACO_LOCATE_FAILED;
+}
+
+int draco_cyclic_recombination_vector(const draco_plan* p, const uint64_t* mask_host, double* b_host) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC || mask_host == nullptr || b_host == nullptr)
+        return DRACO_EINVAL;
+    const int P = p->P;
+    std::vector<uint8_t> mask(P);
+    for (int j = 0; j < P; ++j) mask[j] = (uint8_t)((mask_host[j >> 6] >> (j & 63)) & 1ull);
+    std::vector<cplx_t> b;
+    if (!cyclic_recombination_vector(P, p->s, mask, b)) return DRACO_EINVAL;
+    for (int j = 0; j < P; ++j) {
+        b_host[2 * j] = (double)b[j].real();
+        b_host[2 * j + 1] = (double)b[j].imag();
+    }
+    return DRACO_OK;
+}
+
+const char* draco_strerror(int status) {
+    switch (status) {
+        case DRACO_OK: return "ok";
+        case DRACO_NO_MAJORITY: return "repetition code: a group has more than s nodes that differ from its vote";
+        case DRACO_LOCATE_FAILED: return "cyclic code: no set of at most s nodes accounts for the syndromes";
+        case DRACO_EINVAL: return "invalid argument";
+        case DRACO_EALIGN: return "pointer not 16-byte aligned or stride not a multiple of 4 floats / too short";
+        case DRACO_EHIP: return "HIP runtime error";
+        case DRACO_ENOMEM: return "out of host memory";
+        default: return "unknown status";
+    }
+}
+
+int draco_plan_set_timing(draco_plan* p, int max_records) {
+    if (p == nullptr || max_records < 0 || max_records > 65536) return DRACO_EINVAL;
+    int rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    for (auto& t : p->timers) {
+        while ((int)t.start.size() > max_records) {
+            (void)hipEventDestroy(t.start.back());
+            (void)hipEventDestroy(t.stop.back());
+            t.start.pop_back();
+            t.stop.pop_back();
+        }
+        while ((int)t.start.size() < max_records) {
+            hipEvent_t a = nullptr, b = nullptr;
+            HIP_TRY(hipEventCreate(&a));
+            if (hipEventCreate(&b) != hipSuccess) {
+                (void)hipEventDestroy(a);
+                return DRACO_EHIP;
+            }
+            t.start.push_back(a);
+            t.stop.push_back(b);
+        }
+        t.used = 0;
+    }
+    return DRACO_OK;
+}
+
+int draco_plan_kernel_time(draco_plan* p, int kind, double* total_ms, int* launches) {
+    if (p == nullptr || kind < 0 || kind >= kKinds || total_ms == nullptr || launches == nullptr) return DRACO_EINVAL;
+    Timer& t = p->timers[kind];
+    double sum = 0.0;
+    for (int i = 0; i < t.used; ++i) {
+        HIP_TRY(hipEventSynchronize(t.stop[i]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+        sum += (double)ms;
+    }
+    *total_ms = sum;
+    *launches = t.used;
+    t.used = 0;
+    return DRACO_OK;
+}
+
+}  // extern "C"

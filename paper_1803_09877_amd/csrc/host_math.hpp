@@ -1,0 +1,47 @@
+// Host-side algebra of the cyclic code (Sec. 3, "Cyclic Code"): the encoding
+// matrix W, the locator phi's small linear algebra and the recombination
+// vector b.  Everything here is O(P s + s^3) work on P <= 256 numbers and runs
+// in extended precision (x87 long double, 64-bit mantissa) because W and b
+// cancel over four to five decimal orders at P = 45.
+#pragma once
+
+#include <complex>
+#include <cstdint>
+#include <vector>
+
+namespace draco {
+
+using real_t = long double;
+using cplx_t = std::complex<real_t>;
+
+// exp(2 pi i k / P), argument reduced first.
+cplx_t root_of_unity(int P, long long k);
+
+struct CyclicCode {
+    int P = 0, s = 0;
+    // Z = G W with W[k][k-t] = rot[k] * taps[t], t = 0..2s (all other entries 0):
+    // node j's message is sum_t taps[t] * (rot[j+t] * g_{j+t}).
+    std::vector<cplx_t> taps;  // 2s+1
+    std::vector<cplx_t> rot;   // P, unimodular
+    void build(int P_, int s_);
+    cplx_t W(int k, int j) const;  // weight of gradient k in node j's message
+};
+
+// Relative size below which a syndrome counts as zero (in units of the median
+// |projection|): 32 ulps of the fp32 wire.
+constexpr double kTauH = 32.0 / 16777216.0;
+
+// phi steps 2-4 on the projections gamma (length P).  mask[j] = 1 for located
+// nodes; t (length P) receives the reconstructed error projections.  Returns
+// true on success, false when no set of at most s nodes accounts for the
+// syndromes (mask then holds the s largest |t_j|) or gamma is not finite
+// (mask empty).
+bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
+                   std::vector<std::complex<double>>& t);
+
+// Minimum-norm b with C_L[:, U] b_U = e_last, U = {j : mask[j] == 0}; needs
+// |V| <= 2s.  b[j] = 0 on masked nodes.  Returns false if |V| > 2s.
+bool cyclic_recombination_vector(int P, int s, const std::vector<uint8_t>& mask,
+                                 std::vector<cplx_t>& b);
+
+}  // namespace draco

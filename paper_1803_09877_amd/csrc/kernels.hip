@@ -1,0 +1,628 @@
+// gfx950 kernels of the DRACO encode/decode path.
+//
+// Every kernel here is a streaming pass over [node][coordinate] fp32 slabs and
+// is bound by HBM bandwidth: one lane owns 4 consecutive floats (one 16-byte
+// load per row), a wavefront therefore reads 1 KiB of each row per step, and
+// the loop over the P rows runs inside the lane so each input byte is read
+// from HBM exactly once.  Workgroups are 256 lanes (4 wavefronts).  There is
+// no reuse between workgroups, so the blockIdx -> tile map is the identity.
+#include "kernels.hpp"
+
+namespace draco {
+
+namespace {
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+
+// Guarded load of up to 4 floats; missing ones read as 0.
+__device__ __forceinline__ float4 ld4_partial(const float* p, int n) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n > 0) v.x = p[0];
+    if (n > 1) v.y = p[1];
+    if (n > 2) v.z = p[2];
+    if (n > 3) v.w = p[3];
+    return v;
+}
+__device__ __forceinline__ void st4_partial(float* p, float4 v, int n) {
+    if (n > 0) p[0] = v.x;
+    if (n > 1) p[1] = v.y;
+    if (n > 2) p[2] = v.z;
+    if (n > 3) p[3] = v.w;
+}
+
+__device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ? 0 : (int)n); }
+
+}  // namespace
+
+// ===========================================================================
+// Repetition code
+// ===========================================================================
+
+// E^Rep for all nodes: one pass reads each gradient once, forms each group's
+// sum in ascending gradient order and stores it r times.
+template <int R>
+__global__ __launch_bounds__(kBlock) void encode_rep_kernel(const float* __restrict__ G, int64_t ldg,
+                                                            float* __restrict__ Z, int64_t ldm,
+                                                            int groups, int64_t d) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 >= d) return;
+    const int n = clamp4(d - c0);
+    for (int g = 0; g < groups; ++g) {
+        const float* src = G + (int64_t)g * R * ldg + c0;
+        float4 x[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) x[i] = (n == 4) ? ld4(src + (int64_t)i * ldg) : ld4_partial(src + (int64_t)i * ldg, n);
+        float4 acc = x[0];
+#pragma unroll
+        for (int i = 1; i < R; ++i) {
+            acc.x += x[i].x;
+            acc.y += x[i].y;
+            acc.z += x[i].z;
+            acc.w += x[i].w;
+        }
+        float* dst = Z + (int64_t)g * R * ldm + c0;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (n == 4) st4(dst + (int64_t)i * ldm, acc);
+            else st4_partial(dst + (int64_t)i * ldm, acc, n);
+        }
+    }
+}
+
+// Any r (also the one-node form with groups = 1, copies = 1).
+__global__ __launch_bounds__(kBlock) void encode_rep_generic_kernel(const float* __restrict__ G, int64_t ldg,
+                                                                    float* __restrict__ Z, int64_t ldm,
+                                                                    int groups, int r, int copies, int64_t d) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 >= d) return;
+    const int n = clamp4(d - c0);
+    for (int g = 0; g < groups; ++g) {
+        const float* src = G + (int64_t)g * r * ldg + c0;
+        float4 acc = (n == 4) ? ld4(src) : ld4_partial(src, n);
+        for (int i = 1; i < r; ++i) {
+            const float4 x = (n == 4) ? ld4(src + (int64_t)i * ldg) : ld4_partial(src + (int64_t)i * ldg, n);
+            acc.x += x.x;
+            acc.y += x.y;
+            acc.z += x.z;
+            acc.w += x.w;
+        }
+        float* dst = Z + (int64_t)g * r * ldm + c0;
+        for (int i = 0; i < copies; ++i) {
+            if (n == 4) st4(dst + (int64_t)i * ldm, acc);
+            else st4_partial(dst + (int64_t)i * ldm, acc, n);
+        }
+    }
+}
+
+// Streaming majority vote (Algorithm 2) on the bit patterns of one coordinate.
+template <int R>
+__device__ __forceinline__ uint32_t vote(const uint32_t (&v)[R]) {
+    uint32_t ma = v[0];
+    int counter = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        if (counter == 0) {
+            ma = v[i];
+            counter = 1;
+        } else if (v[i] == ma) {
+            ++counter;
+        } else {
+            --counter;
+        }
+    }
+    return ma;
+}
+
+// OR the wavefront-uniform flag words of the four wavefronts of a workgroup
+// into the global flag words, touching global memory only for bits that are
+// not set there yet.
+__device__ __forceinline__ void publish_flags(const uint64_t (&wflags)[kMaskWords], uint64_t* __restrict__ flags) {
+    __shared__ unsigned long long sflags[kMaskWords];
+    if (threadIdx.x < kMaskWords) sflags[threadIdx.x] = 0ull;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int w = 0; w < kMaskWords; ++w)
+            if (wflags[w]) atomicOr(&sflags[w], (unsigned long long)wflags[w]);
+    }
+    __syncthreads();
+    if (threadIdx.x < kMaskWords) {
+        const unsigned long long mine = sflags[threadIdx.x];
+        if (mine) {
+            unsigned long long* dst = reinterpret_cast<unsigned long long*>(flags) + threadIdx.x;
+            const unsigned long long cur = __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (mine & ~cur) atomicOr(dst, mine);
+        }
+    }
+}
+
+// D^Rep: per coordinate and group, the vote over the r copies; winners are
+// summed over groups in ascending order; a node is flagged when any of its
+// coordinates differs from the winner.  Honest groups take the fast path (all
+// copies equal, decided for the whole wavefront by one ballot).
+template <int R>
+__global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restrict__ Rm, int64_t ldm,
+                                                            float* __restrict__ u, uint64_t* __restrict__ flags,
+                                                            int groups, int64_t d) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    uint64_t wflags[kMaskWords] = {0, 0, 0, 0};
+    const bool active = c0 < d;
+    const int n = active ? clamp4(d - c0) : 0;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int g = 0; g < groups; ++g) {
+        uint4 x[R];
+        if (active) {
+            const float* src = Rm + (int64_t)g * R * ldm + c0;
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const float4 t = (n == 4) ? ld4(src + (int64_t)i * ldm) : ld4_partial(src + (int64_t)i * ldm, n);
+                x[i] = make_uint4(__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < R; ++i) x[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        uint32_t differ = 0;
+#pragma unroll
+        for (int i = 1; i < R; ++i)
+            differ |= (x[i].x ^ x[0].x) | (x[i].y ^ x[0].y) | (x[i].z ^ x[0].z) | (x[i].w ^ x[0].w);
+        uint4 win = x[0];
+        if (__ballot(differ != 0) != 0ull) {   // wavefront-uniform: some lane saw a disagreement in this group
+            uint32_t bad = 0;                  // bit i: copy i differs from the vote in one of my coordinates
+            if (differ != 0) {
+                uint32_t v[R];
+#pragma unroll
+                for (int i = 0; i < R; ++i) v[i] = x[i].x;
+                win.x = vote<R>(v);
+#pragma unroll
+                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.x) << i;
+#pragma unroll
+                for (int i = 0; i < R; ++i) v[i] = x[i].y;
+                win.y = vote<R>(v);
+#pragma unroll
+                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.y) << i;
+#pragma unroll
+                for (int i = 0; i < R; ++i) v[i] = x[i].z;
+                win.z = vote<R>(v);
+#pragma unroll
+                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.z) << i;
+#pragma unroll
+                for (int i = 0; i < R; ++i) v[i] = x[i].w;
+                win.w = vote<R>(v);
+#pragma unroll
+                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.w) << i;
+            }
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                if (__ballot((bad >> i) & 1u) != 0ull) {
+                    const int node = g * R + i;
+#pragma unroll
+                    for (int w = 0; w < kMaskWords; ++w)
+                        if (w == (node >> 6)) wflags[w] |= 1ull << (node & 63);
+                }
+            }
+        }
+        acc.x += __uint_as_float(win.x);
+        acc.y += __uint_as_float(win.y);
+        acc.z += __uint_as_float(win.z);
+        acc.w += __uint_as_float(win.w);
+    }
+    if (active) {
+        if (n == 4) st4(u + c0, acc);
+        else st4_partial(u + c0, acc, n);
+    }
+    publish_flags(wflags, flags);
+}
+
+// Any r: one coordinate per lane, copies re-read from cache for the count.
+__global__ __launch_bounds__(kBlock) void decode_rep_generic_kernel(const float* __restrict__ Rm, int64_t ldm,
+                                                                    float* __restrict__ u, uint64_t* __restrict__ flags,
+                                                                    int groups, int r, int64_t d) {
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    uint64_t wflags[kMaskWords] = {0, 0, 0, 0};
+    const bool active = c < d;
+    float acc = 0.f;
+    for (int g = 0; g < groups; ++g) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(Rm) + (int64_t)g * r * ldm + c;
+        uint32_t ma = 0;
+        int counter = 0;
+        if (active) {
+            for (int i = 0; i < r; ++i) {
+                const uint32_t v = src[(int64_t)i * ldm];
+                if (counter == 0) {
+                    ma = v;
+                    counter = 1;
+                } else if (v == ma) {
+                    ++counter;
+                } else {
+                    --counter;
+                }
+            }
+        }
+        for (int i = 0; i < r; ++i) {
+            const bool bad = active && src[(int64_t)i * ldm] != ma;
+            if (__ballot(bad) != 0ull) {
+                const int node = g * r + i;
+#pragma unroll
+                for (int w = 0; w < kMaskWords; ++w)
+                    if (w == (node >> 6)) wflags[w] |= 1ull << (node & 63);
+            }
+        }
+        acc += __uint_as_float(ma);
+    }
+    if (active) u[c] = acc;
+    publish_flags(wflags, flags);
+}
+
+__global__ void decode_rep_finish_kernel(uint64_t* __restrict__ flags, uint64_t* __restrict__ mask_out,
+                                         int32_t* __restrict__ status_out, int P, int s) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int r = 2 * s + 1;
+    int status = 0;
+    for (int g = 0; g < P / r; ++g) {
+        int cnt = 0;
+        for (int i = 0; i < r; ++i) {
+            const int node = g * r + i;
+            cnt += (int)((flags[node >> 6] >> (node & 63)) & 1ull);
+        }
+        if (cnt > s) status = 1;  // DRACO_NO_MAJORITY
+    }
+    for (int w = 0; w < (P + 63) / 64; ++w) mask_out[w] = flags[w];
+    for (int w = 0; w < kMaskWords; ++w) flags[w] = 0;
+    *status_out = status;
+}
+
+// ===========================================================================
+// Cyclic code
+// ===========================================================================
+
+// (cr + i ci) * (x + i y), the same instruction sequence wherever it is used.
+__device__ __forceinline__ void cmul(double cr, double ci, double x, double y, double& re, double& im) {
+    re = fma(cr, x, -(ci * y));
+    im = fma(cr, y, ci * x);
+}
+// acc += (tr + i ti) * (x + i y)
+__device__ __forceinline__ void cmac(double tr, double ti, double x, double y, double& are, double& aim) {
+    are = fma(tr, x, are);
+    are = fma(-ti, y, are);
+    aim = fma(tr, y, aim);
+    aim = fma(ti, x, aim);
+}
+
+// E^Cyc for all nodes.  Because W[k][k-t] = rot[k]*taps[t], node n's message is
+// a (2s+1)-tap complex FIR filter over the rotated gradients g'_k = rot[k] g_k
+// taken cyclically: z_n = sum_t taps[t] * g'_{n+t}.  A lane keeps the window
+// g'_n .. g'_{n+2s} of its two complex coordinates in registers (fp64) and
+// slides it down the P rows; rows 0..2s-1, needed again by the last 2s nodes,
+// are parked in LDS (each lane reads back only what it wrote: no barrier).
+template <int S>
+__global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
+                                                            float* __restrict__ Z, int64_t ldm,
+                                                            const double2* __restrict__ taps,
+                                                            const double2* __restrict__ rot, int P, int64_t d) {
+    constexpr int R = 2 * S + 1;
+    extern __shared__ float4 head[];  // [2S][kBlock]
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (c0 >= mlen) return;
+    const int nin = clamp4(d - c0);      // gradient floats that exist (the pad of an odd d reads as 0)
+    const int nout = clamp4(mlen - c0);  // message floats to write
+
+    double tr[R], ti[R];
+#pragma unroll
+    for (int t = 0; t < R; ++t) {
+        tr[t] = taps[t].x;
+        ti[t] = taps[t].y;
+    }
+    double wre[R][2], wim[R][2];  // window slot = row index mod R
+
+    auto load_row = [&](int k) -> float4 {
+        const float* p = G + (int64_t)k * ldg + c0;
+        return (nin == 4) ? ld4(p) : ld4_partial(p, nin);
+    };
+    auto put = [&](int slot, int k, const float4& raw) {
+        const double cr = rot[k].x, ci = rot[k].y;
+        cmul(cr, ci, (double)raw.x, (double)raw.y, wre[slot][0], wim[slot][0]);
+        cmul(cr, ci, (double)raw.z, (double)raw.w, wre[slot][1], wim[slot][1]);
+    };
+
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const float4 raw = load_row(k);
+        head[k * kBlock + threadIdx.x] = raw;
+        put(k, k, raw);
+    }
+    for (int n0 = 0; n0 < P; n0 += R) {
+        float4 raw[R];
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {  // issue the loads of this round together
+            const int kk = n0 + uu + 2 * S;
+            if (n0 + uu < P) {
+                if (kk < P) raw[uu] = load_row(kk);
+                else raw[uu] = head[(kk - P) * kBlock + threadIdx.x];
+            }
+        }
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                const int kk = n + 2 * S;
+                put((uu + 2 * S) % R, kk < P ? kk : kk - P, raw[uu]);
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    cmac(tr[t], ti[t], wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(tr[t], ti[t], wre[slot][1], wim[slot][1], are1, aim1);
+                }
+                const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                float* dst = Z + (int64_t)n * ldm + c0;
+                if (nout == 4) st4(dst, out);
+                else st4_partial(dst, out, nout);
+            }
+        }
+    }
+}
+
+// One node (also the path for s > kMaxS in the all-node form, called per
+// node): z = sum_t taps[t] * (rot[k_t] * g_t), rows of Gn at k_t = row_of[t].
+__global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
+                                                                 float* __restrict__ z,
+                                                                 const double2* __restrict__ taps,
+                                                                 const double2* __restrict__ rot, int node, int P,
+                                                                 int r, int wrap_rows, int64_t d) {
+    // wrap_rows == 0: Gn holds only this node's r gradients in assignment order.
+    // wrap_rows == P: Gn is the full [P][ldg] slab and row (node+t) mod P is used.
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (c0 >= mlen) return;
+    const int nin = clamp4(d - c0);
+    const int nout = clamp4(mlen - c0);
+    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+    for (int t = 0; t < r; ++t) {
+        int k = node + t;
+        if (k >= P) k -= P;
+        const float* p = Gn + (int64_t)(wrap_rows ? k : t) * ldg + c0;
+        const float4 raw = (nin == 4) ? ld4(p) : ld4_partial(p, nin);
+        double xr0, xi0, xr1, xi1;
+        cmul(rot[k].x, rot[k].y, (double)raw.x, (double)raw.y, xr0, xi0);
+        cmul(rot[k].x, rot[k].y, (double)raw.z, (double)raw.w, xr1, xi1);
+        cmac(taps[t].x, taps[t].y, xr0, xi0, are0, aim0);
+        cmac(taps[t].x, taps[t].y, xr1, xi1, are1, aim1);
+    }
+    const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+    if (nout == 4) st4(z + c0, out);
+    else st4_partial(z + c0, out, nout);
+}
+
+// phi step 1: gamma'_j = sum_i f_i * r_j[i].  A workgroup owns a tile of
+// kBlock*kProjectLoads float4 (two complex numbers each) of every row, keeps
+// its slice of f in registers, and for each row forms a per-wavefront sum in
+// fp64; the four wavefront sums are added in fixed order and stored per tile.
+__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm, int64_t ldm,
+                                                             const float* __restrict__ f,
+                                                             double2* __restrict__ partial, int P, int64_t d) {
+    constexpr int K = kProjectLoads;
+    __shared__ double2 wsum[kBlock / 64][kMaxNodes];
+    const int64_t h = (d + 1) / 2;                                   // complex numbers per row
+    const int64_t q0 = (int64_t)blockIdx.x * (kBlock * K) + threadIdx.x;  // my first float4
+    const bool tile_full = ((int64_t)(blockIdx.x + 1) * (kBlock * K)) * 2 <= h;
+    double f0[K], f1[K];
+    int nflt[K];  // message floats that exist in my k-th float4 (4, 2 or 0)
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t q = q0 + (int64_t)k * kBlock;
+        const int64_t c = 2 * q;  // first complex index
+        f0[k] = (c < h) ? (double)f[c] : 0.0;
+        f1[k] = (c + 1 < h) ? (double)f[c + 1] : 0.0;
+        nflt[k] = (c + 1 < h) ? 4 : (c < h ? 2 : 0);
+    }
+    const int wave = threadIdx.x >> 6;
+    for (int j = 0; j < P; ++j) {
+        const float* row = Rm + (int64_t)j * ldm + q0 * 4;
+        float4 x[K];
+        if (tile_full) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) x[k] = ld4(row + (int64_t)k * kBlock * 4);
+        } else {
+#pragma unroll
+            for (int k = 0; k < K; ++k) x[k] = ld4_partial(row + (int64_t)k * kBlock * 4, nflt[k]);
+        }
+        double are = 0.0, aim = 0.0;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            are = fma(f0[k], (double)x[k].x, are);
+            aim = fma(f0[k], (double)x[k].y, aim);
+            are = fma(f1[k], (double)x[k].z, are);
+            aim = fma(f1[k], (double)x[k].w, aim);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            are += __shfl_xor(are, off);
+            aim += __shfl_xor(aim, off);
+        }
+        if ((threadIdx.x & 63) == 0) wsum[wave][j] = make_double2(are, aim);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < P) {
+        double2 a = wsum[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            a.x += wsum[w][threadIdx.x].x;
+            a.y += wsum[w][threadIdx.x].y;
+        }
+        partial[(int64_t)blockIdx.x * P + threadIdx.x] = a;
+    }
+}
+
+// gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
+__global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double2* __restrict__ partial,
+                                                                    double2* __restrict__ gamma, int P,
+                                                                    int64_t tiles) {
+    __shared__ double2 sm[kBlock];
+    const int j = blockIdx.x;
+    double2 a = make_double2(0.0, 0.0);
+    for (int64_t t = threadIdx.x; t < tiles; t += kBlock) {
+        const double2 p = partial[t * P + j];
+        a.x += p.x;
+        a.y += p.y;
+    }
+    sm[threadIdx.x] = a;
+    __syncthreads();
+    for (int off = kBlock / 2; off >= 1; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            sm[threadIdx.x].x += sm[threadIdx.x + off].x;
+            sm[threadIdx.x].y += sm[threadIdx.x + off].y;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) gamma[j] = sm[0];
+}
+
+// u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
+// ascending node order, fp64 accumulation, one rounding to fp32.
+__global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm, int64_t ldm,
+                                                               const double2* __restrict__ b,
+                                                               const int32_t* __restrict__ idx, int nu,
+                                                               float* __restrict__ u, int64_t d) {
+    constexpr int UN = 8;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 >= d) return;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const int nin = clamp4(mlen - c0);
+    const int nout = clamp4(d - c0);
+    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+    for (int q0 = 0; q0 < nu; q0 += UN) {
+        float4 x[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            if (q0 + i < nu) {
+                const float* p = Rm + (int64_t)idx[q0 + i] * ldm + c0;
+                x[i] = (nin == 4) ? ld4(p) : ld4_partial(p, nin);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            if (q0 + i < nu) {
+                const double br = b[q0 + i].x, bi = b[q0 + i].y;
+                cmac(br, bi, (double)x[i].x, (double)x[i].y, are0, aim0);
+                cmac(br, bi, (double)x[i].z, (double)x[i].w, are1, aim1);
+            }
+        }
+    }
+    const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+    if (nout == 4) st4(u + c0, out);
+    else st4_partial(u + c0, out, nout);
+}
+
+// ===========================================================================
+// Launchers
+// ===========================================================================
+
+static inline unsigned grid_for(int64_t units_of_4_floats) {
+    return (unsigned)((units_of_4_floats + kBlock - 1) / kBlock);
+}
+
+hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm, int P, int s, int64_t d,
+                             hipStream_t stream) {
+    const int r = 2 * s + 1, groups = P / r;
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+#define DRACO_CASE(S)                                                                                       \
+    case S:                                                                                                 \
+        hipLaunchKernelGGL((encode_rep_kernel<2 * S + 1>), grid, block, 0, stream, G, ldg, Z, ldm, groups, d); \
+        break;
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default:
+            hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, G, ldg, Z, ldm, groups, r, r, d);
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_rep_node(const float* Gn, int64_t ldg, float* z, int s, int64_t d, hipStream_t stream) {
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, Gn, ldg, z, (int64_t)0, 1, 2 * s + 1, 1, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_t* flags, int P, int s, int64_t d,
+                                  hipStream_t stream) {
+    const int r = 2 * s + 1, groups = P / r;
+    const dim3 block(kBlock);
+    const dim3 grid(grid_for((d + 3) / 4));
+#define DRACO_CASE(S)                                                                                        \
+    case S:                                                                                                  \
+        hipLaunchKernelGGL((decode_rep_kernel<2 * S + 1>), grid, block, 0, stream, R, ldm, u, flags, groups, d); \
+        break;
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default: {
+            const dim3 g1((unsigned)((d + kBlock - 1) / kBlock));
+            hipLaunchKernelGGL(decode_rep_generic_kernel, g1, block, 0, stream, R, ldm, u, flags, groups, r, d);
+        }
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t* status_out, int P, int s,
+                                    hipStream_t stream) {
+    hipLaunchKernelGGL(decode_rep_finish_kernel, dim3(1), dim3(64), 0, stream, flags, mask_out, status_out, P, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* taps,
+                             const double2* rot, int P, int s, int64_t d, hipStream_t stream) {
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const size_t lds = (size_t)2 * s * kBlock * sizeof(float4);
+#define DRACO_CASE(S)                                                                                            \
+    case S:                                                                                                      \
+        hipLaunchKernelGGL((encode_cyc_kernel<S>), grid, block, lds, stream, G, ldg, Z, ldm, taps, rot, P, d);   \
+        break;
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default:
+            for (int j = 0; j < P; ++j)
+                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm, taps,
+                                   rot, j, P, 2 * s + 1, P, d);
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* taps, const double2* rot,
+                                  int node, int P, int s, int64_t d, hipStream_t stream) {
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, taps, rot, node, P, 2 * s + 1, 0, d);
+    return hipGetLastError();
+}
+
+int64_t project_tiles(int64_t d) {
+    const int64_t h = (d + 1) / 2;
+    const int64_t nvec = (h + 1) / 2;
+    const int64_t per = (int64_t)kBlock * kProjectLoads;
+    return (nvec + per - 1) / per;
+}
+
+hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, double2* partial, double2* gamma, int P,
+                              int64_t d, hipStream_t stream) {
+    const int64_t tiles = project_tiles(d);
+    hipLaunchKernelGGL(cyc_project_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, ldm, f, partial, P, d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx, int nu, float* u,
+                                int64_t d, hipStream_t stream) {
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    hipLaunchKernelGGL(cyc_recombine_kernel, grid, block, 0, stream, R, ldm, b, idx, nu, u, d);
+    return hipGetLastError();
+}
+
+}  // namespace draco

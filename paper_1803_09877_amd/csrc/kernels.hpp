@@ -1,0 +1,49 @@
+// Launchers of the gfx950 kernels behind the C ABI.  All pointers are device
+// pointers; every launcher only enqueues work on `stream` and returns the HIP
+// error of the launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace draco {
+
+constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts of 64)
+constexpr int kMaxS = 7;              // kernels are specialised for r = 2s+1 <= 15; larger r takes the generic path
+constexpr int kProjectLoads = 8;      // float4 loads per lane per message row in the projection kernel
+constexpr int kMaxNodes = 256;        // DRACO_MAX_NODES
+constexpr int kMaskWords = 4;         // 64-bit words of node flags (kMaxNodes / 64)
+
+// Complex numbers in device tables: (re, im) as double2.
+
+// ---- repetition code ----
+hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm, int P, int s,
+                             int64_t d, hipStream_t stream);
+hipError_t launch_encode_rep_node(const float* Gn, int64_t ldg, float* z, int s, int64_t d,
+                                  hipStream_t stream);
+// ORs node flags into flags[kMaskWords] (must be zero on entry).
+hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_t* flags, int P,
+                                  int s, int64_t d, hipStream_t stream);
+// mask_out <- flags; status_out <- NO_MAJORITY if a group has more than s flags; flags <- 0.
+hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t* status_out,
+                                    int P, int s, hipStream_t stream);
+
+// ---- cyclic code ----
+// taps[2s+1], rot[P]: see CyclicCode.
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* taps,
+                             const double2* rot, int P, int s, int64_t d, hipStream_t stream);
+// Gn holds only the node's 2s+1 gradients, in assignment order.
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* taps,
+                                  const double2* rot, int node, int P, int s, int64_t d,
+                                  hipStream_t stream);
+// Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
+int64_t project_tiles(int64_t d);
+// partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
+hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, double2* partial,
+                              double2* gamma, int P, int64_t d, hipStream_t stream);
+// u <- unpack( sum_{q < nu} b[q] * R[idx[q]] ).
+hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx,
+                                int nu, float* u, int64_t d, hipStream_t stream);
+
+}  // namespace draco

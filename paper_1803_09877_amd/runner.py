@@ -1,0 +1,70 @@
+"""Device-side harness around the library for one workload: allocates the
+slabs, fills them from the seeded generators, and calls the C-ABI entry points
+through the binding.  Used by the GPU tests, the smoke check and the benchmark.
+It holds no arithmetic of the method."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+from . import synth
+
+
+class Case:
+    """Slabs of one workload resident in HBM.
+
+    G  [P][ld_g]  per-sample (unit) gradients
+    Z  [P][ld_m]  messages as the encoder wrote them
+    R  [P][ld_m]  messages as received: Z with the adversaries' edits
+    u  [d_pad]    decoded sum
+    f  [ceil(d/2)] phi's random projection vector (cyclic code)
+    """
+
+    def __init__(self, w: synth.Workload, device: str = "cuda:0"):
+        self.w = w
+        self.device = torch.device(device)
+        code = B.CODE_REPETITION if w.code == "rep" else B.CODE_CYCLIC
+        self.plan = B.Plan(code, w.P, w.s, w.d)
+        self.mlen = self.plan.message_len
+        self.ld_g = synth.padded_len(w.d)
+        self.ld_m = synth.padded_len(self.mlen)
+        self.G = synth.make_gradients(w.P, w.d, w.sigma, w.seed, device=self.device, ld=self.ld_g)
+        self.Z = torch.zeros((w.P, self.ld_m), dtype=torch.float32, device=self.device)
+        self.R = None
+        self.u = torch.zeros(synth.padded_len(w.d), dtype=torch.float32, device=self.device)
+        self.f = None
+        if w.code == "cyc":
+            self.f = synth.make_projection((w.d + 1) // 2, w.seed, device=self.device)
+        self.adversaries = w.adversaries()
+        self.plan.prepare()
+
+    def encode(self, stream=None) -> None:
+        self.plan.encode(self.G, self.Z, stream)
+
+    def receive(self) -> None:
+        """R <- Z, then the adversaries rewrite their rows (outside the hot path)."""
+        self.R = self.Z.clone()
+        synth.apply_attacks(self.R, self.mlen, self.adversaries, self.w.seed)
+
+    def decode(self, stream=None):
+        """-> (mask bool[P], status); the sum lands in self.u[:d]."""
+        if self.w.code == "rep":
+            return self.plan.decode_repetition(self.R, self.u, stream)
+        return self.plan.decode_cyclic(self.R, self.f, self.u, stream)
+
+    def step(self):
+        """One pass of the whole hot path: encode all nodes, decode what was received."""
+        self.encode()
+        if self.w.decode:
+            return self.decode()
+        return None
+
+    def expected_mask(self):
+        import numpy as np
+        m = np.zeros(self.w.P, dtype=bool)
+        for j, _ in self.adversaries:
+            m[j] = True
+        return m
+
+    def close(self) -> None:
+        self.plan.close()

@@ -1,0 +1,259 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs, element by element.
+
+Bars (from the benchmark contract): adversary masks and statuses bit-exact;
+decoded sums within relative L2 1e-5 (repetition) / 1e-4 (cyclic) of the fp64
+oracle on the SAME received messages; encoded messages within relative L2 1e-6
+per node of the oracle's fp64 messages (the wire is fp32: one rounding is
+6e-8); repetition copies bit-identical within a group."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import draco_oracle as o
+from paper_1803_09877_amd import binding as B
+from paper_1803_09877_amd import synth
+from paper_1803_09877_amd.runner import Case
+
+pytestmark = pytest.mark.gpu
+
+TOL_MSG = 1e-6
+TOL_SUM = {"rep": 1e-5, "cyc": 1e-4}
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / (nb if nb > 0 else 1.0))
+
+
+def wl(code, P, s, d, attacks=(), placement="any", sigma=1.0, seed=0):
+    return synth.Workload(name=f"{code}_{P}_{s}_{d}", code=code, P=P, s=s, d=d, sigma=sigma,
+                          attacks=tuple(attacks), placement=placement, seed=synth.SEED_BASE + 1000 + seed)
+
+
+def oracle_encode(c: Case):
+    G = c.G[:, :c.w.d].cpu().numpy()
+    if c.w.code == "rep":
+        return o.encode_repetition(G, c.w.s)
+    return o.encode_cyclic(G, c.w.s)
+
+
+def oracle_decode(c: Case, R_host):
+    if c.w.code == "rep":
+        return o.decode_repetition(R_host, c.w.s)
+    return o.decode_cyclic(R_host, c.f.cpu().numpy(), c.w.s, c.w.d)
+
+
+def run_and_check(w, extra_edit=None, expect_status=0, check_true_sum=None):
+    print(f"case {w.name} P={w.P} s={w.s} d={w.d} attacks={w.attacks} seed={w.seed}", flush=True)
+    c = Case(w)
+    try:
+        c.Z.fill_(float("nan"))                      # anything the encoder fails to write shows up
+        c.encode()
+        torch.cuda.synchronize()
+        Zg = c.Z[:, :c.mlen].cpu().numpy()
+        Zo = oracle_encode(c)
+        assert Zg.shape == Zo.shape
+        for j in range(w.P):
+            assert rel_l2(Zg[j], Zo[j]) <= TOL_MSG, f"message {j}"
+        if c.ld_m > c.mlen:                           # padding untouched
+            assert torch.isnan(c.Z[:, c.mlen:]).all()
+        if w.code == "rep":
+            r = w.r
+            for j in range(w.P):
+                assert np.array_equal(Zg[j].view(np.uint32), Zg[(j // r) * r].view(np.uint32))
+        c.receive()
+        if extra_edit is not None:
+            extra_edit(c)
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        R_host = c.R[:, :c.mlen].cpu().numpy()
+        uo, mo, so = oracle_decode(c, R_host)
+        assert status == so == expect_status
+        assert np.array_equal(mask, mo)
+        if expect_status == 0:
+            if extra_edit is None:
+                assert np.array_equal(mask, c.expected_mask())
+            ug = c.u[:w.d].cpu().numpy()
+            assert np.isfinite(ug).all()
+            assert rel_l2(ug, uo) <= TOL_SUM[w.code]
+            if check_true_sum is not None:               # Definition 2, end to end, up to the fp32 wire
+                ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
+                assert rel_l2(ug, ref) <= check_true_sum
+        if c.u.numel() > w.d:
+            assert torch.isnan(c.u[w.d:]).all()
+        return c
+    finally:
+        c.close()
+
+
+# ----------------------------------------------------------- repetition -----
+def test_rep_config0_exact_recipe():
+    run_and_check(synth.WORKLOADS[0], check_true_sum=1e-6)
+
+
+@pytest.mark.parametrize("P,s,d,attacks,placement", [
+    (3, 1, 1, ("noise",), "any"),
+    (3, 1, 3, ("signflip",), "any"),
+    (6, 1, 1023, ("constant",), "any"),
+    (15, 1, 4097, ("noise",), "any"),
+    (15, 2, 10_007, ("signflip", "noise"), "distinct_groups"),
+    (15, 2, 10_007, ("signflip", "noise"), "any"),
+    (45, 2, 70_001, ("signflip", "signflip"), "distinct_groups"),
+    (6, 0, 5000, (), "any"),
+    (21, 3, 3333, ("noise", "constant", "signflip"), "any"),
+    (15, 7, 2050, ("noise",) * 7, "any"),
+    (17, 8, 2051, ("noise",) * 8, "any"),             # r = 17: generic path
+    (34, 8, 777, ("signflip", "noise", "constant"), "any"),
+    (66, 1, 555, ("noise",), "any"),                   # more than 64 nodes: second mask word
+    (255, 2, 300, ("noise", "signflip"), "distinct_groups"),
+])
+def test_rep_parity(P, s, d, attacks, placement):
+    for seed in range(2):
+        run_and_check(wl("rep", P, s, d, attacks, placement, seed=seed), check_true_sum=1e-6)
+
+
+@pytest.mark.parametrize("kind", ["one_ulp", "nan", "neg_zero", "last_coord"])
+def test_rep_bit_level_adversaries(kind):
+    P, s, d = 15, 2, 5003
+
+    def edit(c):
+        j = 7
+        if kind == "one_ulp":
+            x = c.R[j, 1234:1235].view(torch.int32)
+            x += 1
+        elif kind == "nan":
+            c.R[j, 77] = float("nan")
+        elif kind == "neg_zero":
+            c.R[:, 500] = 0.0
+            c.R[j, 500] = -0.0
+        elif kind == "last_coord":
+            c.R[j, d - 1] += 1.0
+    c = run_and_check(wl("rep", P, s, d), extra_edit=edit)
+
+
+def test_rep_more_than_s_liars_is_reported():
+    def edit(c):
+        for j in (0, 2, 4):
+            c.R[j, :c.mlen] = float(j + 1)
+    run_and_check(wl("rep", 10, 2, 999), extra_edit=edit, expect_status=B.NO_MAJORITY)
+
+
+def test_rep_async_form_and_determinism():
+    w = wl("rep", 45, 2, 123_457, ("signflip", "signflip"), "distinct_groups")
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        mask_dev = torch.zeros(4, dtype=torch.int64, device=c.device)
+        status_dev = torch.full((1,), -7, dtype=torch.int32, device=c.device)
+        outs = []
+        for _ in range(2):
+            c.u.zero_()
+            c.plan.decode_repetition_async(c.R, c.u, mask_dev, status_dev)
+            torch.cuda.synchronize()
+            outs.append((c.u.clone(), mask_dev.clone(), int(status_dev.item())))
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        assert outs[0][2] == 0
+        m, st = c.decode()
+        words = B.bool_to_mask(m, w.P)
+        assert int(mask_dev[0].item()) == int(words[0].astype(np.int64))
+        assert np.array_equal(m, c.expected_mask())
+    finally:
+        c.close()
+
+
+# --------------------------------------------------------------- cyclic -----
+@pytest.mark.parametrize("P,s,d,attacks,placement,sigma,e2e", [
+    (4, 1, 2, ("signflip",), "any", 1.0, 1e-5),
+    (4, 1, 1, ("offset",), "any", 1.0, 1e-5),
+    (5, 2, 1001, ("noise", "offset"), "any", 1.0, 1e-5),           # P = 2s+1: every node holds everything
+    (6, 0, 4099, (), "any", 1.0, 1e-5),
+    (15, 2, 40_000, ("offset", "offset"), "any", 1.0, 1e-5),
+    (15, 2, 40_003, ("offset", "signflip"), "adjacent_pair", 1.0, 1e-5),
+    (15, 2, 40_002, ("noise",), "any", 1.0, 1e-5),
+    (15, 2, 8191, (), "any", 1.0, 1e-5),
+    (45, 3, 70_001, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2, 2e-3),
+    (45, 3, 70_002, ("signflip",), "any", 1e-2, 2e-3),
+    (45, 1, 9_999, ("noise",), "any", 1e-2, 1e-4),
+    (15, 7, 6_001, ("noise", "signflip", "offset", "constant", "noise", "signflip", "offset"), "any", 1.0, 1e-5),
+    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0, 1e-4),   # r = 17: generic encoder path
+    (70, 2, 2_001, ("noise", "signflip"), "any", 1.0, None),       # second mask word
+])
+def test_cyc_parity(P, s, d, attacks, placement, sigma, e2e):
+    for seed in range(2):
+        run_and_check(wl("cyc", P, s, d, attacks, placement, sigma, seed=seed), check_true_sum=e2e)
+
+
+def test_cyc_more_than_s_adversaries_is_reported():
+    def edit(c):
+        g = torch.Generator(device=c.device)
+        g.manual_seed(5)
+        for j in (0, 3, 6):
+            c.R[j, :c.mlen] = torch.randn(c.mlen, generator=g, device=c.device) * 100
+    run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
+
+
+def test_cyc_nonfinite_message_is_reported():
+    def edit(c):
+        c.R[2, 10] = float("inf")
+    run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
+
+
+def test_cyc_determinism():
+    w = wl("cyc", 15, 2, 100_003, ("offset", "offset"))
+    c = Case(w)
+    try:
+        c.encode()
+        z0 = c.Z.clone()
+        c.encode()
+        assert torch.equal(z0, c.Z)
+        c.receive()
+        outs = []
+        for _ in range(2):
+            c.u.zero_()
+            m, st = c.decode()
+            outs.append((c.u.clone(), m))
+        assert torch.equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    finally:
+        c.close()
+
+
+# ------------------------------------------------------ one-node encoder ----
+@pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7)])
+def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
+    w = wl(code, P, s, d)
+    c = Case(w)
+    try:
+        c.encode()
+        r = w.r
+        for node in range(P):
+            rows = [(node // r) * r + t for t in range(r)] if code == "rep" else [(node + t) % P for t in range(r)]
+            Gn = c.G[rows].contiguous()
+            z = torch.full((c.ld_m,), float("nan"), dtype=torch.float32, device=c.device)
+            c.plan.encode_node(node, Gn, z)
+            torch.cuda.synchronize()
+            assert torch.equal(z[:c.mlen].view(torch.int32), c.Z[node, :c.mlen].view(torch.int32)), node
+    finally:
+        c.close()
+
+
+# ------------------------------------------------------------ arguments -----
+def test_alignment_and_argument_errors():
+    w = wl("rep", 6, 1, 100)
+    c = Case(w)
+    try:
+        L = B.lib()
+        st = torch.cuda.current_stream().cuda_stream
+        assert L.draco_encode(c.plan._h, c.G.data_ptr() + 4, c.ld_g, c.Z.data_ptr(), c.ld_m, st) == B.EALIGN
+        assert L.draco_encode(c.plan._h, c.G.data_ptr(), c.ld_g + 1, c.Z.data_ptr(), c.ld_m, st) == B.EALIGN
+        assert L.draco_encode(c.plan._h, c.G.data_ptr(), 96, c.Z.data_ptr(), c.ld_m, st) == B.EALIGN
+        assert L.draco_encode(c.plan._h, None, c.ld_g, c.Z.data_ptr(), c.ld_m, st) == B.EINVAL
+        words = np.zeros(1, dtype=np.uint64)
+        assert L.draco_decode_cyclic(c.plan._h, c.Z.data_ptr(), c.ld_m, c.G.data_ptr(), c.u.data_ptr(),
+                                     words.ctypes.data, st) == B.EINVAL          # wrong code for the call
+    finally:
+        c.close()
