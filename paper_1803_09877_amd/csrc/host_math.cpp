@@ -127,8 +127,25 @@ real_t unexplained(int P, int s, const std::vector<cplx_t>& hk, const std::vecto
 }  // namespace
 
 cplx_t root_of_unity(int P, long long k) {
+    // One table per P (P <= 256), built on first use: the decoder asks for
+    // O(P^2) roots per call and long-double trigonometry is slow.
+    struct Table {
+        std::vector<cplx_t> w;
+    };
+    thread_local Table tables[257];
     k %= P;
     if (k < 0) k += P;
+    if (P <= 256) {
+        Table& t = tables[P];
+        if (t.w.empty()) {
+            t.w.resize(P);
+            for (int i = 0; i < P; ++i) {
+                const real_t ang = 2 * kPi * (real_t)i / (real_t)P;
+                t.w[i] = cplx_t(std::cos(ang), std::sin(ang));
+            }
+        }
+        return t.w[(size_t)k];
+    }
     const real_t ang = 2 * kPi * (real_t)k / (real_t)P;
     return cplx_t(std::cos(ang), std::sin(ang));
 }
