@@ -173,6 +173,10 @@ int draco_cyclic_recombination_vector(const draco_plan* plan, const uint64_t* ma
 /* Static, NUL-terminated description of a status value. */
 const char* draco_strerror(int status);
 
+/* Text describing the last HIP runtime failure behind a DRACO_EHIP return on the
+ * calling thread (the failing call and HIP's error string); "" if none. */
+const char* draco_last_hip_error(void);
+
 /* Kernel timing with HIP events recorded on the stream each kernel is launched
  * on.  draco_plan_set_timing(plan, n) gives every kernel kind n event pairs
  * (n = 0 switches timing off); from then on each launch of a kind uses the next

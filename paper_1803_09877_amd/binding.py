@@ -32,7 +32,7 @@ EXPORTS = [
     "draco_plan_assign", "draco_plan_weights", "draco_encode", "draco_encode_node",
     "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
-    "draco_plan_set_timing", "draco_plan_kernel_time",
+    "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
 ]
 
 
@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
     L.draco_cyclic_recombination_vector.restype = i32
     L.draco_strerror.argtypes = [i32]
     L.draco_strerror.restype = ctypes.c_char_p
+    L.draco_last_hip_error.argtypes = []
+    L.draco_last_hip_error.restype = ctypes.c_char_p
     L.draco_plan_set_timing.argtypes = [vp, i32]
     L.draco_plan_set_timing.restype = i32
     L.draco_plan_kernel_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -105,7 +107,9 @@ def lib() -> ctypes.CDLL:
 class DracoError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
-        super().__init__(f"draco status {status}: {lib().draco_strerror(status).decode()}")
+        detail = lib().draco_last_hip_error().decode() if status == EHIP else ""
+        super().__init__(f"draco status {status}: {lib().draco_strerror(status).decode()}"
+                         + (f" [{detail}]" if detail else ""))
 
 
 def _check(status: int) -> None:

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <complex>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -36,8 +37,7 @@ struct draco_plan {
     // device side (valid once prepared)
     bool prepared = false;
     int device = -1;
-    double2* taps_dev = nullptr;     // 2s+1
-    double2* rot_dev = nullptr;      // P
+    double2* coef_dev = nullptr;     // P*(2s+1): W[(n+t) mod P][n]
     double2* partial_dev = nullptr;  // project_tiles(d) * P
     double2* gamma_dev = nullptr;    // P
     double2* b_dev = nullptr;        // P
@@ -68,12 +68,18 @@ int64_t message_len(const draco_plan* p) {
     return p->code == DRACO_CODE_REPETITION ? p->d : 2 * ((p->d + 1) / 2);
 }
 
-#define HIP_TRY(expr)                           \
-    do {                                        \
-        if ((expr) != hipSuccess) {             \
-            (void)hipGetLastError();            \
-            return DRACO_EHIP;                  \
-        }                                       \
+// Text of the last HIP failure seen by this thread (for draco_last_hip_error).
+thread_local char g_hip_detail[256] = "";
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        const hipError_t hip_try_e = (expr);                                                   \
+        if (hip_try_e != hipSuccess) {                                                         \
+            std::snprintf(g_hip_detail, sizeof(g_hip_detail), "%s (line %d): %s", #expr, __LINE__, \
+                          hipGetErrorString(hip_try_e));                                       \
+            (void)hipGetLastError();                                                           \
+            return DRACO_EHIP;                                                                 \
+        }                                                                                      \
     } while (0)
 
 int prepare(draco_plan* p) {
@@ -86,8 +92,7 @@ int prepare(draco_plan* p) {
     HIP_TRY(hipMalloc(&p->status_dev, sizeof(int32_t)));
     HIP_TRY(hipHostMalloc(&p->mask_pin, (kMaskWords + 1) * sizeof(uint64_t), hipHostMallocDefault));
     if (p->code == DRACO_CODE_CYCLIC) {
-        HIP_TRY(hipMalloc(&p->taps_dev, r * sizeof(double2)));
-        HIP_TRY(hipMalloc(&p->rot_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->coef_dev, (size_t)P * r * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(p->d) * P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->gamma_dev, P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->b_dev, P * sizeof(double2)));
@@ -95,17 +100,14 @@ int prepare(draco_plan* p) {
         HIP_TRY(hipHostMalloc(&p->gamma_pin, 2 * P * sizeof(double), hipHostMallocDefault));
         HIP_TRY(hipHostMalloc(&p->b_pin, 2 * P * sizeof(double), hipHostMallocDefault));
         HIP_TRY(hipHostMalloc(&p->idx_pin, P * sizeof(int32_t), hipHostMallocDefault));
-        std::vector<double> tmp(2 * std::max(P, r));
-        for (int t = 0; t < r; ++t) {
-            tmp[2 * t] = (double)p->cyc.taps[t].real();
-            tmp[2 * t + 1] = (double)p->cyc.taps[t].imag();
-        }
-        HIP_TRY(hipMemcpy(p->taps_dev, tmp.data(), r * sizeof(double2), hipMemcpyHostToDevice));
-        for (int k = 0; k < P; ++k) {
-            tmp[2 * k] = (double)p->cyc.rot[k].real();
-            tmp[2 * k + 1] = (double)p->cyc.rot[k].imag();
-        }
-        HIP_TRY(hipMemcpy(p->rot_dev, tmp.data(), P * sizeof(double2), hipMemcpyHostToDevice));
+        std::vector<double> tmp((size_t)2 * P * r);
+        for (int n = 0; n < P; ++n)
+            for (int t = 0; t < r; ++t) {
+                const cplx_t w = p->cyc.W((n + t) % P, n);
+                tmp[2 * ((size_t)n * r + t)] = (double)w.real();
+                tmp[2 * ((size_t)n * r + t) + 1] = (double)w.imag();
+            }
+        HIP_TRY(hipMemcpy(p->coef_dev, tmp.data(), tmp.size() * sizeof(double), hipMemcpyHostToDevice));
     }
     p->prepared = true;
     return DRACO_OK;
@@ -164,8 +166,7 @@ void draco_plan_destroy(draco_plan* p) {
     if (p == nullptr) return;
     if (p->device >= 0) {
         (void)hipDeviceSynchronize();
-        (void)hipFree(p->taps_dev);
-        (void)hipFree(p->rot_dev);
+        (void)hipFree(p->coef_dev);
         (void)hipFree(p->partial_dev);
         (void)hipFree(p->gamma_dev);
         (void)hipFree(p->b_dev);
@@ -235,7 +236,7 @@ int draco_encode(draco_plan* p, const float* grads_dev, int64_t ld_g, float* mes
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep(grads_dev, ld_g, messages_dev, ld_m, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, messages_dev, ld_m, p->taps_dev, p->rot_dev, p->P, p->s, p->d, st));
+        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, messages_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
     return DRACO_OK;
 }
 
@@ -253,8 +254,7 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_node(node_grads_dev, ld_g, message_dev, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, p->taps_dev, p->rot_dev, node, p->P, p->s,
-                                       p->d, st));
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
     return DRACO_OK;
 }
 
@@ -381,6 +381,8 @@ const char* draco_strerror(int status) {
         default: return "unknown status";
     }
 }
+
+const char* draco_last_hip_error(void) { return g_hip_detail; }
 
 int draco_plan_set_timing(draco_plan* p, int max_records) {
     if (p == nullptr || max_records < 0 || max_records > 65536) return DRACO_EINVAL;

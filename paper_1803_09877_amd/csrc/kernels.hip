@@ -53,32 +53,44 @@ __device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ?
 // ===========================================================================
 
 // E^Rep for all nodes: one pass reads each gradient once, forms each group's
-// sum in ascending gradient order and stores it r times.
-template <int R>
+// sum in ascending gradient order and stores it r times.  GU groups are loaded
+// before the first is summed, so a lane has GU*R 16-byte loads in flight.
+template <int R, int GU>
 __global__ __launch_bounds__(kBlock) void encode_rep_kernel(const float* __restrict__ G, int64_t ldg,
                                                             float* __restrict__ Z, int64_t ldm,
                                                             int groups, int64_t d) {
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     if (c0 >= d) return;
     const int n = clamp4(d - c0);
-    for (int g = 0; g < groups; ++g) {
-        const float* src = G + (int64_t)g * R * ldg + c0;
-        float4 x[R];
+    for (int g0 = 0; g0 < groups; g0 += GU) {
+        float4 x[GU][R];
 #pragma unroll
-        for (int i = 0; i < R; ++i) x[i] = (n == 4) ? ld4(src + (int64_t)i * ldg) : ld4_partial(src + (int64_t)i * ldg, n);
-        float4 acc = x[0];
+        for (int a = 0; a < GU; ++a) {
+            if (g0 + a < groups) {
+                const float* src = G + (int64_t)(g0 + a) * R * ldg + c0;
 #pragma unroll
-        for (int i = 1; i < R; ++i) {
-            acc.x += x[i].x;
-            acc.y += x[i].y;
-            acc.z += x[i].z;
-            acc.w += x[i].w;
+                for (int i = 0; i < R; ++i)
+                    x[a][i] = (n == 4) ? ld4(src + (int64_t)i * ldg) : ld4_partial(src + (int64_t)i * ldg, n);
+            }
         }
-        float* dst = Z + (int64_t)g * R * ldm + c0;
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            if (n == 4) st4(dst + (int64_t)i * ldm, acc);
-            else st4_partial(dst + (int64_t)i * ldm, acc, n);
+        for (int a = 0; a < GU; ++a) {
+            if (g0 + a < groups) {
+                float4 acc = x[a][0];
+#pragma unroll
+                for (int i = 1; i < R; ++i) {
+                    acc.x += x[a][i].x;
+                    acc.y += x[a][i].y;
+                    acc.z += x[a][i].z;
+                    acc.w += x[a][i].w;
+                }
+                float* dst = Z + (int64_t)(g0 + a) * R * ldm + c0;
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    if (n == 4) st4(dst + (int64_t)i * ldm, acc);
+                    else st4_partial(dst + (int64_t)i * ldm, acc, n);
+                }
+            }
         }
     }
 }
@@ -150,11 +162,60 @@ __device__ __forceinline__ void publish_flags(const uint64_t (&wflags)[kMaskWord
     }
 }
 
+// Vote of one group held in registers: returns the winner of each of the
+// lane's four coordinates and ORs the flags of differing nodes (wavefront-
+// uniform) into wflags.  Honest groups take the fast path: all copies equal,
+// decided for the whole wavefront by one ballot.
+template <int R>
+__device__ __forceinline__ uint4 vote_group(const uint4 (&x)[R], int first_node, uint64_t (&wflags)[kMaskWords]) {
+    uint32_t differ = 0;
+#pragma unroll
+    for (int i = 1; i < R; ++i)
+        differ |= (x[i].x ^ x[0].x) | (x[i].y ^ x[0].y) | (x[i].z ^ x[0].z) | (x[i].w ^ x[0].w);
+    uint4 win = x[0];
+    if (__ballot(differ != 0) != 0ull) {   // some lane of the wavefront saw a disagreement in this group
+        uint32_t bad = 0;                  // bit i: copy i differs from the vote in one of my coordinates
+        if (differ != 0) {
+            uint32_t v[R];
+#pragma unroll
+            for (int i = 0; i < R; ++i) v[i] = x[i].x;
+            win.x = vote<R>(v);
+#pragma unroll
+            for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.x) << i;
+#pragma unroll
+            for (int i = 0; i < R; ++i) v[i] = x[i].y;
+            win.y = vote<R>(v);
+#pragma unroll
+            for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.y) << i;
+#pragma unroll
+            for (int i = 0; i < R; ++i) v[i] = x[i].z;
+            win.z = vote<R>(v);
+#pragma unroll
+            for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.z) << i;
+#pragma unroll
+            for (int i = 0; i < R; ++i) v[i] = x[i].w;
+            win.w = vote<R>(v);
+#pragma unroll
+            for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.w) << i;
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (__ballot((bad >> i) & 1u) != 0ull) {
+                const int node = first_node + i;
+#pragma unroll
+                for (int w = 0; w < kMaskWords; ++w)
+                    if (w == (node >> 6)) wflags[w] |= 1ull << (node & 63);
+            }
+        }
+    }
+    return win;
+}
+
 // D^Rep: per coordinate and group, the vote over the r copies; winners are
 // summed over groups in ascending order; a node is flagged when any of its
-// coordinates differs from the winner.  Honest groups take the fast path (all
-// copies equal, decided for the whole wavefront by one ballot).
-template <int R>
+// coordinates differs from the winner.  GU groups are loaded before the first
+// is voted on (GU*R 16-byte loads in flight per lane).
+template <int R, int GU>
 __global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restrict__ Rm, int64_t ldm,
                                                             float* __restrict__ u, uint64_t* __restrict__ flags,
                                                             int groups, int64_t d) {
@@ -163,63 +224,35 @@ __global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restr
     const bool active = c0 < d;
     const int n = active ? clamp4(d - c0) : 0;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int g = 0; g < groups; ++g) {
-        uint4 x[R];
-        if (active) {
-            const float* src = Rm + (int64_t)g * R * ldm + c0;
+    for (int g0 = 0; g0 < groups; g0 += GU) {
+        uint4 x[GU][R];
 #pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const float4 t = (n == 4) ? ld4(src + (int64_t)i * ldm) : ld4_partial(src + (int64_t)i * ldm, n);
-                x[i] = make_uint4(__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w));
-            }
-        } else {
+        for (int a = 0; a < GU; ++a) {
+            if (g0 + a < groups) {
+                if (active) {
+                    const float* src = Rm + (int64_t)(g0 + a) * R * ldm + c0;
 #pragma unroll
-            for (int i = 0; i < R; ++i) x[i] = make_uint4(0u, 0u, 0u, 0u);
-        }
-        uint32_t differ = 0;
+                    for (int i = 0; i < R; ++i) {
+                        const float4 t = (n == 4) ? ld4(src + (int64_t)i * ldm) : ld4_partial(src + (int64_t)i * ldm, n);
+                        x[a][i] = make_uint4(__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z),
+                                             __float_as_uint(t.w));
+                    }
+                } else {
 #pragma unroll
-        for (int i = 1; i < R; ++i)
-            differ |= (x[i].x ^ x[0].x) | (x[i].y ^ x[0].y) | (x[i].z ^ x[0].z) | (x[i].w ^ x[0].w);
-        uint4 win = x[0];
-        if (__ballot(differ != 0) != 0ull) {   // wavefront-uniform: some lane saw a disagreement in this group
-            uint32_t bad = 0;                  // bit i: copy i differs from the vote in one of my coordinates
-            if (differ != 0) {
-                uint32_t v[R];
-#pragma unroll
-                for (int i = 0; i < R; ++i) v[i] = x[i].x;
-                win.x = vote<R>(v);
-#pragma unroll
-                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.x) << i;
-#pragma unroll
-                for (int i = 0; i < R; ++i) v[i] = x[i].y;
-                win.y = vote<R>(v);
-#pragma unroll
-                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.y) << i;
-#pragma unroll
-                for (int i = 0; i < R; ++i) v[i] = x[i].z;
-                win.z = vote<R>(v);
-#pragma unroll
-                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.z) << i;
-#pragma unroll
-                for (int i = 0; i < R; ++i) v[i] = x[i].w;
-                win.w = vote<R>(v);
-#pragma unroll
-                for (int i = 0; i < R; ++i) bad |= (uint32_t)(v[i] != win.w) << i;
-            }
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                if (__ballot((bad >> i) & 1u) != 0ull) {
-                    const int node = g * R + i;
-#pragma unroll
-                    for (int w = 0; w < kMaskWords; ++w)
-                        if (w == (node >> 6)) wflags[w] |= 1ull << (node & 63);
+                    for (int i = 0; i < R; ++i) x[a][i] = make_uint4(0u, 0u, 0u, 0u);
                 }
             }
         }
-        acc.x += __uint_as_float(win.x);
-        acc.y += __uint_as_float(win.y);
-        acc.z += __uint_as_float(win.z);
-        acc.w += __uint_as_float(win.w);
+#pragma unroll
+        for (int a = 0; a < GU; ++a) {
+            if (g0 + a < groups) {
+                const uint4 win = vote_group<R>(x[a], (g0 + a) * R, wflags);
+                acc.x += __uint_as_float(win.x);
+                acc.y += __uint_as_float(win.y);
+                acc.z += __uint_as_float(win.z);
+                acc.w += __uint_as_float(win.w);
+            }
+        }
     }
     if (active) {
         if (n == 4) st4(u + c0, acc);
@@ -290,12 +323,7 @@ __global__ void decode_rep_finish_kernel(uint64_t* __restrict__ flags, uint64_t*
 // Cyclic code
 // ===========================================================================
 
-// (cr + i ci) * (x + i y), the same instruction sequence wherever it is used.
-__device__ __forceinline__ void cmul(double cr, double ci, double x, double y, double& re, double& im) {
-    re = fma(cr, x, -(ci * y));
-    im = fma(cr, y, ci * x);
-}
-// acc += (tr + i ti) * (x + i y)
+// acc += (tr + i ti) * (x + i y): one instruction sequence wherever it is used
 __device__ __forceinline__ void cmac(double tr, double ti, double x, double y, double& are, double& aim) {
     are = fma(tr, x, are);
     are = fma(-ti, y, are);
@@ -303,17 +331,17 @@ __device__ __forceinline__ void cmac(double tr, double ti, double x, double y, d
     aim = fma(ti, x, aim);
 }
 
-// E^Cyc for all nodes.  Because W[k][k-t] = rot[k]*taps[t], node n's message is
-// a (2s+1)-tap complex FIR filter over the rotated gradients g'_k = rot[k] g_k
-// taken cyclically: z_n = sum_t taps[t] * g'_{n+t}.  A lane keeps the window
-// g'_n .. g'_{n+2s} of its two complex coordinates in registers (fp64) and
-// slides it down the P rows; rows 0..2s-1, needed again by the last 2s nodes,
-// are parked in LDS (each lane reads back only what it wrote: no barrier).
+// E^Cyc for all nodes: z_n = sum_{t=0}^{2s} coef[n][t] * g_{(n+t) mod P} with
+// coef[n][t] = W[(n+t) mod P][n], on packed complex coordinates in fp64.  A lane
+// keeps the window g_n .. g_{n+2s} of its two complex coordinates in registers
+// and slides it down the P rows, so every gradient row is read from HBM once;
+// rows 0..2s-1, needed again by the last 2s nodes, are parked in LDS (each lane
+// reads back only what it wrote: no barrier).  Rows are fetched a round of
+// R = 2s+1 ahead of the arithmetic (two register buffers, ping-pong).
 template <int S>
 __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
                                                             float* __restrict__ Z, int64_t ldm,
-                                                            const double2* __restrict__ taps,
-                                                            const double2* __restrict__ rot, int P, int64_t d) {
+                                                            const double2* __restrict__ coef, int P, int64_t d) {
     constexpr int R = 2 * S + 1;
     extern __shared__ float4 head[];  // [2S][kBlock]
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
@@ -322,52 +350,43 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
     const int nin = clamp4(d - c0);      // gradient floats that exist (the pad of an odd d reads as 0)
     const int nout = clamp4(mlen - c0);  // message floats to write
 
-    double tr[R], ti[R];
-#pragma unroll
-    for (int t = 0; t < R; ++t) {
-        tr[t] = taps[t].x;
-        ti[t] = taps[t].y;
-    }
     double wre[R][2], wim[R][2];  // window slot = row index mod R
 
     auto load_row = [&](int k) -> float4 {
         const float* p = G + (int64_t)k * ldg + c0;
         return (nin == 4) ? ld4(p) : ld4_partial(p, nin);
     };
-    auto put = [&](int slot, int k, const float4& raw) {
-        const double cr = rot[k].x, ci = rot[k].y;
-        cmul(cr, ci, (double)raw.x, (double)raw.y, wre[slot][0], wim[slot][0]);
-        cmul(cr, ci, (double)raw.z, (double)raw.w, wre[slot][1], wim[slot][1]);
+    auto put = [&](int slot, const float4& raw) {
+        wre[slot][0] = (double)raw.x;
+        wim[slot][0] = (double)raw.y;
+        wre[slot][1] = (double)raw.z;
+        wim[slot][1] = (double)raw.w;
     };
-
+    // fetch the rows that nodes n0 .. n0+R-1 bring into the window
+    auto issue = [&](int n0, float4 (&buf)[R]) {
 #pragma unroll
-    for (int k = 0; k < 2 * S; ++k) {
-        const float4 raw = load_row(k);
-        head[k * kBlock + threadIdx.x] = raw;
-        put(k, k, raw);
-    }
-    for (int n0 = 0; n0 < P; n0 += R) {
-        float4 raw[R];
-#pragma unroll
-        for (int uu = 0; uu < R; ++uu) {  // issue the loads of this round together
+        for (int uu = 0; uu < R; ++uu) {
             const int kk = n0 + uu + 2 * S;
             if (n0 + uu < P) {
-                if (kk < P) raw[uu] = load_row(kk);
-                else raw[uu] = head[(kk - P) * kBlock + threadIdx.x];
+                if (kk < P) buf[uu] = load_row(kk);
+                else buf[uu] = head[(kk - P) * kBlock + threadIdx.x];
             }
         }
+    };
+    auto consume = [&](int n0, const float4 (&buf)[R]) {
 #pragma unroll
         for (int uu = 0; uu < R; ++uu) {
             const int n = n0 + uu;
             if (n < P) {
-                const int kk = n + 2 * S;
-                put((uu + 2 * S) % R, kk < P ? kk : kk - P, raw[uu]);
+                put((uu + 2 * S) % R, buf[uu]);
+                const double2* cn = coef + (int64_t)n * R;
                 double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
 #pragma unroll
                 for (int t = 0; t < R; ++t) {
                     const int slot = (uu + t) % R;
-                    cmac(tr[t], ti[t], wre[slot][0], wim[slot][0], are0, aim0);
-                    cmac(tr[t], ti[t], wre[slot][1], wim[slot][1], are1, aim1);
+                    const double cr = cn[t].x, ci = cn[t].y;
+                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
                 }
                 const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 float* dst = Z + (int64_t)n * ldm + c0;
@@ -375,18 +394,35 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
                 else st4_partial(dst, out, nout);
             }
         }
+    };
+
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const float4 raw = load_row(k);
+        head[k * kBlock + threadIdx.x] = raw;
+        put(k, raw);
+    }
+    float4 bufA[R], bufB[R];
+    issue(0, bufA);
+    for (int n0 = 0; n0 < P; n0 += 2 * R) {
+        if (n0 + R < P) issue(n0 + R, bufB);
+        consume(n0, bufA);
+        if (n0 + R < P) {
+            if (n0 + 2 * R < P) issue(n0 + 2 * R, bufA);
+            consume(n0 + R, bufB);
+        }
     }
 }
 
-// One node (also the path for s > kMaxS in the all-node form, called per
-// node): z = sum_t taps[t] * (rot[k_t] * g_t), rows of Gn at k_t = row_of[t].
+// One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
+// wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
+// with wrap_rows == P it is the full [P][ldg] slab and row (node+t) mod P is
+// used (the all-node path for r > 2*kMaxS+1).  Same operation order as the
+// all-node kernel, so results are bit-identical.
 __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
                                                                  float* __restrict__ z,
-                                                                 const double2* __restrict__ taps,
-                                                                 const double2* __restrict__ rot, int node, int P,
+                                                                 const double2* __restrict__ cn, int node, int P,
                                                                  int r, int wrap_rows, int64_t d) {
-    // wrap_rows == 0: Gn holds only this node's r gradients in assignment order.
-    // wrap_rows == P: Gn is the full [P][ldg] slab and row (node+t) mod P is used.
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (c0 >= mlen) return;
@@ -398,11 +434,8 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
         if (k >= P) k -= P;
         const float* p = Gn + (int64_t)(wrap_rows ? k : t) * ldg + c0;
         const float4 raw = (nin == 4) ? ld4(p) : ld4_partial(p, nin);
-        double xr0, xi0, xr1, xi1;
-        cmul(rot[k].x, rot[k].y, (double)raw.x, (double)raw.y, xr0, xi0);
-        cmul(rot[k].x, rot[k].y, (double)raw.z, (double)raw.w, xr1, xi1);
-        cmac(taps[t].x, taps[t].y, xr0, xi0, are0, aim0);
-        cmac(taps[t].x, taps[t].y, xr1, xi1, are1, aim1);
+        cmac(cn[t].x, cn[t].y, (double)raw.x, (double)raw.y, are0, aim0);
+        cmac(cn[t].x, cn[t].y, (double)raw.z, (double)raw.w, are1, aim1);
     }
     const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
     if (nout == 4) st4(z + c0, out);
@@ -537,20 +570,72 @@ static inline unsigned grid_for(int64_t units_of_4_floats) {
     return (unsigned)((units_of_4_floats + kBlock - 1) / kBlock);
 }
 
+// --- occupancy throttle -----------------------------------------------------
+// HBM throughput on MI355X peaks when a CU has roughly 24-48 KiB of loads in
+// flight (measured: a [45][25.6M] copy runs at 5.3 TB/s with 32 resident
+// wavefronts per CU and at 5.9 TB/s with 4; a read-only pass at 6.1 vs 6.7).
+// The streaming kernels therefore ask for more LDS than they use, so that only
+// `blocks_per_cu` workgroups fit on a CU at a time.
+static size_t lds_per_cu() {
+    static const size_t v = [] {
+        int dev = 0, val = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return (size_t)65536;
+        if (hipDeviceGetAttribute(&val, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess || val <= 0)
+            return (size_t)65536;
+        return (size_t)val;
+    }();
+    return v;
+}
+
+// Dynamic LDS bytes to request so that at most blocks_per_cu workgroups are
+// resident per CU (0 = no limit), given the kernel's static LDS use and the
+// dynamic bytes it really needs.
+static size_t throttle_lds(int blocks_per_cu, size_t static_bytes, size_t needed) {
+    if (blocks_per_cu <= 0) return needed;
+    size_t per = lds_per_cu() / (size_t)blocks_per_cu;
+    per = per / 1024 * 1024;
+    const size_t dyn = per > static_bytes ? per - static_bytes : 0;
+    return dyn > needed ? dyn : needed;
+}
+
+// Opt a kernel in to workgroups with more than 64 KiB of dynamic LDS (once);
+// static_bytes is what the kernel declares itself.
+template <auto Kernel>
+static void allow_large_lds(size_t static_bytes = 0) {
+    static const hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(lds_per_cu() - static_bytes));
+    if (e != hipSuccess) (void)hipGetLastError();  // the launch itself reports a request that does not fit
+}
+
+// Groups fetched per round: keeps (r * groups) 16-byte loads in flight per lane.
+#define DRACO_REP_DISPATCH(KERNEL, ...)                                                    \
+    switch (s) {                                                                           \
+        case 0: KERNEL(1, 8, __VA_ARGS__); break;                                          \
+        case 1: KERNEL(3, 2, __VA_ARGS__); break;                                          \
+        case 2: KERNEL(5, 1, __VA_ARGS__); break;                                          \
+        case 3: KERNEL(7, 1, __VA_ARGS__); break;                                          \
+        case 4: KERNEL(9, 1, __VA_ARGS__); break;                                          \
+        case 5: KERNEL(11, 1, __VA_ARGS__); break;                                         \
+        case 6: KERNEL(13, 1, __VA_ARGS__); break;                                         \
+        case 7: KERNEL(15, 1, __VA_ARGS__); break;                                         \
+        default: generic = true;                                                           \
+    }
+
 hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm, int P, int s, int64_t d,
                              hipStream_t stream) {
     const int r = 2 * s + 1, groups = P / r;
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
-#define DRACO_CASE(S)                                                                                       \
-    case S:                                                                                                 \
-        hipLaunchKernelGGL((encode_rep_kernel<2 * S + 1>), grid, block, 0, stream, G, ldg, Z, ldm, groups, d); \
-        break;
-    switch (s) {
-        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
-        default:
-            hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, G, ldg, Z, ldm, groups, r, r, d);
+    bool generic = false;
+#define DRACO_LAUNCH(R, GU, BPC)                                                                             \
+    {                                                                                                        \
+        allow_large_lds<encode_rep_kernel<R, GU>>();                                                         \
+        hipLaunchKernelGGL((encode_rep_kernel<R, GU>), grid, block, throttle_lds(BPC, 0, 0), stream, G, ldg, \
+                           Z, ldm, groups, d);                                                               \
     }
-#undef DRACO_CASE
+    DRACO_REP_DISPATCH(DRACO_LAUNCH, 1)
+#undef DRACO_LAUNCH
+    if (generic) hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, G, ldg, Z, ldm, groups, r, r, d);
     return hipGetLastError();
 }
 
@@ -565,18 +650,20 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
     const int r = 2 * s + 1, groups = P / r;
     const dim3 block(kBlock);
     const dim3 grid(grid_for((d + 3) / 4));
-#define DRACO_CASE(S)                                                                                        \
-    case S:                                                                                                  \
-        hipLaunchKernelGGL((decode_rep_kernel<2 * S + 1>), grid, block, 0, stream, R, ldm, u, flags, groups, d); \
-        break;
-    switch (s) {
-        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
-        default: {
-            const dim3 g1((unsigned)((d + kBlock - 1) / kBlock));
-            hipLaunchKernelGGL(decode_rep_generic_kernel, g1, block, 0, stream, R, ldm, u, flags, groups, r, d);
-        }
+    bool generic = false;
+#define DRACO_LAUNCH(R_, GU, BPC)                                                                               \
+    {                                                                                                           \
+        allow_large_lds<decode_rep_kernel<R_, GU>>(kMaskWords * sizeof(unsigned long long));                                                           \
+        hipLaunchKernelGGL((decode_rep_kernel<R_, GU>), grid, block,                                            \
+                           throttle_lds(BPC, kMaskWords * sizeof(unsigned long long), 0), stream, R, ldm, u,    \
+                           flags, groups, d);                                                                   \
     }
-#undef DRACO_CASE
+    DRACO_REP_DISPATCH(DRACO_LAUNCH, 2)
+#undef DRACO_LAUNCH
+    if (generic) {
+        const dim3 g1((unsigned)((d + kBlock - 1) / kBlock));
+        hipLaunchKernelGGL(decode_rep_generic_kernel, g1, block, 0, stream, R, ldm, u, flags, groups, r, d);
+    }
     return hipGetLastError();
 }
 
@@ -586,31 +673,35 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* taps,
-                             const double2* rot, int P, int s, int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef, int P, int s,
+                             int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
-    const size_t lds = (size_t)2 * s * kBlock * sizeof(float4);
-#define DRACO_CASE(S)                                                                                            \
-    case S:                                                                                                      \
-        hipLaunchKernelGGL((encode_cyc_kernel<S>), grid, block, lds, stream, G, ldg, Z, ldm, taps, rot, P, d);   \
+    const size_t lds = throttle_lds(2, 0, (size_t)2 * s * kBlock * sizeof(float4));
+    const int r = 2 * s + 1;
+#define DRACO_CASE(S)                                                                                      \
+    case S:                                                                                                \
+        allow_large_lds<encode_cyc_kernel<S>>();                                                           \
+        hipLaunchKernelGGL((encode_cyc_kernel<S>), grid, block, lds, stream, G, ldg, Z, ldm, coef, P, d);  \
         break;
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         default:
             for (int j = 0; j < P; ++j)
-                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm, taps,
-                                   rot, j, P, 2 * s + 1, P, d);
+                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
+                                   coef + (int64_t)j * r, j, P, r, P, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* taps, const double2* rot,
-                                  int node, int P, int s, int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node, int P, int s,
+                                  int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
-    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, taps, rot, node, P, 2 * s + 1, 0, d);
+    const int r = 2 * s + 1;
+    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, coef + (int64_t)node * r, node, P,
+                       r, 0, d);
     return hipGetLastError();
 }
 
@@ -634,7 +725,8 @@ hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, doubl
 hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx, int nu, float* u,
                                 int64_t d, hipStream_t stream) {
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
-    hipLaunchKernelGGL(cyc_recombine_kernel, grid, block, 0, stream, R, ldm, b, idx, nu, u, d);
+    allow_large_lds<cyc_recombine_kernel>();
+    hipLaunchKernelGGL(cyc_recombine_kernel, grid, block, throttle_lds(2, 0, 0), stream, R, ldm, b, idx, nu, u, d);
     return hipGetLastError();
 }
 

@@ -30,13 +30,12 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
                                     int P, int s, hipStream_t stream);
 
 // ---- cyclic code ----
-// taps[2s+1], rot[P]: see CyclicCode.
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* taps,
-                             const double2* rot, int P, int s, int64_t d, hipStream_t stream);
+// coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
+                             int P, int s, int64_t d, hipStream_t stream);
 // Gn holds only the node's 2s+1 gradients, in assignment order.
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* taps,
-                                  const double2* rot, int node, int P, int s, int64_t d,
-                                  hipStream_t stream);
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* coef,
+                                  int node, int P, int s, int64_t d, hipStream_t stream);
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
 int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
