@@ -26,6 +26,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 KIND_NAMES = ["encode", "vote", "project", "recombine"]
 
+# HBM bytes per launch divided by the algorithmic bytes, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this file, each counter scaled by what it
+# reads for the library's plain copy kernel (fetch x2.0000, write x1.0000);
+# the figures are in profiles/<workload>_kernels.md.
+MEASURED_TRAFFIC_RATIO = {
+    "rep_P45_s2_d11.2M": {"encode": 1.0000, "vote": 1.0030},
+    "cyc_P45_s3_d25.6M": {"encode": 1.0001, "project": 1.0005, "recombine": 1.0000},
+}
+
 
 def algorithmic_bytes(w, mlen, n_honest):
     """Bytes each kernel must move per launch (every input read once, every output written once)."""
@@ -117,6 +126,24 @@ def main():
         mask, status = c.decode()
         assert status == 0 and np.array_equal(mask, c.expected_mask()), "decode did not find the planted adversaries"
 
+    # copy-kernel ceiling of this GPU on the same slabs (G -> Z, which the next encode overwrites)
+    ld = min(c.ld_g, c.ld_m)
+    row_len = min(w.d, c.mlen) // 4 * 4
+    assert c.ld_g == c.ld_m == ld
+
+    def copy_once():
+        B.draco_copy_probe(c.G, c.Z, w.P, row_len, ld)
+
+    for _ in range(2):
+        copy_once()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        copy_once()
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * 4 * w.P * row_len * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
     for _ in range(args.warmup):
         c.step()
     c.plan.set_timing(args.steps)
@@ -139,6 +166,9 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
     roof = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": kernels[dominant]["GBps"] / HBM_PEAK_GBS, "traffic": None}
+    ratio = MEASURED_TRAFFIC_RATIO.get(w.name, {}).get(dominant)
+    if ratio is not None:
+        roof["traffic"] = ratio * kernels[dominant]["algorithmic_bytes"]
 
     consumed = w.P * w.d * 4
     out = {
@@ -158,6 +188,7 @@ def main():
                    "adversaries": [[int(j), a] for j, a in c.adversaries],
                    "step": "encode(all nodes) + decode" if w.decode else "encode(all nodes)"},
         "pct_hbm_peak_consumed": consumed / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100,
+        "copy_kernel_ceiling_GBps": copy_gbps,
         "roofline": roof,
         "kernels": kernels,
     }

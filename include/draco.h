@@ -177,6 +177,16 @@ const char* draco_strerror(int status);
  * calling thread (the failing call and HIP's error string); "" if none. */
 const char* draco_last_hip_error(void);
 
+/* Plain device-to-device copy of a [rows][ld] fp32 slab (row_len floats used
+ * per row; row_len and ld multiples of 4, pointers 16-byte aligned) with the
+ * access pattern, 16-byte non-temporal accesses and occupancy limit of the
+ * encoders: a calibration kernel.  Timing it gives the copy bandwidth this GPU
+ * sustains (the ceiling of the encoders, which read and write equal amounts);
+ * profiling it gives the scale of the hardware byte counters for a known
+ * 2*4*rows*row_len bytes.  Asynchronous on `stream`. */
+int draco_copy_probe(const float* src_dev, float* dst_dev, int rows, int64_t row_len, int64_t ld,
+                     void* stream);
+
 /* Kernel timing with HIP events recorded on the stream each kernel is launched
  * on.  draco_plan_set_timing(plan, n) gives every kernel kind n event pairs
  * (n = 0 switches timing off); from then on each launch of a kind uses the next

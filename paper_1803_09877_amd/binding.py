@@ -33,6 +33,7 @@ EXPORTS = [
     "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
+    "draco_copy_probe",
 ]
 
 
@@ -96,6 +97,8 @@ def lib() -> ctypes.CDLL:
     L.draco_strerror.restype = ctypes.c_char_p
     L.draco_last_hip_error.argtypes = []
     L.draco_last_hip_error.restype = ctypes.c_char_p
+    L.draco_copy_probe.argtypes = [vp, vp, i32, i64, i64, vp]
+    L.draco_copy_probe.restype = i32
     L.draco_plan_set_timing.argtypes = [vp, i32]
     L.draco_plan_set_timing.restype = i32
     L.draco_plan_kernel_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -233,6 +236,10 @@ class Plan:
         ms, n = ctypes.c_double(), ctypes.c_int()
         _check(lib().draco_plan_kernel_time(self._h, kind, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
+
+
+def draco_copy_probe(src, dst, rows: int, row_len: int, ld: int, stream=None) -> None:
+    _check(lib().draco_copy_probe(src.data_ptr(), dst.data_ptr(), rows, row_len, ld, _stream_ptr(stream)))
 
 
 # Names of the C entry points, module-level, same spelling as the header.

@@ -562,6 +562,26 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
     else st4_partial(u + c0, out, nout);
 }
 
+// Plain copy of a [rows][ld] slab (row_len floats used per row) with the access
+// pattern of the encoders: a lane owns one 16-byte column of every row and has
+// eight rows in flight.  Calibration kernel for bandwidth figures and for
+// scaling hardware byte counters.
+__global__ __launch_bounds__(kBlock) void copy_probe_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                            int rows, int64_t row_len, int64_t ld) {
+    constexpr int UN = 8;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 + 4 > row_len) return;
+    for (int j0 = 0; j0 < rows; j0 += UN) {
+        float4 x[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if (j0 + i < rows) x[i] = ld4(src + (int64_t)(j0 + i) * ld + c0);
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if (j0 + i < rows) st4(dst + (int64_t)(j0 + i) * ld + c0, x[i]);
+    }
+}
+
 // ===========================================================================
 // Launchers
 // ===========================================================================
@@ -719,6 +739,14 @@ hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, doubl
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row_len, int64_t ld,
+                             hipStream_t stream) {
+    allow_large_lds<copy_probe_kernel>();
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid_for(row_len / 4)), dim3(kBlock), throttle_lds(1, 0, 0), stream, src,
+                       dst, rows, row_len, ld);
     return hipGetLastError();
 }
 

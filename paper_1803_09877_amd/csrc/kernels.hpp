@@ -45,4 +45,9 @@ hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, doubl
 hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx,
                                 int nu, float* u, int64_t d, hipStream_t stream);
 
+// dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
+// (bandwidth / counter calibration).
+hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row_len, int64_t ld,
+                             hipStream_t stream);
+
 }  // namespace draco
