@@ -56,7 +56,7 @@ def cpu_baseline(w):
     from oracle import draco_oracle as o
     from paper_1803_09877_amd import synth
 
-    d_s = min(w.d, 4_000_000 if w.code == "cyc" else 8_000_000)
+    d_s = min(w.d, 8_000_000 if w.code == "cyc" else 16_000_000)
     ws = synth.scaled(w, d_s)
     G = synth.make_gradients(ws.P, d_s, ws.sigma, ws.seed, device="cpu")[:, :d_s].numpy()
     f = synth.make_projection((d_s + 1) // 2, ws.seed).numpy()

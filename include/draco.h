@@ -147,11 +147,28 @@ int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, i
  *   sum_dev      [d] fp32 out
  *   mask_host    as above: the located set V
  * Returns DRACO_LOCATE_FAILED if no set of at most s nodes explains the
- * syndromes, or if a projection is not finite.  Waits for `stream` (the
- * small linear algebra of phi and b runs on the host between two kernels). */
+ * syndromes, or if a projection is not finite.  For s <= 16 the small linear
+ * algebra of phi and b runs in one fp64 wavefront between the two streaming
+ * kernels, so the whole call is stream-ordered and waits for `stream` only
+ * once, at the end, to fetch mask and status; for larger s it is
+ * draco_decode_cyclic_hostphi. */
 int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_m,
                         const float* f_dev, float* sum_dev, uint64_t* mask_host,
                         void* stream);
+
+/* Same, stream-ordered (s <= 16 only, else DRACO_EINVAL): mask_dev
+ * [ceil(P/64)] and status_dev [1] are DEVICE outputs valid once `stream`
+ * reaches the end of the call.  Does not wait, allocates nothing. */
+int draco_decode_cyclic_async(draco_plan* plan, const float* messages_dev, int64_t ld_m,
+                              const float* f_dev, float* sum_dev, uint64_t* mask_dev,
+                              int32_t* status_dev, void* stream);
+
+/* Same result with phi and b computed on the HOST in extended precision
+ * between the projection and the recombination kernel: waits for `stream`
+ * twice (after the projection and at the end).  Any s. */
+int draco_decode_cyclic_hostphi(draco_plan* plan, const float* messages_dev, int64_t ld_m,
+                                const float* f_dev, float* sum_dev, uint64_t* mask_host,
+                                void* stream);
 
 /* ---- host-side pieces of D^Cyc, exposed for inspection and testing ----- */
 

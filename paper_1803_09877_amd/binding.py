@@ -17,7 +17,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libdraco.so")
-SOURCES = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hip", "api.hip", "host_math.cpp")]
+SOURCES = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hip", "locate.hip", "api.hip", "host_math.cpp")]
 HEADERS = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hpp", "host_math.hpp")] + [
     os.path.join(_ROOT, "include", "draco.h")]
 
@@ -31,6 +31,7 @@ EXPORTS = [
     "draco_plan_create", "draco_plan_prepare", "draco_plan_destroy", "draco_message_len",
     "draco_plan_assign", "draco_plan_weights", "draco_encode", "draco_encode_node",
     "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
+    "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe",
@@ -41,7 +42,7 @@ def build(verbose: bool = False) -> str:
     """Compile the library for gfx950 in-tree with hipcc (cross-compiles without a GPU)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fcomplex-arithmetic=basic",
            "-I" + os.path.join(_ROOT, "include"), *SOURCES, "-o", LIB_PATH]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
@@ -89,6 +90,10 @@ def lib() -> ctypes.CDLL:
     L.draco_decode_repetition_async.restype = i32
     L.draco_decode_cyclic.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.draco_decode_cyclic.restype = i32
+    L.draco_decode_cyclic_hostphi.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.draco_decode_cyclic_hostphi.restype = i32
+    L.draco_decode_cyclic_async.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.draco_decode_cyclic_async.restype = i32
     L.draco_cyclic_locate.argtypes = [vp, vp, vp, vp]
     L.draco_cyclic_locate.restype = i32
     L.draco_cyclic_recombination_vector.argtypes = [vp, vp, vp]
@@ -227,6 +232,18 @@ class Plan:
                                            out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
         _check(status)
         return mask_to_bool(words, self.P), status
+
+    def decode_cyclic_hostphi(self, messages, f, out_sum, stream=None):
+        words = np.zeros(mask_words(self.P), dtype=np.uint64)
+        status = lib().draco_decode_cyclic_hostphi(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+                                                   out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
+        _check(status)
+        return mask_to_bool(words, self.P), status
+
+    def decode_cyclic_async(self, messages, f, out_sum, mask_dev, status_dev, stream=None) -> None:
+        _check(lib().draco_decode_cyclic_async(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+                                               out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
+                                               _stream_ptr(stream)))
 
     def set_timing(self, max_records: int) -> None:
         _check(lib().draco_plan_set_timing(self._h, max_records))

@@ -41,7 +41,7 @@ struct draco_plan {
     double2* partial_dev = nullptr;  // project_tiles(d) * P
     double2* gamma_dev = nullptr;    // P
     double2* b_dev = nullptr;        // P
-    int32_t* idx_dev = nullptr;      // P
+    int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
     uint64_t* mask_dev = nullptr;    // kMaskWords
     int32_t* status_dev = nullptr;   // 1
@@ -96,10 +96,10 @@ int prepare(draco_plan* p) {
         HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(p->d) * P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->gamma_dev, P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->b_dev, P * sizeof(double2)));
-        HIP_TRY(hipMalloc(&p->idx_dev, P * sizeof(int32_t)));
+        HIP_TRY(hipMalloc(&p->idx_dev, (P + 1) * sizeof(int32_t)));
         HIP_TRY(hipHostMalloc(&p->gamma_pin, 2 * P * sizeof(double), hipHostMallocDefault));
         HIP_TRY(hipHostMalloc(&p->b_pin, 2 * P * sizeof(double), hipHostMallocDefault));
-        HIP_TRY(hipHostMalloc(&p->idx_pin, P * sizeof(int32_t), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&p->idx_pin, (P + 1) * sizeof(int32_t), hipHostMallocDefault));
         std::vector<double> tmp((size_t)2 * P * r);
         for (int n = 0; n < P; ++n)
             for (int t = 0; t < r; ++t) {
@@ -294,14 +294,44 @@ int draco_decode_repetition(draco_plan* p, const float* messages_dev, int64_t ld
     return status;
 }
 
-int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev,
-                        uint64_t* mask_host, void* stream) {
+namespace {
+
+int check_cyclic_args(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
-    if (f_dev == nullptr || sum_dev == nullptr || mask_host == nullptr) return DRACO_EINVAL;
-    int rc = check_slab(messages_dev, ld_m, message_len(p));
+    if (f_dev == nullptr || sum_dev == nullptr) return DRACO_EINVAL;
+    const int rc = check_slab(messages_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
     if (!aligned16(sum_dev) || (reinterpret_cast<uintptr_t>(f_dev) & 3u) != 0) return DRACO_EALIGN;
-    rc = prepare(p);
+    return prepare(p);
+}
+
+}  // namespace
+
+int draco_decode_cyclic_async(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
+                              float* sum_dev, uint64_t* mask_dev, int32_t* status_dev, void* stream) {
+    if (mask_dev == nullptr || status_dev == nullptr) return DRACO_EINVAL;
+    int rc = check_cyclic_args(p, messages_dev, ld_m, f_dev, sum_dev);
+    if (rc != DRACO_OK) return rc;
+    if (p->s > kLocateMaxS) return DRACO_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int P = p->P;
+    {
+        Timed timed(p, kProject, st);
+        HIP_TRY(launch_cyc_project(messages_dev, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+    }
+    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, mask_dev, status_dev, p->b_dev, p->idx_dev, p->idx_dev + P,
+                              st));
+    {
+        Timed timed(p, kRecombine, st);
+        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
+    }
+    return DRACO_OK;
+}
+
+int draco_decode_cyclic_hostphi(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
+                                float* sum_dev, uint64_t* mask_host, void* stream) {
+    if (mask_host == nullptr) return DRACO_EINVAL;
+    int rc = check_cyclic_args(p, messages_dev, ld_m, f_dev, sum_dev);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P, s = p->s;
@@ -327,14 +357,34 @@ int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, 
         p->b_pin[2 * nu + 1] = (double)b[j].imag();
         ++nu;
     }
+    p->idx_pin[P] = nu;
     HIP_TRY(hipMemcpyAsync(p->b_dev, p->b_pin, nu * sizeof(double2), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, nu * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, (P + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, nu, sum_dev, p->d, st));
+        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
     }
     HIP_TRY(hipStreamSynchronize(st));
     return located ? DRACO_OK : DRACO_LOCATE_FAILED;
+}
+
+int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev,
+                        uint64_t* mask_host, void* stream) {
+    if (p == nullptr || mask_host == nullptr) return DRACO_EINVAL;
+    if (p->s > kLocateMaxS) return draco_decode_cyclic_hostphi(p, messages_dev, ld_m, f_dev, sum_dev, mask_host, stream);
+    int rc = prepare(p);
+    if (rc != DRACO_OK) return rc;
+    rc = draco_decode_cyclic_async(p, messages_dev, ld_m, f_dev, sum_dev, p->mask_dev, p->status_dev, stream);
+    if (rc != DRACO_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int words = (p->P + 63) / 64;
+    HIP_TRY(hipMemcpyAsync(p->mask_pin, p->mask_dev, words * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(p->mask_pin + kMaskWords, p->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int w = 0; w < words; ++w) mask_host[w] = p->mask_pin[w];
+    int32_t status;
+    std::memcpy(&status, p->mask_pin + kMaskWords, sizeof(status));
+    return status;
 }
 
 int draco_cyclic_locate(const draco_plan* p, const double* gamma_host, uint64_t* mask_host, double* t_host) {

@@ -216,14 +216,27 @@ bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<
         for (int u = 0; u < s; ++u) acc += beta[u] * h[((l + u - s) % P + P) % P];
         h[l] = acc;
     }
-    // t = C h
-    std::vector<real_t> tmag(P);
+    // t = C h.  t only ranks the nodes (the decision is the residual test below), so
+    // plain doubles are enough here and keep this O(P^2) loop cheap.
+    std::vector<std::complex<double>> hd(P), wd(P);
+    for (int m = 0; m < P; ++m) {
+        hd[m] = std::complex<double>((double)h[m].real(), (double)h[m].imag());
+        const cplx_t w = root_of_unity(P, m);
+        wd[m] = std::complex<double>((double)w.real(), (double)w.imag());
+    }
+    const double isqd = (double)isq;
+    std::vector<double> tmag(P);
     for (int j = 0; j < P; ++j) {
-        cplx_t acc = 0;
-        for (int m = 0; m < P; ++m) acc += h[m] * root_of_unity(P, (long long)m * j);
-        acc *= isq;
-        t_out[j] = std::complex<double>((double)acc.real(), (double)acc.imag());
-        tmag[j] = std::abs(acc);
+        double ar = 0.0, ai = 0.0;
+        int e = 0;  // (m * j) mod P
+        for (int m = 0; m < P; ++m) {
+            ar += hd[m].real() * wd[e].real() - hd[m].imag() * wd[e].imag();
+            ai += hd[m].real() * wd[e].imag() + hd[m].imag() * wd[e].real();
+            e += j;
+            if (e >= P) e -= P;
+        }
+        t_out[j] = std::complex<double>(ar * isqd, ai * isqd);
+        tmag[j] = std::abs(t_out[j]);
     }
     std::vector<int> order(P);
     std::iota(order.begin(), order.end(), 0);

@@ -563,8 +563,10 @@ __global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double
 template <bool FULL>
 __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, int64_t ldm,
                                                    const double2* __restrict__ b, const int32_t* __restrict__ idx,
-                                                   int nu, float* __restrict__ u, int64_t d) {
+                                                   const int32_t* __restrict__ nu_ptr, float* __restrict__ u,
+                                                   int64_t d) {
     constexpr int UN = 8;
+    const int nu = *nu_ptr;  // honest nodes; written by the locator (device) or copied in by the host path
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     if (!FULL && c0 >= d) return;
     const int64_t mlen = 2 * ((d + 1) / 2);
@@ -590,7 +592,8 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
 
 __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm, int64_t ldm,
                                                                const double2* __restrict__ b,
-                                                               const int32_t* __restrict__ idx, int nu,
+                                                               const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ nu,
                                                                float* __restrict__ u, int64_t d) {
     if (block_is_full(d)) cyc_recombine_body<true>(Rm, ldm, b, idx, nu, u, d);
     else cyc_recombine_body<false>(Rm, ldm, b, idx, nu, u, d);
@@ -787,8 +790,8 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
     return hipGetLastError();
 }
 
-hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx, int nu, float* u,
-                                int64_t d, hipStream_t stream) {
+hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx, const int32_t* nu,
+                                float* u, int64_t d, hipStream_t stream) {
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
     allow_large_lds<cyc_recombine_kernel>();
     hipLaunchKernelGGL(cyc_recombine_kernel, grid, block, throttle_lds(2, 0, 0), stream, R, ldm, b, idx, nu, u, d);

@@ -14,6 +14,7 @@ constexpr int kMaxS = 7;              // kernels are specialised for r = 2s+1 <=
 constexpr int kProjectLoads = 8;      // float4 loads per lane per message row in the projection kernel
 constexpr int kMaxNodes = 256;        // DRACO_MAX_NODES
 constexpr int kMaskWords = 4;         // 64-bit words of node flags (kMaxNodes / 64)
+constexpr int kLocateMaxS = 16;       // largest s the on-device locator handles
 
 // Complex numbers in device tables: (re, im) as double2.
 
@@ -41,9 +42,15 @@ int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
 hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, double2* partial,
                               double2* gamma, int P, int64_t d, hipStream_t stream);
-// u <- unpack( sum_{q < nu} b[q] * R[idx[q]] ).
+// phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
+// gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
+// their count in *nu_out.  tau: relative zero threshold for syndromes.
+hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, uint64_t* mask_out,
+                             int32_t* status_out, double2* b_out, int32_t* idx_out, int32_t* nu_out,
+                             hipStream_t stream);
+// u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
 hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx,
-                                int nu, float* u, int64_t d, hipStream_t stream);
+                                const int32_t* nu, float* u, int64_t d, hipStream_t stream);
 
 // dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
 // (bandwidth / counter calibration).

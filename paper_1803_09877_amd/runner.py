@@ -46,10 +46,13 @@ class Case:
         self.R = self.Z.clone()
         synth.apply_attacks(self.R, self.mlen, self.adversaries, self.w.seed)
 
-    def decode(self, stream=None):
-        """-> (mask bool[P], status); the sum lands in self.u[:d]."""
+    def decode(self, stream=None, hostphi: bool = False):
+        """-> (mask bool[P], status); the sum lands in self.u[:d].  hostphi selects the
+        cyclic decoder whose small linear algebra runs on the host."""
         if self.w.code == "rep":
             return self.plan.decode_repetition(self.R, self.u, stream)
+        if hostphi:
+            return self.plan.decode_cyclic_hostphi(self.R, self.f, self.u, stream)
         return self.plan.decode_cyclic(self.R, self.f, self.u, stream)
 
     def step(self):

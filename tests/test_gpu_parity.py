@@ -67,24 +67,26 @@ def run_and_check(w, extra_edit=None, expect_status=0, check_true_sum=None):
         c.receive()
         if extra_edit is not None:
             extra_edit(c)
-        c.u.fill_(float("nan"))
-        mask, status = c.decode()
-        torch.cuda.synchronize()
         R_host = c.R[:, :c.mlen].cpu().numpy()
         uo, mo, so = oracle_decode(c, R_host)
-        assert status == so == expect_status
-        assert np.array_equal(mask, mo)
-        if expect_status == 0:
-            if extra_edit is None:
-                assert np.array_equal(mask, c.expected_mask())
-            ug = c.u[:w.d].cpu().numpy()
-            assert np.isfinite(ug).all()
-            assert rel_l2(ug, uo) <= TOL_SUM[w.code]
-            if check_true_sum is not None:               # Definition 2, end to end, up to the fp32 wire
-                ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
-                assert rel_l2(ug, ref) <= check_true_sum
-        if c.u.numel() > w.d:
-            assert torch.isnan(c.u[w.d:]).all()
+        # the cyclic decoder has two forms: phi and b on the device (default) and on the host
+        for hostphi in ((False, True) if w.code == "cyc" else (False,)):
+            c.u.fill_(float("nan"))
+            mask, status = c.decode(hostphi=hostphi)
+            torch.cuda.synchronize()
+            assert status == so == expect_status, hostphi
+            assert np.array_equal(mask, mo), hostphi
+            if expect_status == 0:
+                if extra_edit is None:
+                    assert np.array_equal(mask, c.expected_mask())
+                ug = c.u[:w.d].cpu().numpy()
+                assert np.isfinite(ug).all()
+                assert rel_l2(ug, uo) <= TOL_SUM[w.code], hostphi
+                if check_true_sum is not None:               # Definition 2, end to end, up to the fp32 wire
+                    ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
+                    assert rel_l2(ug, ref) <= check_true_sum
+            if c.u.numel() > w.d:
+                assert torch.isnan(c.u[w.d:]).all()
         return c
     finally:
         c.close()
@@ -201,6 +203,47 @@ def test_cyc_nonfinite_message_is_reported():
     def edit(c):
         c.R[2, 10] = float("inf")
     run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
+
+
+def test_cyc_async_form_needs_no_host_value():
+    w = wl("cyc", 45, 3, 90_001, ("noise", "signflip", "noise"), "adjacent_pair", sigma=1e-2)
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        mask_dev = torch.zeros(4, dtype=torch.int64, device=c.device)
+        status_dev = torch.full((1,), -7, dtype=torch.int32, device=c.device)
+        c.u.zero_()
+        c.plan.decode_cyclic_async(c.R, c.f, c.u, mask_dev, status_dev)
+        torch.cuda.synchronize()
+        u_async = c.u.clone()
+        m, st = c.decode()
+        assert st == 0 == int(status_dev.item())
+        assert int(mask_dev[0].item()) == int(B.bool_to_mask(m, w.P)[0].astype(np.int64))
+        assert np.array_equal(m, c.expected_mask())
+        assert torch.equal(u_async, c.u)
+        mh, sth = c.decode(hostphi=True)
+        assert sth == 0 and np.array_equal(mh, m)
+        assert rel_l2(c.u[:w.d].cpu().numpy(), u_async[:w.d].cpu().numpy()) <= 1e-6
+    finally:
+        c.close()
+
+
+def test_cyc_large_s_takes_the_host_form():
+    # s = 17 > 16: the default entry point falls back to host phi; the async form refuses
+    w = wl("cyc", 40, 17, 1_001, ("noise", "signflip", "offset"), "any")
+    c = run_and_check(w)
+    c2 = Case(w)
+    try:
+        mask_dev = torch.zeros(4, dtype=torch.int64, device=c2.device)
+        status_dev = torch.zeros(1, dtype=torch.int32, device=c2.device)
+        c2.encode()
+        c2.receive()
+        with pytest.raises(B.DracoError) as e:
+            c2.plan.decode_cyclic_async(c2.R, c2.f, c2.u, mask_dev, status_dev)
+        assert e.value.status == B.EINVAL
+    finally:
+        c2.close()
 
 
 def test_cyc_determinism():
