@@ -36,14 +36,16 @@ MEASURED_TRAFFIC_RATIO = {
 }
 
 
-def algorithmic_bytes(w, mlen, n_honest):
-    """Bytes each kernel must move per launch (every input read once, every output written once)."""
+def algorithmic_bytes(w, mlen, n_honest, wide=False):
+    """Bytes each kernel must move per launch (every input read once, every output written once).
+    On the wide wire every message float is two fp32 words."""
     P, d, h = w.P, w.d, (w.d + 1) // 2
+    words = 2 if wide else 1
     return {
-        "encode": (P * d + P * mlen) * 4,
+        "encode": (P * d + words * P * mlen) * 4,
         "vote": (P * d + d) * 4,
-        "project": (P * mlen + h) * 4,
-        "recombine": (n_honest * mlen + d) * 4,
+        "project": (words * P * mlen + h) * 4,
+        "recombine": (words * n_honest * mlen + d) * 4,
     }
 
 
@@ -100,6 +102,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into the five benchmark workloads (default 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wide", action="store_true", help="cyclic workloads on the two-word (hi+lo) wire")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the P nodes are message slabs in one GPU's HBM); "
@@ -117,7 +120,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = synth.WORKLOADS[args.config]
-    c = Case(w, "cuda:0")
+    c = Case(w, "cuda:0", wide=args.wide)
     c.encode()
     c.receive()
     torch.cuda.synchronize()
@@ -155,7 +158,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    abytes = algorithmic_bytes(w, c.mlen, n_honest)
+    abytes = algorithmic_bytes(w, c.mlen, n_honest, args.wide)
     kernels = {}
     for kind, name in enumerate(KIND_NAMES):
         total_ms, n = c.plan.kernel_time(kind)
@@ -166,7 +169,7 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
     roof = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": kernels[dominant]["GBps"] / HBM_PEAK_GBS, "traffic": None}
-    ratio = MEASURED_TRAFFIC_RATIO.get(w.name, {}).get(dominant)
+    ratio = None if args.wide else MEASURED_TRAFFIC_RATIO.get(w.name, {}).get(dominant)
     if ratio is not None:
         roof["traffic"] = ratio * kernels[dominant]["algorithmic_bytes"]
 
@@ -184,7 +187,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if w.code == "rep" else "f64",
         "data": "synthetic",
-        "config": {"workload": w.name, "code": w.code, "P": w.P, "s": w.s, "d": w.d,
+        "config": {"workload": w.name + ("+wide_wire" if args.wide else ""), "code": w.code, "P": w.P, "s": w.s,
+                   "d": w.d, "wire_words": 2 if args.wide else 1,
                    "adversaries": [[int(j), a] for j, a in c.adversaries],
                    "step": "encode(all nodes) + decode" if w.decode else "encode(all nodes)"},
         "pct_hbm_peak_consumed": consumed / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100,

@@ -108,6 +108,17 @@ int draco_plan_weights(const draco_plan* plan, double* W_host);
 int draco_encode(draco_plan* plan, const float* grads_dev, int64_t ld_g,
                  float* messages_dev, int64_t ld_m, void* stream);
 
+/* Cyclic code with the WIDE wire: every message is sent as two fp32 words per
+ * float, messages_hi = fp32(z) and messages_lo = fp32(z - hi) with z the fp64
+ * value, so that hi + lo carries 48 bits of z.  The entries of W grow like
+ * 1e4-1e5 at P = 45 and the decoder cancels them back to O(1); rounding z to
+ * one fp32 word then leaves a relative error near 3e-4 in the decoded sum,
+ * the wide wire leaves about 1e-9, at twice the message bytes.  Same layout
+ * and conditions as draco_encode for each of the two slabs (one ld_m).
+ * DRACO_EINVAL for the repetition code. */
+int draco_encode_wide(draco_plan* plan, const float* grads_dev, int64_t ld_g,
+                      float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m, void* stream);
+
 /* One node, as a real compute node would run it: node_grads_dev holds ONLY
  * that node's r = 2s+1 assigned gradients, [r][ld_g], in assignment order
  * (repetition: ascending k within the group; cyclic: k = node, node+1, ...,
@@ -169,6 +180,17 @@ int draco_decode_cyclic_async(draco_plan* plan, const float* messages_dev, int64
 int draco_decode_cyclic_hostphi(draco_plan* plan, const float* messages_dev, int64_t ld_m,
                                 const float* f_dev, float* sum_dev, uint64_t* mask_host,
                                 void* stream);
+
+/* D^Cyc on the wide wire of draco_encode_wide: the received message of node j
+ * is messages_hi[j] + messages_lo[j] (added exactly in fp64).  Otherwise as
+ * draco_decode_cyclic / draco_decode_cyclic_async. */
+int draco_decode_cyclic_wide(draco_plan* plan, const float* messages_hi_dev,
+                             const float* messages_lo_dev, int64_t ld_m, const float* f_dev,
+                             float* sum_dev, uint64_t* mask_host, void* stream);
+int draco_decode_cyclic_wide_async(draco_plan* plan, const float* messages_hi_dev,
+                                   const float* messages_lo_dev, int64_t ld_m, const float* f_dev,
+                                   float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
+                                   void* stream);
 
 /* ---- host-side pieces of D^Cyc, exposed for inspection and testing ----- */
 

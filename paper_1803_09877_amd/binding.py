@@ -31,7 +31,8 @@ EXPORTS = [
     "draco_plan_create", "draco_plan_prepare", "draco_plan_destroy", "draco_message_len",
     "draco_plan_assign", "draco_plan_weights", "draco_encode", "draco_encode_node",
     "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
-    "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi",
+    "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi", "draco_encode_wide",
+    "draco_decode_cyclic_wide", "draco_decode_cyclic_wide_async",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe",
@@ -94,6 +95,12 @@ def lib() -> ctypes.CDLL:
     L.draco_decode_cyclic_hostphi.restype = i32
     L.draco_decode_cyclic_async.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     L.draco_decode_cyclic_async.restype = i32
+    L.draco_encode_wide.argtypes = [vp, vp, i64, vp, vp, i64, vp]
+    L.draco_encode_wide.restype = i32
+    L.draco_decode_cyclic_wide.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
+    L.draco_decode_cyclic_wide.restype = i32
+    L.draco_decode_cyclic_wide_async.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
+    L.draco_decode_cyclic_wide_async.restype = i32
     L.draco_cyclic_locate.argtypes = [vp, vp, vp, vp]
     L.draco_cyclic_locate.restype = i32
     L.draco_cyclic_recombination_vector.argtypes = [vp, vp, vp]
@@ -244,6 +251,25 @@ class Plan:
         _check(lib().draco_decode_cyclic_async(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
                                                out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                _stream_ptr(stream)))
+
+    def encode_wide(self, grads, hi, lo, stream=None) -> None:
+        assert hi.stride(0) == lo.stride(0)
+        _check(lib().draco_encode_wide(self._h, grads.data_ptr(), grads.stride(0), hi.data_ptr(), lo.data_ptr(),
+                                       hi.stride(0), _stream_ptr(stream)))
+
+    def decode_cyclic_wide(self, hi, lo, f, out_sum, stream=None):
+        assert hi.stride(0) == lo.stride(0)
+        words = np.zeros(mask_words(self.P), dtype=np.uint64)
+        status = lib().draco_decode_cyclic_wide(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), f.data_ptr(),
+                                                out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
+        _check(status)
+        return mask_to_bool(words, self.P), status
+
+    def decode_cyclic_wide_async(self, hi, lo, f, out_sum, mask_dev, status_dev, stream=None) -> None:
+        assert hi.stride(0) == lo.stride(0)
+        _check(lib().draco_decode_cyclic_wide_async(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), f.data_ptr(),
+                                                    out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
+                                                    _stream_ptr(stream)))
 
     def set_timing(self, max_records: int) -> None:
         _check(lib().draco_plan_set_timing(self._h, max_records))

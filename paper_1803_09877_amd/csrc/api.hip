@@ -222,22 +222,42 @@ int draco_plan_weights(const draco_plan* p, double* W) {
     return DRACO_OK;
 }
 
-int draco_encode(draco_plan* p, const float* grads_dev, int64_t ld_g, float* messages_dev, int64_t ld_m,
-                 void* stream) {
+namespace {
+
+int encode_impl(draco_plan* p, const float* grads_dev, int64_t ld_g, float* hi_dev, float* lo_dev, bool wide,
+                int64_t ld_m, void* stream) {
     if (p == nullptr) return DRACO_EINVAL;
+    if (wide && p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
     int rc = check_slab(grads_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
-    rc = check_slab(messages_dev, ld_m, message_len(p));
+    rc = check_slab(hi_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
+    if (wide) {
+        rc = check_slab(lo_dev, ld_m, message_len(p));
+        if (rc != DRACO_OK) return rc;
+    }
     rc = prepare(p);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Timed timed(p, kEncode, st);
     if (p->code == DRACO_CODE_REPETITION)
-        HIP_TRY(launch_encode_rep(grads_dev, ld_g, messages_dev, ld_m, p->P, p->s, p->d, st));
+        HIP_TRY(launch_encode_rep(grads_dev, ld_g, hi_dev, ld_m, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, messages_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
+        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, ld_m, p->coef_dev, p->P, p->s,
+                                  p->d, st));
     return DRACO_OK;
+}
+
+}  // namespace
+
+int draco_encode(draco_plan* p, const float* grads_dev, int64_t ld_g, float* messages_dev, int64_t ld_m,
+                 void* stream) {
+    return encode_impl(p, grads_dev, ld_g, messages_dev, nullptr, false, ld_m, stream);
+}
+
+int draco_encode_wide(draco_plan* p, const float* grads_dev, int64_t ld_g, float* messages_hi_dev,
+                      float* messages_lo_dev, int64_t ld_m, void* stream) {
+    return encode_impl(p, grads_dev, ld_g, messages_hi_dev, messages_lo_dev, true, ld_m, stream);
 }
 
 int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
@@ -254,7 +274,8 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_node(node_grads_dev, ld_g, message_dev, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, p->coef_dev, node, p->P, p->s, p->d,
+                                       st));
     return DRACO_OK;
 }
 
@@ -296,48 +317,54 @@ int draco_decode_repetition(draco_plan* p, const float* messages_dev, int64_t ld
 
 namespace {
 
-int check_cyclic_args(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev) {
+int check_cyclic_args(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
+                      const float* f_dev, float* sum_dev) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
     if (f_dev == nullptr || sum_dev == nullptr) return DRACO_EINVAL;
-    const int rc = check_slab(messages_dev, ld_m, message_len(p));
+    int rc = check_slab(hi_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
+    if (wide) {
+        rc = check_slab(lo_dev, ld_m, message_len(p));
+        if (rc != DRACO_OK) return rc;
+    }
     if (!aligned16(sum_dev) || (reinterpret_cast<uintptr_t>(f_dev) & 3u) != 0) return DRACO_EALIGN;
     return prepare(p);
 }
 
-}  // namespace
-
-int draco_decode_cyclic_async(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
-                              float* sum_dev, uint64_t* mask_dev, int32_t* status_dev, void* stream) {
+int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
+                             const float* f_dev, float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
+                             void* stream) {
     if (mask_dev == nullptr || status_dev == nullptr) return DRACO_EINVAL;
-    int rc = check_cyclic_args(p, messages_dev, ld_m, f_dev, sum_dev);
+    int rc = check_cyclic_args(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev);
     if (rc != DRACO_OK) return rc;
     if (p->s > kLocateMaxS) return DRACO_EINVAL;
+    const float* lo = wide ? lo_dev : nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(messages_dev, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
     }
     HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, mask_dev, status_dev, p->b_dev, p->idx_dev, p->idx_dev + P,
                               st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
     }
     return DRACO_OK;
 }
 
-int draco_decode_cyclic_hostphi(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
-                                float* sum_dev, uint64_t* mask_host, void* stream) {
+int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
+                               const float* f_dev, float* sum_dev, uint64_t* mask_host, void* stream) {
     if (mask_host == nullptr) return DRACO_EINVAL;
-    int rc = check_cyclic_args(p, messages_dev, ld_m, f_dev, sum_dev);
+    int rc = check_cyclic_args(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev);
     if (rc != DRACO_OK) return rc;
+    const float* lo = wide ? lo_dev : nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P, s = p->s;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(messages_dev, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -362,19 +389,20 @@ int draco_decode_cyclic_hostphi(draco_plan* p, const float* messages_dev, int64_
     HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, (P + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(messages_dev, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
     }
     HIP_TRY(hipStreamSynchronize(st));
     return located ? DRACO_OK : DRACO_LOCATE_FAILED;
 }
 
-int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev,
-                        uint64_t* mask_host, void* stream) {
+int decode_cyclic_impl(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
+                       const float* f_dev, float* sum_dev, uint64_t* mask_host, void* stream) {
     if (p == nullptr || mask_host == nullptr) return DRACO_EINVAL;
-    if (p->s > kLocateMaxS) return draco_decode_cyclic_hostphi(p, messages_dev, ld_m, f_dev, sum_dev, mask_host, stream);
+    if (p->s > kLocateMaxS)
+        return decode_cyclic_hostphi_impl(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev, mask_host, stream);
     int rc = prepare(p);
     if (rc != DRACO_OK) return rc;
-    rc = draco_decode_cyclic_async(p, messages_dev, ld_m, f_dev, sum_dev, p->mask_dev, p->status_dev, stream);
+    rc = decode_cyclic_async_impl(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev, p->mask_dev, p->status_dev, stream);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int words = (p->P + 63) / 64;
@@ -385,6 +413,36 @@ int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, 
     int32_t status;
     std::memcpy(&status, p->mask_pin + kMaskWords, sizeof(status));
     return status;
+}
+
+}  // namespace
+
+int draco_decode_cyclic(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev, float* sum_dev,
+                        uint64_t* mask_host, void* stream) {
+    return decode_cyclic_impl(p, messages_dev, nullptr, false, ld_m, f_dev, sum_dev, mask_host, stream);
+}
+
+int draco_decode_cyclic_async(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
+                              float* sum_dev, uint64_t* mask_dev, int32_t* status_dev, void* stream) {
+    return decode_cyclic_async_impl(p, messages_dev, nullptr, false, ld_m, f_dev, sum_dev, mask_dev, status_dev,
+                                    stream);
+}
+
+int draco_decode_cyclic_hostphi(draco_plan* p, const float* messages_dev, int64_t ld_m, const float* f_dev,
+                                float* sum_dev, uint64_t* mask_host, void* stream) {
+    return decode_cyclic_hostphi_impl(p, messages_dev, nullptr, false, ld_m, f_dev, sum_dev, mask_host, stream);
+}
+
+int draco_decode_cyclic_wide(draco_plan* p, const float* messages_hi_dev, const float* messages_lo_dev, int64_t ld_m,
+                             const float* f_dev, float* sum_dev, uint64_t* mask_host, void* stream) {
+    return decode_cyclic_impl(p, messages_hi_dev, messages_lo_dev, true, ld_m, f_dev, sum_dev, mask_host, stream);
+}
+
+int draco_decode_cyclic_wide_async(draco_plan* p, const float* messages_hi_dev, const float* messages_lo_dev,
+                                   int64_t ld_m, const float* f_dev, float* sum_dev, uint64_t* mask_dev,
+                                   int32_t* status_dev, void* stream) {
+    return decode_cyclic_async_impl(p, messages_hi_dev, messages_lo_dev, true, ld_m, f_dev, sum_dev, mask_dev,
+                                    status_dev, stream);
 }
 
 int draco_cyclic_locate(const draco_plan* p, const double* gamma_host, uint64_t* mask_host, double* t_host) {

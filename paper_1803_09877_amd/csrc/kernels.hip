@@ -363,9 +363,10 @@ __device__ __forceinline__ void cmac(double tr, double ti, double x, double y, d
 // rows 0..2s-1, needed again by the last 2s nodes, are parked in LDS (each lane
 // reads back only what it wrote: no barrier).  Rows are fetched NB-1 rounds of
 // R = 2s+1 ahead of the arithmetic (a ring of NB register buffers).
-template <int S, int NB, bool FULL>
+template <int S, int NB, bool FULL, bool WIDE>
 __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int64_t ldg, float* __restrict__ Z,
-                                                int64_t ldm, const double2* __restrict__ coef, int P, int64_t d,
+                                                float* __restrict__ Zlo, int64_t ldm,
+                                                const double2* __restrict__ coef, int P, int64_t d,
                                                 float4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
@@ -408,8 +409,13 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
                     cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
                     cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
                 }
-                stx<FULL>(Z + (int64_t)n * ldm + c0,
-                          make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if constexpr (WIDE) {  // second word of the wide wire: what the first rounding lost
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
             }
         }
     };
@@ -437,13 +443,14 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
     }
 }
 
-template <int S, int NB>
+template <int S, int NB, bool WIDE>
 __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
-                                                            float* __restrict__ Z, int64_t ldm,
-                                                            const double2* __restrict__ coef, int P, int64_t d) {
+                                                            float* __restrict__ Z, float* __restrict__ Zlo,
+                                                            int64_t ldm, const double2* __restrict__ coef, int P,
+                                                            int64_t d) {
     extern __shared__ float4 head[];  // [2S][kBlock]
-    if (block_is_full(d)) encode_cyc_body<S, NB, true>(G, ldg, Z, ldm, coef, P, d, head);
-    else encode_cyc_body<S, NB, false>(G, ldg, Z, ldm, coef, P, d, head);
+    if (block_is_full(d)) encode_cyc_body<S, NB, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    else encode_cyc_body<S, NB, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
 }
 
 // One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
@@ -452,7 +459,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
 // used (the all-node path for r > 2*kMaxS+1).  Same operation order as the
 // all-node kernel, so results are bit-identical.
 __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
-                                                                 float* __restrict__ z,
+                                                                 float* __restrict__ z, float* __restrict__ zlo,
                                                                  const double2* __restrict__ cn, int node, int P,
                                                                  int r, int wrap_rows, int64_t d) {
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
@@ -472,13 +479,21 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
     const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
     if (nout == 4) st4(z + c0, out);
     else st4_partial(z + c0, out, nout);
+    if (zlo != nullptr) {
+        const float4 lo = make_float4((float)(are0 - (double)out.x), (float)(aim0 - (double)out.y),
+                                      (float)(are1 - (double)out.z), (float)(aim1 - (double)out.w));
+        if (nout == 4) st4(zlo + c0, lo);
+        else st4_partial(zlo + c0, lo, nout);
+    }
 }
 
 // phi step 1: gamma'_j = sum_i f_i * r_j[i].  A workgroup owns a tile of
 // kBlock*kProjectLoads float4 (two complex numbers each) of every row, keeps
 // its slice of f in registers, and for each row forms a per-wavefront sum in
 // fp64; the four wavefront sums are added in fixed order and stored per tile.
-__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm, int64_t ldm,
+template <bool WIDE>
+__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
+                                                             const float* __restrict__ Rlo, int64_t ldm,
                                                              const float* __restrict__ f,
                                                              double2* __restrict__ partial, int P, int64_t d) {
     constexpr int K = kProjectLoads;
@@ -508,12 +523,31 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
             for (int k = 0; k < K; ++k) x[k] = ld4_partial(row + (int64_t)k * kBlock * 4, nflt[k]);
         }
         double are = 0.0, aim = 0.0;
+        if constexpr (WIDE) {  // wire value = hi + lo, exact in fp64
+            const float* rowl = Rlo + (int64_t)j * ldm + q0 * 4;
+            float4 xl[K];
+            if (tile_full) {
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            are = fma(f0[k], (double)x[k].x, are);
-            aim = fma(f0[k], (double)x[k].y, aim);
-            are = fma(f1[k], (double)x[k].z, are);
-            aim = fma(f1[k], (double)x[k].w, aim);
+                for (int k = 0; k < K; ++k) xl[k] = ld4(rowl + (int64_t)k * kBlock * 4);
+            } else {
+#pragma unroll
+                for (int k = 0; k < K; ++k) xl[k] = ld4_partial(rowl + (int64_t)k * kBlock * 4, nflt[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                are = fma(f0[k], (double)x[k].x + (double)xl[k].x, are);
+                aim = fma(f0[k], (double)x[k].y + (double)xl[k].y, aim);
+                are = fma(f1[k], (double)x[k].z + (double)xl[k].z, are);
+                aim = fma(f1[k], (double)x[k].w + (double)xl[k].w, aim);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                are = fma(f0[k], (double)x[k].x, are);
+                aim = fma(f0[k], (double)x[k].y, aim);
+                are = fma(f1[k], (double)x[k].z, are);
+                aim = fma(f1[k], (double)x[k].w, aim);
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -560,8 +594,9 @@ __global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double
 
 // u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
 // ascending node order, fp64 accumulation, one rounding to fp32.
-template <bool FULL>
-__device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, int64_t ldm,
+template <bool FULL, bool WIDE>
+__device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
+                                                   int64_t ldm,
                                                    const double2* __restrict__ b, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ nu_ptr, float* __restrict__ u,
                                                    int64_t d) {
@@ -574,29 +609,40 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
     const int nout = FULL ? 4 : clamp4(d - c0);
     double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
     for (int q0 = 0; q0 < nu; q0 += UN) {
-        float4 x[UN];
+        float4 x[UN], xl[WIDE ? UN : 1];
 #pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if (q0 + i < nu) x[i] = ldx<FULL>(Rm + (int64_t)idx[q0 + i] * ldm + c0, nin);
+        for (int i = 0; i < UN; ++i) {
+            if (q0 + i < nu) {
+                x[i] = ldx<FULL>(Rm + (int64_t)idx[q0 + i] * ldm + c0, nin);
+                if constexpr (WIDE) xl[i] = ldx<FULL>(Rlo + (int64_t)idx[q0 + i] * ldm + c0, nin);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
             if (q0 + i < nu) {
                 const double br = b[q0 + i].x, bi = b[q0 + i].y;
-                cmac(br, bi, (double)x[i].x, (double)x[i].y, are0, aim0);
-                cmac(br, bi, (double)x[i].z, (double)x[i].w, are1, aim1);
+                if constexpr (WIDE) {
+                    cmac(br, bi, (double)x[i].x + (double)xl[i].x, (double)x[i].y + (double)xl[i].y, are0, aim0);
+                    cmac(br, bi, (double)x[i].z + (double)xl[i].z, (double)x[i].w + (double)xl[i].w, are1, aim1);
+                } else {
+                    cmac(br, bi, (double)x[i].x, (double)x[i].y, are0, aim0);
+                    cmac(br, bi, (double)x[i].z, (double)x[i].w, are1, aim1);
+                }
             }
         }
     }
     stx<FULL>(u + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
 }
 
-__global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm, int64_t ldm,
+template <bool WIDE>
+__global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm,
+                                                               const float* __restrict__ Rlo, int64_t ldm,
                                                                const double2* __restrict__ b,
                                                                const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ nu,
                                                                float* __restrict__ u, int64_t d) {
-    if (block_is_full(d)) cyc_recombine_body<true>(Rm, ldm, b, idx, nu, u, d);
-    else cyc_recombine_body<false>(Rm, ldm, b, idx, nu, u, d);
+    if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
+    else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
 }
 
 // Plain copy of a [rows][ld] slab (row_len floats used per row) with the access
@@ -730,38 +776,45 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef, int P, int s,
-                             int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm, const double2* coef, int P,
+                             int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
     // One workgroup per CU with rows fetched two rounds ahead (measured best: 5.7 TB/s at
     // P=45, s=3 against 5.45 with two workgroups per CU); one round ahead for wide windows.
     const size_t lds = throttle_lds(1, 0, (size_t)2 * s * kBlock * sizeof(float4));
     const int r = 2 * s + 1;
-#define DRACO_CASE(S)                                                                                          \
-    case S: {                                                                                                  \
-        constexpr int NB = (S <= 3) ? 3 : 2;                                                                   \
-        allow_large_lds<encode_cyc_kernel<S, NB>>();                                                           \
-        hipLaunchKernelGGL((encode_cyc_kernel<S, NB>), grid, block, lds, stream, G, ldg, Z, ldm, coef, P, d);  \
+#define DRACO_CASE(S)                                                                                               \
+    case S: {                                                                                                       \
+        constexpr int NB = (S <= 3) ? 3 : 2;                                                                        \
+        if (Zlo == nullptr) {                                                                                       \
+            allow_large_lds<encode_cyc_kernel<S, NB, false>>();                                                     \
+            hipLaunchKernelGGL((encode_cyc_kernel<S, NB, false>), grid, block, lds, stream, G, ldg, Z, Zlo, ldm,    \
+                               coef, P, d);                                                                         \
+        } else {                                                                                                    \
+            allow_large_lds<encode_cyc_kernel<S, NB, true>>();                                                      \
+            hipLaunchKernelGGL((encode_cyc_kernel<S, NB, true>), grid, block, lds, stream, G, ldg, Z, Zlo, ldm,     \
+                               coef, P, d);                                                                         \
+        }                                                                                                           \
     } break;
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   coef + (int64_t)j * r, j, P, r, P, d);
+                                   Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node, int P, int s,
-                                  int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef, int node,
+                                  int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
     const int r = 2 * s + 1;
-    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, coef + (int64_t)node * r, node, P,
-                       r, 0, d);
+    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, coef + (int64_t)node * r, node,
+                       P, r, 0, d);
     return hipGetLastError();
 }
 
@@ -772,10 +825,15 @@ int64_t project_tiles(int64_t d) {
     return (nvec + per - 1) / per;
 }
 
-hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, double2* partial, double2* gamma, int P,
-                              int64_t d, hipStream_t stream) {
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, double2* partial,
+                              double2* gamma, int P, int64_t d, hipStream_t stream) {
     const int64_t tiles = project_tiles(d);
-    hipLaunchKernelGGL(cyc_project_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, ldm, f, partial, P, d);
+    if (Rlo == nullptr)
+        hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           partial, P, d);
+    else
+        hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           partial, P, d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
@@ -790,11 +848,18 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
     return hipGetLastError();
 }
 
-hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx, const int32_t* nu,
-                                float* u, int64_t d, hipStream_t stream) {
+hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
+                                const int32_t* nu, float* u, int64_t d, hipStream_t stream) {
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
-    allow_large_lds<cyc_recombine_kernel>();
-    hipLaunchKernelGGL(cyc_recombine_kernel, grid, block, throttle_lds(2, 0, 0), stream, R, ldm, b, idx, nu, u, d);
+    if (Rlo == nullptr) {
+        allow_large_lds<cyc_recombine_kernel<false>>();
+        hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+                           nu, u, d);
+    } else {
+        allow_large_lds<cyc_recombine_kernel<true>>();
+        hipLaunchKernelGGL(cyc_recombine_kernel<true>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+                           nu, u, d);
+    }
     return hipGetLastError();
 }
 

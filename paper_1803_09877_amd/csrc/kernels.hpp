@@ -32,16 +32,17 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
 
 // ---- cyclic code ----
 // coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
-                             int P, int s, int64_t d, hipStream_t stream);
+// Zlo / zlo / Rlo below: second word of the wide wire (message = hi + lo), or nullptr.
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm,
+                             const double2* coef, int P, int s, int64_t d, hipStream_t stream);
 // Gn holds only the node's 2s+1 gradients, in assignment order.
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, const double2* coef,
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef,
                                   int node, int P, int s, int64_t d, hipStream_t stream);
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
 int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
-hipError_t launch_cyc_project(const float* R, int64_t ldm, const float* f, double2* partial,
-                              double2* gamma, int P, int64_t d, hipStream_t stream);
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f,
+                              double2* partial, double2* gamma, int P, int64_t d, hipStream_t stream);
 // phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
 // gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
 // their count in *nu_out.  tau: relative zero threshold for syndromes.
@@ -49,8 +50,9 @@ hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, uin
                              int32_t* status_out, double2* b_out, int32_t* idx_out, int32_t* nu_out,
                              hipStream_t stream);
 // u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
-hipError_t launch_cyc_recombine(const float* R, int64_t ldm, const double2* b, const int32_t* idx,
-                                const int32_t* nu, float* u, int64_t d, hipStream_t stream);
+hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b,
+                                const int32_t* idx, const int32_t* nu, float* u, int64_t d,
+                                hipStream_t stream);
 
 // dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
 // (bandwidth / counter calibration).

@@ -20,8 +20,11 @@ class Case:
     f  [ceil(d/2)] phi's random projection vector (cyclic code)
     """
 
-    def __init__(self, w: synth.Workload, device: str = "cuda:0"):
+    def __init__(self, w: synth.Workload, device: str = "cuda:0", wide: bool = False):
+        """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word)."""
         self.w = w
+        self.wide = wide
+        assert not (wide and w.code != "cyc")
         self.device = torch.device(device)
         code = B.CODE_REPETITION if w.code == "rep" else B.CODE_CYCLIC
         self.plan = B.Plan(code, w.P, w.s, w.d)
@@ -31,6 +34,8 @@ class Case:
         self.G = synth.make_gradients(w.P, w.d, w.sigma, w.seed, device=self.device, ld=self.ld_g)
         self.Z = torch.zeros((w.P, self.ld_m), dtype=torch.float32, device=self.device)
         self.R = None
+        self.Zlo = torch.zeros_like(self.Z) if wide else None
+        self.Rlo = None
         self.u = torch.zeros(synth.padded_len(w.d), dtype=torch.float32, device=self.device)
         self.f = None
         if w.code == "cyc":
@@ -39,11 +44,17 @@ class Case:
         self.plan.prepare()
 
     def encode(self, stream=None) -> None:
-        self.plan.encode(self.G, self.Z, stream)
+        if self.wide:
+            self.plan.encode_wide(self.G, self.Z, self.Zlo, stream)
+        else:
+            self.plan.encode(self.G, self.Z, stream)
 
     def receive(self) -> None:
-        """R <- Z, then the adversaries rewrite their rows (outside the hot path)."""
+        """R <- Z, then the adversaries rewrite their rows (outside the hot path).
+        On the wide wire they edit the first word; the second stays as sent."""
         self.R = self.Z.clone()
+        if self.wide:
+            self.Rlo = self.Zlo.clone()
         synth.apply_attacks(self.R, self.mlen, self.adversaries, self.w.seed)
 
     def decode(self, stream=None, hostphi: bool = False):
@@ -51,6 +62,8 @@ class Case:
         cyclic decoder whose small linear algebra runs on the host."""
         if self.w.code == "rep":
             return self.plan.decode_repetition(self.R, self.u, stream)
+        if self.wide:
+            return self.plan.decode_cyclic_wide(self.R, self.Rlo, self.f, self.u, stream)
         if hostphi:
             return self.plan.decode_cyclic_hostphi(self.R, self.f, self.u, stream)
         return self.plan.decode_cyclic(self.R, self.f, self.u, stream)

@@ -107,3 +107,29 @@ def test_full_size_workload(idx):
             assert err <= (1e-5 if w.P == 15 else 1e-3)
     finally:
         c.close()
+
+
+def test_full_size_cyclic_wide_wire_end_to_end():
+    """Config 4 (P=45, s=3, d=25.6M) on the two-word wire: mask exact and the
+    decoded sum within 1e-6 of the TRUE gradient sum (the one-word wire's floor
+    is 3e-4 here)."""
+    w = synth.WORKLOADS[4]
+    print(f"full-size wide {w.name}", flush=True)
+    c = Case(w, wide=True)
+    try:
+        c.encode()
+        c.receive()
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        for a, b in windows(w.d, w.code):
+            Zo = o.encode_cyclic(c.G[:, a:b].cpu().numpy(), w.s)
+            Zw = (c.Z[:, a:a + Zo.shape[1]].double() + c.Zlo[:, a:a + Zo.shape[1]].double()).cpu().numpy()
+            for j in range(w.P):
+                assert rel_l2(Zw[j], Zo[j]) <= 1e-12
+        ref = c.G[:, :w.d].double().sum(0)
+        err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
+        print(f"   end-to-end rel-L2 vs true sum (wide wire): {err:.3e}", flush=True)
+        assert err <= 1e-6
+    finally:
+        c.close()

@@ -246,6 +246,50 @@ def test_cyc_large_s_takes_the_host_form():
         c2.close()
 
 
+@pytest.mark.parametrize("P,s,d,attacks,placement,sigma", [
+    (15, 2, 40_003, ("offset", "signflip"), "adjacent_pair", 1.0),
+    (45, 3, 70_001, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2),
+    (45, 3, 70_002, (), "any", 1e-2),
+    (45, 5, 30_000, ("noise", "signflip", "offset", "constant", "noise"), "any", 1e-2),
+    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0),          # generic encoder path
+    (40, 17, 1_001, ("noise", "signflip"), "any", 1.0),                  # host phi fallback
+])
+def test_cyc_wide_wire(P, s, d, attacks, placement, sigma):
+    """Two-word wire: hi + lo carries the fp64 message to 48 bits, so the decoded
+    sum meets Definition 2 END TO END (against the true gradient sum) far inside
+    the 1e-4 bar also at P = 45, where the one-word wire cannot."""
+    w = wl("cyc", P, s, d, attacks, placement, sigma)
+    print(f"wide case {w.name} attacks={w.attacks} seed={w.seed}", flush=True)
+    c = Case(w, wide=True)
+    try:
+        c.Z.fill_(float("nan"))
+        c.Zlo.fill_(float("nan"))
+        c.encode()
+        torch.cuda.synchronize()
+        Zw = c.Z[:, :c.mlen].double().cpu().numpy() + c.Zlo[:, :c.mlen].double().cpu().numpy()
+        Zo = o.encode_cyclic(c.G[:, :w.d].cpu().numpy(), w.s)
+        for j in range(P):
+            assert rel_l2(Zw[j], Zo[j]) <= 1e-12, j
+        assert torch.equal(c.Z[:, :c.mlen], torch.from_numpy(Zo.astype(np.float32)).to(c.device)) or \
+            rel_l2(c.Z[:, :c.mlen].cpu().numpy(), Zo) <= 1e-7
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        Rw = c.R[:, :c.mlen].double().cpu().numpy() + c.Rlo[:, :c.mlen].double().cpu().numpy()
+        uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), w.s, w.d)
+        assert status == so == 0
+        assert np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
+        ug = c.u[:w.d].cpu().numpy()
+        assert rel_l2(ug, uo) <= 1e-6
+        ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
+        assert rel_l2(ug, ref) <= 1e-6                                   # fp32 output rounding is 6e-8
+        if c.u.numel() > w.d:
+            assert torch.isnan(c.u[w.d:]).all()
+    finally:
+        c.close()
+
+
 def test_cyc_determinism():
     w = wl("cyc", 15, 2, 100_003, ("offset", "offset"))
     c = Case(w)
