@@ -66,6 +66,8 @@ std::vector<cplx_t> solve_truncated(const Mat& H, const std::vector<cplx_t>& rhs
                 }
                 const real_t ag = std::abs(g);
                 if (ag == 0 || ag <= eps * std::sqrt(alpha * beta)) continue;
+                // columns that both end below the cutoff are dropped from the solution
+                if (alpha <= cutoff * cutoff && beta <= cutoff * cutoff) continue;
                 rotated = true;
                 const cplx_t ph = std::conj(g / ag);  // turns column q so that <a_p, a_q> is real >= 0
                 const real_t zeta = (beta - alpha) / (2 * ag);

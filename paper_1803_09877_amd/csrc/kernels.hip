@@ -711,11 +711,12 @@ static void allow_large_lds(size_t static_bytes = 0) {
     if (e != hipSuccess) (void)hipGetLastError();  // the launch itself reports a request that does not fit
 }
 
-// Groups fetched per round: keeps (r * groups) 16-byte loads in flight per lane.
-#define DRACO_REP_DISPATCH(KERNEL, ...)                                                    \
+// Groups fetched per round (GU0 for r = 1, GU1 for r = 3, one group otherwise):
+// keeps r * groups 16-byte loads in flight per lane.
+#define DRACO_REP_DISPATCH(KERNEL, GU0, GU1, ...)                                          \
     switch (s) {                                                                           \
-        case 0: KERNEL(1, 8, __VA_ARGS__); break;                                          \
-        case 1: KERNEL(3, 2, __VA_ARGS__); break;                                          \
+        case 0: KERNEL(1, GU0, __VA_ARGS__); break;                                        \
+        case 1: KERNEL(3, GU1, __VA_ARGS__); break;                                        \
         case 2: KERNEL(5, 1, __VA_ARGS__); break;                                          \
         case 3: KERNEL(7, 1, __VA_ARGS__); break;                                          \
         case 4: KERNEL(9, 1, __VA_ARGS__); break;                                          \
@@ -736,7 +737,7 @@ hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm,
         hipLaunchKernelGGL((encode_rep_kernel<R, GU>), grid, block, throttle_lds(BPC, 0, 0), stream, G, ldg, \
                            Z, ldm, groups, d);                                                               \
     }
-    DRACO_REP_DISPATCH(DRACO_LAUNCH, 1)
+    DRACO_REP_DISPATCH(DRACO_LAUNCH, 8, 2, 1)
 #undef DRACO_LAUNCH
     if (generic) hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, G, ldg, Z, ldm, groups, r, r, d);
     return hipGetLastError();
@@ -761,7 +762,7 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
                            throttle_lds(BPC, kMaskWords * sizeof(unsigned long long), 0), stream, R, ldm, u,    \
                            flags, groups, d);                                                                   \
     }
-    DRACO_REP_DISPATCH(DRACO_LAUNCH, 2)
+    DRACO_REP_DISPATCH(DRACO_LAUNCH, 4, 1, 2)
 #undef DRACO_LAUNCH
     if (generic) {
         const dim3 g1((unsigned)((d + kBlock - 1) / kBlock));
@@ -776,35 +777,47 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
     return hipGetLastError();
 }
 
+template <int S, int NB>
+static void launch_encode_cyc_one(dim3 grid, size_t lds, hipStream_t stream, const float* G, int64_t ldg, float* Z,
+                                  float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d) {
+    if (Zlo == nullptr) {
+        allow_large_lds<encode_cyc_kernel<S, NB, false>>();
+        hipLaunchKernelGGL((encode_cyc_kernel<S, NB, false>), grid, dim3(kBlock), lds, stream, G, ldg, Z, Zlo, ldm, coef,
+                           P, d);
+    } else {
+        allow_large_lds<encode_cyc_kernel<S, NB, true>>();
+        hipLaunchKernelGGL((encode_cyc_kernel<S, NB, true>), grid, dim3(kBlock), lds, stream, G, ldg, Z, Zlo, ldm, coef,
+                           P, d);
+    }
+}
+
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm, const double2* coef, int P,
                              int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
-    // One workgroup per CU with rows fetched two rounds ahead (measured best: 5.7 TB/s at
-    // P=45, s=3 against 5.45 with two workgroups per CU); one round ahead for wide windows.
-    const size_t lds = throttle_lds(1, 0, (size_t)2 * s * kBlock * sizeof(float4));
     const int r = 2 * s + 1;
-#define DRACO_CASE(S)                                                                                               \
-    case S: {                                                                                                       \
-        constexpr int NB = (S <= 3) ? 3 : 2;                                                                        \
-        if (Zlo == nullptr) {                                                                                       \
-            allow_large_lds<encode_cyc_kernel<S, NB, false>>();                                                     \
-            hipLaunchKernelGGL((encode_cyc_kernel<S, NB, false>), grid, block, lds, stream, G, ldg, Z, Zlo, ldm,    \
-                               coef, P, d);                                                                         \
-        } else {                                                                                                    \
-            allow_large_lds<encode_cyc_kernel<S, NB, true>>();                                                      \
-            hipLaunchKernelGGL((encode_cyc_kernel<S, NB, true>), grid, block, lds, stream, G, ldg, Z, Zlo, ldm,     \
-                               coef, P, d);                                                                         \
-        }                                                                                                           \
-    } break;
+    // Launch shape from a sweep on MI355X.  Narrow windows on many rows run best with ONE
+    // workgroup per CU and rows fetched two rounds ahead (5.7-5.8 TB/s at P = 45 against
+    // 5.5 with two workgroups); few rows (short workgroup lifetimes) or wide windows (more
+    // fp64 work per byte) need two workgroups per CU to overlap.
+    const bool one_per_cu = s <= 3 && P >= 32;
+    const size_t lds = throttle_lds(one_per_cu ? 1 : 2, 0, (size_t)2 * s * kBlock * sizeof(float4));
+#define DRACO_GO(S, NB) launch_encode_cyc_one<S, NB>(grid, lds, stream, G, ldg, Z, Zlo, ldm, coef, P, d)
     switch (s) {
-        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        case 0: DRACO_GO(0, 3); break;
+        case 1: if (one_per_cu) DRACO_GO(1, 3); else DRACO_GO(1, 1); break;
+        case 2: if (one_per_cu) DRACO_GO(2, 3); else DRACO_GO(2, 1); break;
+        case 3: DRACO_GO(3, 3); break;
+        case 4: DRACO_GO(4, 3); break;
+        case 5: DRACO_GO(5, 3); break;
+        case 6: DRACO_GO(6, 2); break;
+        case 7: DRACO_GO(7, 2); break;
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
                                    Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, d);
     }
-#undef DRACO_CASE
+#undef DRACO_GO
     return hipGetLastError();
 }
 

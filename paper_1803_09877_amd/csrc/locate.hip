@@ -11,22 +11,34 @@
 // products are wavefront reductions.  Limits: P <= 256, s <= kLocateMaxS.
 #include "kernels.hpp"
 
+// Phase marker for profiling builds (defined by a harness that includes this file); no-op otherwise.
+#ifndef DRACO_STAMP
+#define DRACO_STAMP(i)
+#endif
+
 namespace draco {
 
 namespace {
 
 constexpr int kW = 64;  // one wavefront
 
+// Butterfly reductions over aligned groups of N lanes (every lane of a group gets the
+// group's result).  The dense algebra only populates lanes < 2s <= 32 (or < s <= 16),
+// so it reduces over 32 (or 16) lanes; lanes outside contribute zeros to their own group.
+template <int N = kW>
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    for (int off = N / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off);
     return v;
 }
+template <int N = kW>
 __device__ __forceinline__ double wave_max(double v) {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+    for (int off = N / 2; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
     return v;
 }
+constexpr int kRowLanes = 2 * kLocateMaxS;  // lanes that can hold a row of a (2s) x a matrix
+constexpr int kColLanes = kLocateMaxS;      // lanes that can hold a row of the s x s system
 __device__ __forceinline__ double2 cmul(double2 a, double2 b) {
     return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }
@@ -66,7 +78,7 @@ __device__ __forceinline__ void mgs_append(Smem& sm, int rows, int c, int lane) 
         for (int i = 0; i < c; ++i) {
             double2 prod = make_double2(0.0, 0.0);
             if (lane < rows) prod = cmul(cconj(sm.Q[i * ldq + lane]), sm.Q[c * ldq + lane]);
-            const double2 dot = make_double2(wave_sum(prod.x), wave_sum(prod.y));
+            const double2 dot = make_double2(wave_sum<kRowLanes>(prod.x), wave_sum<kRowLanes>(prod.y));
             if (lane < rows) sm.Q[c * ldq + lane] = csub(sm.Q[c * ldq + lane], cmul(dot, sm.Q[i * ldq + lane]));
             if (lane == 0) sm.Rr[c * ldq + i] = pass == 0 ? dot : cadd(sm.Rr[c * ldq + i], dot);
             __syncthreads();
@@ -74,7 +86,7 @@ __device__ __forceinline__ void mgs_append(Smem& sm, int rows, int c, int lane) 
     }
     double n2 = 0.0;
     if (lane < rows) n2 = cnorm2(sm.Q[c * ldq + lane]);
-    const double nrm = sqrt(wave_sum(n2));
+    const double nrm = sqrt(wave_sum<kRowLanes>(n2));
     if (lane < rows) sm.Q[c * ldq + lane] = cscale(sm.Q[c * ldq + lane], 1.0 / nrm);
     if (lane == 0) sm.Rr[c * ldq + c] = make_double2(nrm, 0.0);
     __syncthreads();
@@ -106,6 +118,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         sm.mask[j] = 0;
     }
     if (lane == 0) sm.nv = 0;
+    DRACO_STAMP(0);
     __syncthreads();
     const bool all_finite = __ballot(!finite) == 0ull;
 
@@ -121,6 +134,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
         const double rho = 0.5 * (sm.lo + sm.hi);
+        DRACO_STAMP(1);
         const double zero = tau * rho;
 
         // syndromes h_m = (1/sqrt P) sum_j gamma_j w^{-m j}, m = n .. P-1
@@ -143,6 +157,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
         const double hmax = wave_max(mymax);
+        DRACO_STAMP(2);
 
         if (hmax > zero) {
             // ---- beta: least squares on the s x s system, singular values <= zero dropped
@@ -164,13 +179,23 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                             ap = sm.A[p * kLocateMaxS + lane];
                             aq = sm.A[q * kLocateMaxS + lane];
                         }
-                        const double alpha = wave_sum(cnorm2(ap));
-                        const double bet = wave_sum(cnorm2(aq));
+                        // lanes >= kColLanes form their own (all-zero) groups: they skip every
+                        // rotation and never touch A or V, so only group 0's decisions matter
+                        const double alpha = wave_sum<kColLanes>(cnorm2(ap));
+                        const double bet = wave_sum<kColLanes>(cnorm2(aq));
                         const double2 gp = cmul(cconj(ap), aq);
-                        const double2 g = make_double2(wave_sum(gp.x), wave_sum(gp.y));
+                        const double2 g = make_double2(wave_sum<kColLanes>(gp.x), wave_sum<kColLanes>(gp.y));
                         const double ag = hypot(g.x, g.y);
-                        if (ag == 0.0 || ag <= 1e-15 * sqrt(alpha * bet)) continue;   // uniform across the wavefront
+                        // columns that both end below the cutoff are dropped from the solution: no need
+                        // to make them orthogonal to each other
+                        const bool skip = ag == 0.0 || ag <= 1e-10 * sqrt(alpha * bet) ||
+                                          (alpha <= zero * zero && bet <= zero * zero);
+                        if (__shfl(skip ? 1 : 0, 0) != 0) continue;   // lane 0's verdict, uniform
                         rotated = true;
+                        if (lane >= s) {   // nothing to rotate; keep the barrier count equal
+                            __syncthreads();
+                            continue;
+                        }
                         const double2 ph = make_double2(g.x / ag, -g.y / ag);
                         const double zeta = (bet - alpha) / (2.0 * ag);
                         const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
@@ -187,7 +212,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                         __syncthreads();
                     }
                 }
-                if (!rotated) break;
+                if (__shfl(rotated ? 1 : 0, 0) == 0) break;
             }
             // beta_k = sum_i V[k][i] (a_i^H rhs) / |a_i|^2 over columns with |a_i| > zero
             double2 bk = make_double2(0.0, 0.0);
@@ -197,23 +222,31 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                     ai = sm.A[i * kLocateMaxS + lane];
                     ri = sm.rhs[lane];
                 }
-                const double s2 = wave_sum(cnorm2(ai));
+                const double s2 = wave_sum<kColLanes>(cnorm2(ai));
                 const double2 dp = cmul(cconj(ai), ri);
-                const double2 dot = make_double2(wave_sum(dp.x), wave_sum(dp.y));
+                const double2 dot = make_double2(wave_sum<kColLanes>(dp.x), wave_sum<kColLanes>(dp.y));
                 if (sqrt(s2) > zero && lane < s)
                     bk = cadd(bk, cmul(cscale(dot, 1.0 / s2), sm.V[i * kLocateMaxS + lane]));
             }
             if (lane < s) sm.beta[lane] = bk;
             __syncthreads();
+            DRACO_STAMP(3);
 
-            // ---- recurrence h_l = sum_u beta_u h_{l+u-s}, l = 0 .. n-1
-            for (int l = 0; l < n; ++l) {
-                double2 term = make_double2(0.0, 0.0);
-                if (lane < s) term = cmul(sm.beta[lane], sm.h[((l + lane - s) % P + P) % P]);
-                const double2 acc = make_double2(wave_sum(term.x), wave_sum(term.y));
-                if (lane == 0) sm.h[l] = acc;
-                __syncthreads();
+            // ---- recurrence h_l = sum_u beta_u h_{l+u-s}, l = 0 .. n-1: inherently serial, so one
+            // lane runs it out of LDS (a wavefront's LDS accesses complete in order)
+            if (lane == 0) {
+                for (int l = 0; l < n; ++l) {
+                    double2 acc = make_double2(0.0, 0.0);
+                    for (int u = 0; u < s; ++u) {
+                        int e = l + u - s;
+                        if (e < 0) e += P;
+                        acc = cadd(acc, cmul(sm.beta[u], sm.h[e]));
+                    }
+                    sm.h[l] = acc;
+                }
             }
+            __syncthreads();
+            DRACO_STAMP(4);
             // ---- t = C h, ranking by |t_j| (descending, ties to the lower index)
             for (int j = lane; j < P; j += kW) {
                 double2 acc = make_double2(0.0, 0.0);
@@ -233,6 +266,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 if (rank < s) sm.order[rank] = j;
             }
             __syncthreads();
+            DRACO_STAMP(5);
             // ---- shortest leading part of the ranking whose errors account for the syndromes
             int found = 0;
             for (int a = 1; a <= s; ++a) {
@@ -246,14 +280,14 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                     for (int c = 0; c < a; ++c) {
                         double2 prod = make_double2(0.0, 0.0);
                         if (lane < 2 * s) prod = cmul(cconj(sm.Q[c * ldq + lane]), sm.res[lane]);
-                        const double2 dot = make_double2(wave_sum(prod.x), wave_sum(prod.y));
+                        const double2 dot = make_double2(wave_sum<kRowLanes>(prod.x), wave_sum<kRowLanes>(prod.y));
                         if (lane < 2 * s) sm.res[lane] = csub(sm.res[lane], cmul(dot, sm.Q[c * ldq + lane]));
                         __syncthreads();
                     }
                 }
                 double r = 0.0;
                 if (lane < 2 * s) r = hypot(sm.res[lane].x, sm.res[lane].y);
-                if (wave_max(r) <= zero) {
+                if (__shfl(wave_max<kRowLanes>(r), 0) <= zero) {
                     found = a;
                     break;
                 }
@@ -265,6 +299,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
     }
 
+    DRACO_STAMP(6);
     // ---- b: minimum-norm solution of C_L[:, U] b_U = e_last (see host_math.cpp)
     if (lane == 0) {
         int a = 0;
@@ -300,6 +335,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
     }
+    DRACO_STAMP(7);
     for (int j = lane; j < P; j += kW) {
         double2 acc = make_double2(0.0, 0.0);
         if (!sm.mask[j]) {
@@ -322,6 +358,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 ++nu;
             }
         }
+        DRACO_STAMP(8);
         *nu_out = nu;
         for (int w = 0; w < (P + 63) / 64; ++w) mask_out[w] = words[w];
         *status_out = status;
