@@ -133,3 +133,85 @@ def test_full_size_cyclic_wide_wire_end_to_end():
         assert err <= 1e-6
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("code,P,s,d,attacks,placement,sigma", [
+    ("rep", 45, 2, 11_173_001, ("signflip", "signflip"), "distinct_groups", 1e-2),   # ResNet-18's count + 1: odd, ragged
+    ("cyc", 15, 2, 4_000_001, ("offset", "offset"), "any", 1.0),
+    ("cyc", 45, 3, 1_000_003, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2),
+])
+def test_odd_and_unaligned_lengths_at_scale(code, P, s, d, attacks, placement, sigma):
+    """Gradient lengths that are odd and not a multiple of 4: the tail workgroup takes the
+    guarded path while every other one takes the unchecked path."""
+    w = synth.Workload(name=f"{code}_odd_{d}", code=code, P=P, s=s, d=d, sigma=sigma, attacks=attacks,
+                       placement=placement, seed=synth.SEED_BASE + 77)
+    print(f"odd-length {w.name}", flush=True)
+    c = Case(w)
+    try:
+        c.Z.fill_(float("nan"))
+        c.encode()
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        assert torch.isfinite(c.Z[:, :c.mlen]).all() and torch.isfinite(c.u[:d]).all()
+        if c.ld_m > c.mlen:
+            assert torch.isnan(c.Z[:, c.mlen:]).all()                # padding never written
+        if c.u.numel() > d:
+            assert torch.isnan(c.u[d:]).all()
+        a = (d - 3000) // 2 * 2                                     # the ragged tail, element by element
+        G = c.G[:, a:d].cpu().numpy()
+        if code == "rep":
+            Zo = o.encode_repetition(G, s)
+            Zg = c.Z[:, a:d].cpu().numpy()
+            uo, mo, so = o.decode_repetition(c.R[:, a:d].cpu().numpy(), s)
+            assert np.array_equal(mo, mask)
+        else:
+            Zo = o.encode_cyclic(G, s)
+            Zg = c.Z[:, a:c.mlen].cpu().numpy()
+            Rc = o.wire_to_complex(c.R[:, a:c.mlen].cpu().numpy())
+            bo = o.solve_b(P, s, [j for j in range(P) if not mask[j]], "min_norm")
+            uo = o.unpack_complex(sum(bo[j] * Rc[j] for j in range(P) if not mask[j]), d - a)
+        for j in range(P):
+            assert rel_l2(Zg[j], Zo[j]) <= 1e-6, j
+        assert rel_l2(c.u[a:d].cpu().numpy(), uo) <= (1e-5 if code == "rep" else 1e-4)
+    finally:
+        c.close()
+
+
+def _time_ms(fn, reps=5):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+@pytest.mark.parametrize("code", ["rep", "cyc"])
+def test_encode_and_decode_time_is_linear_in_d_and_P(code):
+    """The paper's complexity claims (Remark after Theorem 1; proofs of Theorems 2 and 4): the
+    encoders cost O((2s+1) d) per node and the decoders O(P d): doubling d, or tripling P,
+    multiplies the time by about that factor."""
+    s = 2
+    base = dict(code=code, s=s, sigma=1.0, attacks=(), placement="any", seed=synth.SEED_BASE + 5)
+    times = {}
+    for P, d in [(15, 8_000_000), (15, 16_000_000), (45, 8_000_000)]:
+        c = Case(synth.Workload(name=f"lin_{P}_{d}", P=P, d=d, **base))
+        try:
+            c.encode()
+            c.receive()
+            times[(P, d)] = (_time_ms(c.encode), _time_ms(lambda: c.decode()))
+        finally:
+            c.close()
+    for k in (0, 1):
+        rd = times[(15, 16_000_000)][k] / times[(15, 8_000_000)][k]
+        rp = times[(45, 8_000_000)][k] / times[(15, 8_000_000)][k]
+        print(f"   {code} {'encode' if k == 0 else 'decode'}: x{rd:.2f} for 2x d, x{rp:.2f} for 3x P", flush=True)
+        # the decoders carry a fixed cost (one wavefront of small algebra, one host sync)
+        assert 1.4 <= rd <= 2.6
+        assert 1.7 <= rp <= 4.0
