@@ -108,6 +108,15 @@ int draco_plan_weights(const draco_plan* plan, double* W_host);
 int draco_encode(draco_plan* plan, const float* grads_dev, int64_t ld_g,
                  float* messages_dev, int64_t ld_m, void* stream);
 
+/* B > P (Sec. 1: "each compute node processes rB/P gradients"; the experiments
+ * use B = 180 or 720 on P = 45): samples_dev is [B][ld_g] with B a multiple of
+ * P, and unit gradient k of Sec. 3 is the sum of rows k*(B/P) .. (k+1)*(B/P)-1.
+ * The sums are formed inside the encoder pass (fp32, ascending, for the
+ * repetition code; fp64 for the cyclic code), so every per-sample row is read
+ * from HBM once and no [P][d] intermediate is written.  B = P is draco_encode. */
+int draco_encode_samples(draco_plan* plan, const float* samples_dev, int64_t B, int64_t ld_g,
+                         float* messages_dev, int64_t ld_m, void* stream);
+
 /* Cyclic code with the WIDE wire: every message is sent as two fp32 words per
  * float, messages_hi = fp32(z) and messages_lo = fp32(z - hi) with z the fp64
  * value, so that hi + lo carries 48 bits of z.  The entries of W grow like

@@ -17,9 +17,15 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libdraco.so")
-SOURCES = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hip", "locate.hip", "api.hip", "host_math.cpp")]
-HEADERS = [os.path.join(_HERE, "csrc", n) for n in ("kernels.hpp", "host_math.hpp")] + [
+SOURCES = [os.path.join(_HERE, "csrc", n) for n in (
+    # slowest first: the per-s encoder units dominate the build time
+    "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
+    "cyc_encode_s2.hip", "cyc_encode_s1.hip", "cyc_encode_s0.hip", "rep.hip", "cyc_encode.hip", "cyc_decode.hip",
+    "locate.hip", "api.hip", "host_math.cpp")]
+HEADERS = [os.path.join(_HERE, "csrc", n) for n in (
+    "kernels.hpp", "device_util.hpp", "cyc_encode_kernels.hpp", "cyc_encode_s.inc", "host_math.hpp")] + [
     os.path.join(_ROOT, "include", "draco.h")]
+BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
@@ -31,7 +37,7 @@ EXPORTS = [
     "draco_plan_create", "draco_plan_prepare", "draco_plan_destroy", "draco_message_len",
     "draco_plan_assign", "draco_plan_weights", "draco_encode", "draco_encode_node",
     "draco_decode_repetition", "draco_decode_repetition_async", "draco_decode_cyclic",
-    "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi", "draco_encode_wide",
+    "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi", "draco_encode_wide", "draco_encode_samples",
     "draco_decode_cyclic_wide", "draco_decode_cyclic_wide_async",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
@@ -40,18 +46,38 @@ EXPORTS = [
 
 
 def build(verbose: bool = False) -> str:
-    """Compile the library for gfx950 in-tree with hipcc (cross-compiles without a GPU)."""
+    """Compile the library for gfx950 in-tree with hipcc (cross-compiles without a GPU):
+    one object per source, compiled in parallel, then one link."""
+    from concurrent.futures import ThreadPoolExecutor
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fcomplex-arithmetic=basic",
-           "-I" + os.path.join(_ROOT, "include"), *SOURCES, "-o", LIB_PATH]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    flags = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fcomplex-arithmetic=basic",
+             "-I" + os.path.join(_ROOT, "include")]
+    os.makedirs(BUILD_DIR, exist_ok=True)
+
+    def compile_one(src):
+        obj = os.path.join(BUILD_DIR, os.path.basename(src) + ".o")
+        res = subprocess.run([hipcc, *flags, "-c", src, "-o", obj], capture_output=True, text=True)
+        return src, obj, res
+
+    objs = []
+    with ThreadPoolExecutor(max_workers=min(os.cpu_count() or 4, 8, len(SOURCES))) as ex:
+        for src, obj, res in ex.map(compile_one, SOURCES):
+            if verbose or res.returncode != 0:
+                print(src)
+                print(res.stdout)
+                print(res.stderr)
+            if res.returncode != 0:
+                raise RuntimeError(f"hipcc failed compiling {src}")
+            objs.append(obj)
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH],
+                         capture_output=True, text=True)
     if verbose or res.returncode != 0:
-        print(" ".join(cmd))
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libdraco.so")
+        raise RuntimeError("hipcc failed linking libdraco.so")
     return LIB_PATH
 
 
@@ -95,6 +121,8 @@ def lib() -> ctypes.CDLL:
     L.draco_decode_cyclic_hostphi.restype = i32
     L.draco_decode_cyclic_async.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     L.draco_decode_cyclic_async.restype = i32
+    L.draco_encode_samples.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    L.draco_encode_samples.restype = i32
     L.draco_encode_wide.argtypes = [vp, vp, i64, vp, vp, i64, vp]
     L.draco_encode_wide.restype = i32
     L.draco_decode_cyclic_wide.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
@@ -251,6 +279,11 @@ class Plan:
         _check(lib().draco_decode_cyclic_async(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
                                                out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                _stream_ptr(stream)))
+
+    def encode_samples(self, samples, messages, stream=None) -> None:
+        """samples: [B][ld] with B a multiple of P (B/P per-sample rows per unit gradient)."""
+        _check(lib().draco_encode_samples(self._h, samples.data_ptr(), samples.shape[0], samples.stride(0),
+                                          messages.data_ptr(), messages.stride(0), _stream_ptr(stream)))
 
     def encode_wide(self, grads, hi, lo, stream=None) -> None:
         assert hi.stride(0) == lo.stride(0)

@@ -1,0 +1,237 @@
+// Cyclic code: the two streaming passes of the decoder D^Cyc (Algorithm 1) -- the
+// projection f R of phi and the recombination R_{.,U} b -- and the plain copy kernel
+// used for calibration.
+#include "device_util.hpp"
+
+namespace draco {
+
+// phi step 1: gamma'_j = sum_i f_i * r_j[i].  A workgroup owns a tile of
+// kBlock*kProjectLoads float4 (two complex numbers each) of every row, keeps
+// its slice of f in registers, and for each row forms a per-wavefront sum in
+// fp64; the four wavefront sums are added in fixed order and stored per tile.
+template <bool WIDE>
+__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
+                                                             const float* __restrict__ Rlo, int64_t ldm,
+                                                             const float* __restrict__ f,
+                                                             double2* __restrict__ partial, int P, int64_t d) {
+    constexpr int K = kProjectLoads;
+    __shared__ double2 wsum[kBlock / 64][kMaxNodes];
+    const int64_t h = (d + 1) / 2;                                   // complex numbers per row
+    const int64_t q0 = (int64_t)blockIdx.x * (kBlock * K) + threadIdx.x;  // my first float4
+    const bool tile_full = ((int64_t)(blockIdx.x + 1) * (kBlock * K)) * 2 <= h;
+    double f0[K], f1[K];
+    int nflt[K];  // message floats that exist in my k-th float4 (4, 2 or 0)
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t q = q0 + (int64_t)k * kBlock;
+        const int64_t c = 2 * q;  // first complex index
+        f0[k] = (c < h) ? (double)f[c] : 0.0;
+        f1[k] = (c + 1 < h) ? (double)f[c + 1] : 0.0;
+        nflt[k] = (c + 1 < h) ? 4 : (c < h ? 2 : 0);
+    }
+    const int wave = threadIdx.x >> 6;
+    for (int j = 0; j < P; ++j) {
+        const float* row = Rm + (int64_t)j * ldm + q0 * 4;
+        float4 x[K];
+        if (tile_full) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) x[k] = ld4(row + (int64_t)k * kBlock * 4);
+        } else {
+#pragma unroll
+            for (int k = 0; k < K; ++k) x[k] = ld4_partial(row + (int64_t)k * kBlock * 4, nflt[k]);
+        }
+        double are = 0.0, aim = 0.0;
+        if constexpr (WIDE) {  // wire value = hi + lo, exact in fp64
+            const float* rowl = Rlo + (int64_t)j * ldm + q0 * 4;
+            float4 xl[K];
+            if (tile_full) {
+#pragma unroll
+                for (int k = 0; k < K; ++k) xl[k] = ld4(rowl + (int64_t)k * kBlock * 4);
+            } else {
+#pragma unroll
+                for (int k = 0; k < K; ++k) xl[k] = ld4_partial(rowl + (int64_t)k * kBlock * 4, nflt[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                are = fma(f0[k], (double)x[k].x + (double)xl[k].x, are);
+                aim = fma(f0[k], (double)x[k].y + (double)xl[k].y, aim);
+                are = fma(f1[k], (double)x[k].z + (double)xl[k].z, are);
+                aim = fma(f1[k], (double)x[k].w + (double)xl[k].w, aim);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                are = fma(f0[k], (double)x[k].x, are);
+                aim = fma(f0[k], (double)x[k].y, aim);
+                are = fma(f1[k], (double)x[k].z, are);
+                aim = fma(f1[k], (double)x[k].w, aim);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            are += __shfl_xor(are, off);
+            aim += __shfl_xor(aim, off);
+        }
+        if ((threadIdx.x & 63) == 0) wsum[wave][j] = make_double2(are, aim);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < P) {
+        double2 a = wsum[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            a.x += wsum[w][threadIdx.x].x;
+            a.y += wsum[w][threadIdx.x].y;
+        }
+        partial[(int64_t)blockIdx.x * P + threadIdx.x] = a;
+    }
+}
+
+// gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
+__global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double2* __restrict__ partial,
+                                                                    double2* __restrict__ gamma, int P,
+                                                                    int64_t tiles) {
+    __shared__ double2 sm[kBlock];
+    const int j = blockIdx.x;
+    double2 a = make_double2(0.0, 0.0);
+    for (int64_t t = threadIdx.x; t < tiles; t += kBlock) {
+        const double2 p = partial[t * P + j];
+        a.x += p.x;
+        a.y += p.y;
+    }
+    sm[threadIdx.x] = a;
+    __syncthreads();
+    for (int off = kBlock / 2; off >= 1; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            sm[threadIdx.x].x += sm[threadIdx.x + off].x;
+            sm[threadIdx.x].y += sm[threadIdx.x + off].y;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) gamma[j] = sm[0];
+}
+
+// u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
+// ascending node order, fp64 accumulation, one rounding to fp32.
+template <bool FULL, bool WIDE>
+__device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
+                                                   int64_t ldm,
+                                                   const double2* __restrict__ b, const int32_t* __restrict__ idx,
+                                                   const int32_t* __restrict__ nu_ptr, float* __restrict__ u,
+                                                   int64_t d) {
+    constexpr int UN = 8;
+    const int nu = *nu_ptr;  // honest nodes; written by the locator (device) or copied in by the host path
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (!FULL && c0 >= d) return;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const int nin = FULL ? 4 : clamp4(mlen - c0);
+    const int nout = FULL ? 4 : clamp4(d - c0);
+    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+    for (int q0 = 0; q0 < nu; q0 += UN) {
+        float4 x[UN], xl[WIDE ? UN : 1];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            if (q0 + i < nu) {
+                x[i] = ldx<FULL>(Rm + (int64_t)idx[q0 + i] * ldm + c0, nin);
+                if constexpr (WIDE) xl[i] = ldx<FULL>(Rlo + (int64_t)idx[q0 + i] * ldm + c0, nin);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            if (q0 + i < nu) {
+                const double br = b[q0 + i].x, bi = b[q0 + i].y;
+                if constexpr (WIDE) {
+                    cmac(br, bi, (double)x[i].x + (double)xl[i].x, (double)x[i].y + (double)xl[i].y, are0, aim0);
+                    cmac(br, bi, (double)x[i].z + (double)xl[i].z, (double)x[i].w + (double)xl[i].w, are1, aim1);
+                } else {
+                    cmac(br, bi, (double)x[i].x, (double)x[i].y, are0, aim0);
+                    cmac(br, bi, (double)x[i].z, (double)x[i].w, are1, aim1);
+                }
+            }
+        }
+    }
+    stx<FULL>(u + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
+}
+
+template <bool WIDE>
+__global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm,
+                                                               const float* __restrict__ Rlo, int64_t ldm,
+                                                               const double2* __restrict__ b,
+                                                               const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ nu,
+                                                               float* __restrict__ u, int64_t d) {
+    if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
+    else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
+}
+
+// Plain copy of a [rows][ld] slab (row_len floats used per row) with the access
+// pattern of the encoders: a lane owns one 16-byte column of every row and has
+// eight rows in flight.  Calibration kernel for bandwidth figures and for
+// scaling hardware byte counters.
+__global__ __launch_bounds__(kBlock) void copy_probe_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                            int rows, int64_t row_len, int64_t ld) {
+    constexpr int UN = 8;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 + 4 > row_len) return;
+    for (int j0 = 0; j0 < rows; j0 += UN) {
+        float4 x[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if (j0 + i < rows) x[i] = ld4(src + (int64_t)(j0 + i) * ld + c0);
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if (j0 + i < rows) st4(dst + (int64_t)(j0 + i) * ld + c0, x[i]);
+    }
+}
+
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+
+int64_t project_tiles(int64_t d) {
+    const int64_t h = (d + 1) / 2;
+    const int64_t nvec = (h + 1) / 2;
+    const int64_t per = (int64_t)kBlock * kProjectLoads;
+    return (nvec + per - 1) / per;
+}
+
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, double2* partial,
+                              double2* gamma, int P, int64_t d, hipStream_t stream) {
+    const int64_t tiles = project_tiles(d);
+    if (Rlo == nullptr)
+        hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           partial, P, d);
+    else
+        hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           partial, P, d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row_len, int64_t ld,
+                             hipStream_t stream) {
+    allow_large_lds<copy_probe_kernel>();
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid_for(row_len / 4)), dim3(kBlock), throttle_lds(1, 0, 0), stream, src,
+                       dst, rows, row_len, ld);
+    return hipGetLastError();
+}
+
+hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
+                                const int32_t* nu, float* u, int64_t d, hipStream_t stream) {
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    if (Rlo == nullptr) {
+        allow_large_lds<cyc_recombine_kernel<false>>();
+        hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+                           nu, u, d);
+    } else {
+        allow_large_lds<cyc_recombine_kernel<true>>();
+        hipLaunchKernelGGL(cyc_recombine_kernel<true>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+                           nu, u, d);
+    }
+    return hipGetLastError();
+}
+
+
+}  // namespace draco

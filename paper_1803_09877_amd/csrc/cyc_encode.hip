@@ -1,0 +1,101 @@
+// Cyclic code (Sec. 3, "Cyclic Code"): dispatch of the encoder E^Cyc, z_j = G W_{.,j},
+// over the window width, and the one-node / any-width kernel.
+#include "cyc_encode_kernels.hpp"
+
+namespace draco {
+
+// One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
+// wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
+// with wrap_rows == P it is the full [P][ldg] slab and row (node+t) mod P is
+// used (the all-node path for r > 2*kMaxS+1).  Same operation order as the
+// all-node kernel, so results are bit-identical.
+__global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
+                                                                 float* __restrict__ z, float* __restrict__ zlo,
+                                                                 const double2* __restrict__ cn, int node, int P,
+                                                                 int r, int wrap_rows, int m, int64_t d) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (c0 >= mlen) return;
+    const int nin = clamp4(d - c0);
+    const int nout = clamp4(mlen - c0);
+    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+    for (int t = 0; t < r; ++t) {
+        int k = node + t;
+        if (k >= P) k -= P;
+        const float* p = Gn + (int64_t)(wrap_rows ? k : t) * m * ldg + c0;
+        double gx = 0.0, gy = 0.0, gz = 0.0, gw = 0.0;  // the unit gradient: sum of its m sample rows
+        for (int i = 0; i < m; ++i) {
+            const float4 raw = (nin == 4) ? ld4(p + (int64_t)i * ldg) : ld4_partial(p + (int64_t)i * ldg, nin);
+            gx += (double)raw.x;
+            gy += (double)raw.y;
+            gz += (double)raw.z;
+            gw += (double)raw.w;
+        }
+        cmac(cn[t].x, cn[t].y, gx, gy, are0, aim0);
+        cmac(cn[t].x, cn[t].y, gz, gw, are1, aim1);
+    }
+    const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+    if (nout == 4) st4(z + c0, out);
+    else st4_partial(z + c0, out, nout);
+    if (zlo != nullptr) {
+        const float4 lo = make_float4((float)(are0 - (double)out.x), (float)(aim0 - (double)out.y),
+                                      (float)(are1 - (double)out.z), (float)(aim1 - (double)out.w));
+        if (nout == 4) st4(zlo + c0, lo);
+        else st4_partial(zlo + c0, lo, nout);
+    }
+}
+
+
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm, const double2* coef, int P,
+                             int s, int64_t d, hipStream_t stream) {
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const int r = 2 * s + 1;
+    const bool one_per_cu = s <= 3 && P >= 32;
+#define DRACO_CASE(S) \
+    case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, ldm, coef, P, d);
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default:
+            for (int j = 0; j < P; ++j)
+                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
+                                   Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, 1, d);
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, const double2* coef,
+                                     int P, int s, int64_t d, hipStream_t stream) {
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const int r = 2 * s + 1;
+#define DRACO_CASE(S) \
+    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, ldm, coef, P, d);
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default:
+            for (int j = 0; j < P; ++j)
+                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
+                                   (float*)nullptr, coef + (int64_t)j * r, j, P, r, P, m, d);
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef, int node,
+                                  int P, int s, int64_t d, hipStream_t stream) {
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const int r = 2 * s + 1;
+    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, coef + (int64_t)node * r, node,
+                       P, r, 0, 1, d);
+    return hipGetLastError();
+}
+
+}  // namespace draco

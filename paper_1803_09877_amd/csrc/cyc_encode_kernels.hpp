@@ -1,0 +1,219 @@
+// Kernel templates of the cyclic encoder E^Cyc (Sec. 3, "Cyclic Code"), shared by the
+// per-window-width translation units (one per s, so they compile in parallel).
+#pragma once
+
+#include "device_util.hpp"
+
+namespace draco {
+
+// E^Cyc for all nodes: z_n = sum_{t=0}^{2s} coef[n][t] * g_{(n+t) mod P} with
+// coef[n][t] = W[(n+t) mod P][n], on packed complex coordinates in fp64.  A lane
+// keeps the window g_n .. g_{n+2s} of its two complex coordinates in registers
+// and slides it down the P rows, so every gradient row is read from HBM once;
+// rows 0..2s-1, needed again by the last 2s nodes, are parked in LDS (each lane
+// reads back only what it wrote: no barrier).  Rows are fetched NB-1 rounds of
+// R = 2s+1 ahead of the arithmetic (a ring of NB register buffers).
+template <int S, int NB, bool FULL, bool WIDE>
+__device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int64_t ldg, float* __restrict__ Z,
+                                                float* __restrict__ Zlo, int64_t ldm,
+                                                const double2* __restrict__ coef, int P, int64_t d,
+                                                float4* head /* LDS [2S][kBlock] */) {
+    constexpr int R = 2 * S + 1;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (!FULL && c0 >= mlen) return;
+    const int nin = FULL ? 4 : clamp4(d - c0);      // gradient floats that exist (the pad of an odd d reads as 0)
+    const int nout = FULL ? 4 : clamp4(mlen - c0);  // message floats to write
+
+    double wre[R][2], wim[R][2];  // window slot = row index mod R
+
+    auto put = [&](int slot, const float4& raw) {
+        wre[slot][0] = (double)raw.x;
+        wim[slot][0] = (double)raw.y;
+        wre[slot][1] = (double)raw.z;
+        wim[slot][1] = (double)raw.w;
+    };
+    // fetch the rows that nodes n0 .. n0+R-1 bring into the window
+    auto issue = [&](int n0, float4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int kk = n0 + uu + 2 * S;
+            if (n0 + uu < P) {
+                if (kk < P) buf[uu] = ldx<FULL>(G + (int64_t)kk * ldg + c0, nin);
+                else buf[uu] = head[(kk - P) * kBlock + threadIdx.x];
+            }
+        }
+    };
+    auto consume = [&](int n0, const float4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                put((uu + 2 * S) % R, buf[uu]);
+                const double2* cn = coef + (int64_t)n * R;
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    const double cr = cn[t].x, ci = cn[t].y;
+                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
+                }
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if constexpr (WIDE) {  // second word of the wide wire: what the first rounding lost
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
+            }
+        }
+    };
+
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const float4 raw = ldx<FULL>(G + (int64_t)k * ldg + c0, nin);
+        head[k * kBlock + threadIdx.x] = raw;
+        put(k, raw);
+    }
+    float4 buf[NB][R];
+#pragma unroll
+    for (int b = 0; b < NB - 1; ++b)
+        if (b * R < P) issue(b * R, buf[b]);
+    for (int n0 = 0; n0 < P; n0 += NB * R) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int cur = n0 + b * R;
+            if (cur < P) {
+                const int nxt = cur + (NB - 1) * R;
+                if (nxt < P) issue(nxt, buf[(b + NB - 1) % NB]);
+                consume(cur, buf[b]);
+            }
+        }
+    }
+}
+
+template <int S, int NB, bool WIDE>
+__global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
+                                                            float* __restrict__ Z, float* __restrict__ Zlo,
+                                                            int64_t ldm, const double2* __restrict__ coef, int P,
+                                                            int64_t d) {
+    extern __shared__ float4 head[];  // [2S][kBlock]
+    if (block_is_full(d)) encode_cyc_body<S, NB, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    else encode_cyc_body<S, NB, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+}
+
+// E^Cyc when every unit gradient is the sum of m = B/P per-sample gradients (rows k*m ..
+// k*m+m-1 of the sample slab): the same sliding window, but a window entry is the fp64
+// sum of m rows, formed as the rows arrive; the first 2s unit sums are parked in LDS in
+// fp64 for the wrap-around.  Units are fetched one round ahead.
+template <int S, bool FULL>
+__device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ G, int64_t ldg, int m,
+                                                      float* __restrict__ Z, int64_t ldm,
+                                                      const double2* __restrict__ coef, int P, int64_t d,
+                                                      double4* head /* LDS [2S][kBlock] */) {
+    constexpr int R = 2 * S + 1;
+    constexpr int UN = 4;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (!FULL && c0 >= mlen) return;
+    const int nin = FULL ? 4 : clamp4(d - c0);
+    const int nout = FULL ? 4 : clamp4(mlen - c0);
+
+    double wre[R][2], wim[R][2];
+    auto put = [&](int slot, const double4& v) {
+        wre[slot][0] = v.x;
+        wim[slot][0] = v.y;
+        wre[slot][1] = v.z;
+        wim[slot][1] = v.w;
+    };
+    auto unit_sum = [&](int k) -> double4 {  // g_k = sum of its m sample rows, ascending, in fp64
+        double4 acc = make_double4(0.0, 0.0, 0.0, 0.0);
+        const float* src = G + (int64_t)k * m * ldg + c0;
+        for (int i0 = 0; i0 < m; i0 += UN) {
+            float4 x[UN];
+#pragma unroll
+            for (int i = 0; i < UN; ++i)
+                if (i0 + i < m) x[i] = ldx<FULL>(src + (int64_t)(i0 + i) * ldg, nin);
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                if (i0 + i < m) {
+                    acc.x += (double)x[i].x;
+                    acc.y += (double)x[i].y;
+                    acc.z += (double)x[i].z;
+                    acc.w += (double)x[i].w;
+                }
+            }
+        }
+        return acc;
+    };
+    auto issue = [&](int n0, double4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int kk = n0 + uu + 2 * S;
+            if (n0 + uu < P) {
+                if (kk < P) buf[uu] = unit_sum(kk);
+                else buf[uu] = head[(kk - P) * kBlock + threadIdx.x];
+            }
+        }
+    };
+    auto consume = [&](int n0, const double4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                put((uu + 2 * S) % R, buf[uu]);
+                const double2* cn = coef + (int64_t)n * R;
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    const double cr = cn[t].x, ci = cn[t].y;
+                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
+                }
+                stx<FULL>(Z + (int64_t)n * ldm + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1),
+                          nout);
+            }
+        }
+    };
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const double4 v = unit_sum(k);
+        head[k * kBlock + threadIdx.x] = v;
+        put(k, v);
+    }
+    double4 bufA[R], bufB[R];
+    issue(0, bufA);
+    for (int n0 = 0; n0 < P; n0 += 2 * R) {
+        if (n0 + R < P) issue(n0 + R, bufB);
+        consume(n0, bufA);
+        if (n0 + R < P) {
+            if (n0 + 2 * R < P) issue(n0 + 2 * R, bufA);
+            consume(n0 + R, bufB);
+        }
+    }
+}
+
+template <int S>
+__global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* __restrict__ G, int64_t ldg, int m,
+                                                                  float* __restrict__ Z, int64_t ldm,
+                                                                  const double2* __restrict__ coef, int P,
+                                                                  int64_t d) {
+    extern __shared__ double4 head_sums[];  // [2S][kBlock]
+    if (block_is_full(d)) encode_cyc_multi_body<S, true>(G, ldg, m, Z, ldm, coef, P, d, head_sums);
+    else encode_cyc_multi_body<S, false>(G, ldg, m, Z, ldm, coef, P, d, head_sums);
+}
+
+
+// Launch of the all-node encoder for one s (defined in the translation unit of that s).
+// one_per_cu selects the launch shape: one workgroup per CU with deep prefetch, or two.
+template <int S>
+hipError_t launch_encode_cyc_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg, float* Z,
+                               float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
+// Same for the B > P form (m per-sample rows per unit gradient).
+template <int S>
+hipError_t launch_encode_cyc_multi_s(dim3 grid, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
+                                     int64_t ldm, const double2* coef, int P, int64_t d);
+
+}  // namespace draco

@@ -1,0 +1,126 @@
+// Shared device helpers and launch helpers of the streaming kernels.
+//
+// Every kernel of the library is a streaming pass over [node][coordinate] fp32 slabs and
+// is bound by HBM bandwidth: one lane owns 4 consecutive floats (one 16-byte load per
+// row), a wavefront therefore reads 1 KiB of each row per step, and the loop over the
+// rows runs inside the lane so each input byte is read from HBM exactly once.
+// Workgroups are 256 lanes (4 wavefronts).  There is no reuse between workgroups, so the
+// blockIdx -> tile map is the identity.
+#pragma once
+
+#include "kernels.hpp"
+
+namespace draco {
+namespace {
+
+
+// Slabs are streamed: every byte is used once, so 16-byte accesses carry the
+// non-temporal hint (measured on MI355X: +10% on read-dominated passes).
+typedef float vfloat4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4(const float* p) {
+    const vfloat4 v = __builtin_nontemporal_load(reinterpret_cast<const vfloat4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4(float* p, float4 v) {
+    vfloat4 w;
+    w.x = v.x;
+    w.y = v.y;
+    w.z = v.z;
+    w.w = v.w;
+    __builtin_nontemporal_store(w, reinterpret_cast<vfloat4*>(p));
+}
+
+// Guarded load of up to 4 floats; missing ones read as 0.
+__device__ __forceinline__ float4 ld4_partial(const float* p, int n) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n > 0) v.x = p[0];
+    if (n > 1) v.y = p[1];
+    if (n > 2) v.z = p[2];
+    if (n > 3) v.w = p[3];
+    return v;
+}
+__device__ __forceinline__ void st4_partial(float* p, float4 v, int n) {
+    if (n > 0) p[0] = v.x;
+    if (n > 1) p[1] = v.y;
+    if (n > 2) p[2] = v.z;
+    if (n > 3) p[3] = v.w;
+}
+
+__device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ? 0 : (int)n); }
+
+// Every workgroup but the last of a launch covers whole 16-byte vectors only;
+// the kernels branch ONCE, uniformly, on that, so the common path has no
+// per-access bounds checks (FULL) and the ragged tail takes the guarded path.
+template <bool FULL>
+__device__ __forceinline__ float4 ldx(const float* p, int n) {
+    if constexpr (FULL) return ld4(p);
+    else return ld4_partial(p, n);
+}
+template <bool FULL>
+__device__ __forceinline__ void stx(float* p, float4 v, int n) {
+    if constexpr (FULL) st4(p, v);
+    else st4_partial(p, v, n);
+}
+__device__ __forceinline__ bool block_is_full(int64_t len) {
+    return (int64_t)(blockIdx.x + 1) * (kBlock * 4) <= len;
+}
+
+
+// acc += (tr + i ti) * (x + i y): one instruction sequence wherever it is used
+__device__ __forceinline__ void cmac(double tr, double ti, double x, double y, double& are, double& aim) {
+    are = fma(tr, x, are);
+    are = fma(-ti, y, are);
+    aim = fma(tr, y, aim);
+    aim = fma(ti, x, aim);
+}
+
+
+// ---------------------------------------------------------------------------
+// Launch helpers (host)
+// ---------------------------------------------------------------------------
+
+inline unsigned grid_for(int64_t units_of_4_floats) {
+    return (unsigned)((units_of_4_floats + kBlock - 1) / kBlock);
+}
+
+// --- occupancy throttle -----------------------------------------------------
+// HBM throughput on MI355X peaks when a CU has roughly 24-48 KiB of loads in
+// flight (measured: a [45][25.6M] copy runs at 5.3 TB/s with 32 resident
+// wavefronts per CU and at 5.9 TB/s with 4; a read-only pass at 6.1 vs 6.7).
+// The streaming kernels therefore ask for more LDS than they use, so that only
+// `blocks_per_cu` workgroups fit on a CU at a time.
+inline size_t lds_per_cu() {
+    static const size_t v = [] {
+        int dev = 0, val = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return (size_t)65536;
+        if (hipDeviceGetAttribute(&val, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess || val <= 0)
+            return (size_t)65536;
+        return (size_t)val;
+    }();
+    return v;
+}
+
+// Dynamic LDS bytes to request so that at most blocks_per_cu workgroups are
+// resident per CU (0 = no limit), given the kernel's static LDS use and the
+// dynamic bytes it really needs.
+inline size_t throttle_lds(int blocks_per_cu, size_t static_bytes, size_t needed) {
+    if (blocks_per_cu <= 0) return needed;
+    size_t per = lds_per_cu() / (size_t)blocks_per_cu;
+    per = per / 1024 * 1024;
+    const size_t dyn = per > static_bytes ? per - static_bytes : 0;
+    return dyn > needed ? dyn : needed;
+}
+
+// Opt a kernel in to workgroups with more than 64 KiB of dynamic LDS (once);
+// static_bytes is what the kernel declares itself.
+template <auto Kernel>
+void allow_large_lds(size_t static_bytes = 0) {
+    static const hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(lds_per_cu() - static_bytes));
+    if (e != hipSuccess) (void)hipGetLastError();  // the launch itself reports a request that does not fit
+}
+
+
+}  // namespace
+}  // namespace draco

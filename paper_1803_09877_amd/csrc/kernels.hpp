@@ -30,6 +30,12 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
 hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t* status_out,
                                     int P, int s, hipStream_t stream);
 
+// B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
+hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,
+                                     int s, int64_t d, hipStream_t stream);
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm,
+                                     const double2* coef, int P, int s, int64_t d, hipStream_t stream);
+
 // ---- cyclic code ----
 // coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
 // Zlo / zlo / Rlo below: second word of the wide wire (message = hi + lo), or nullptr.

@@ -328,6 +328,41 @@ def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
         c.close()
 
 
+# ------------------------------------------------- B > P (per-sample rows) ----
+@pytest.mark.parametrize("code,P,s,m,d", [
+    ("rep", 15, 2, 4, 3001), ("rep", 45, 2, 4, 20_003), ("rep", 9, 1, 16, 999), ("rep", 34, 8, 3, 777),
+    ("cyc", 15, 2, 4, 3001), ("cyc", 45, 3, 4, 20_002), ("cyc", 45, 3, 16, 5_001), ("cyc", 15, 7, 2, 2_050),
+    ("cyc", 20, 8, 3, 1_001), ("cyc", 6, 0, 5, 4_099), ("cyc", 45, 5, 4, 8_000),
+])
+def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d):
+    """B = m*P per-sample gradients (the paper runs B = 180 and 720 on P = 45): unit gradient k
+    is the sum of rows k*m .. k*m+m-1, then the code's encoder."""
+    plan = B.Plan(B.CODE_REPETITION if code == "rep" else B.CODE_CYCLIC, P, s, d)
+    try:
+        ld = synth.padded_len(d)
+        S = synth.make_gradients(P * m, d, 1.0, synth.SEED_BASE + 31 * m + P, device="cuda:0", ld=ld)
+        mlen = plan.message_len
+        Z = torch.full((P, synth.padded_len(mlen)), float("nan"), dtype=torch.float32, device="cuda:0")
+        print(f"samples case {code} P={P} s={s} m={m} d={d}", flush=True)
+        plan.encode_samples(S, Z)
+        torch.cuda.synchronize()
+        units = S[:, :d].double().reshape(P, m, d).sum(1).cpu().numpy()
+        Zo = o.encode_repetition(units, s) if code == "rep" else o.encode_cyclic(units, s)
+        Zg = Z[:, :mlen].cpu().numpy()
+        for j in range(P):
+            assert rel_l2(Zg[j], Zo[j]) <= 1e-6, j
+        if Z.shape[1] > mlen:
+            assert torch.isnan(Z[:, mlen:]).all()
+        if code == "rep":
+            r = 2 * s + 1
+            for j in range(P):
+                assert np.array_equal(Zg[j].view(np.uint32), Zg[(j // r) * r].view(np.uint32))
+        with pytest.raises(B.DracoError):
+            plan.encode_samples(S[:P * m - 1], Z)                       # B not a multiple of P
+    finally:
+        plan.close()
+
+
 # ------------------------------------------------------------ arguments -----
 def test_alignment_and_argument_errors():
     w = wl("rep", 6, 1, 100)
