@@ -68,24 +68,25 @@ __device__ __forceinline__ void encode_rep_generic_body(const float* __restrict_
     for (int g = 0; g < groups; ++g) {
         const float* src = G + (int64_t)g * rows * ldg + c0;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int i0 = 0; i0 < rows; i0 += UN) {
+        int i0 = 0;
+        for (; i0 + UN <= rows; i0 += UN) {   // whole rounds: no per-row checks
             float4 x[UN];
 #pragma unroll
-            for (int i = 0; i < UN; ++i)
-                if (i0 + i < rows) x[i] = ldx<FULL>(src + (int64_t)(i0 + i) * ldg, n);
+            for (int i = 0; i < UN; ++i) x[i] = ldx<FULL>(src + (int64_t)(i0 + i) * ldg, n);
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
-                if (i0 + i < rows) {
-                    if (i0 + i == 0) {
-                        acc = x[i];
-                    } else {
-                        acc.x += x[i].x;
-                        acc.y += x[i].y;
-                        acc.z += x[i].z;
-                        acc.w += x[i].w;
-                    }
-                }
+                acc.x += x[i].x;
+                acc.y += x[i].y;
+                acc.z += x[i].z;
+                acc.w += x[i].w;
             }
+        }
+        for (; i0 < rows; ++i0) {
+            const float4 x = ldx<FULL>(src + (int64_t)i0 * ldg, n);
+            acc.x += x.x;
+            acc.y += x.y;
+            acc.z += x.z;
+            acc.w += x.w;
         }
         float* dst = Z + (int64_t)g * copies * ldm + c0;
         for (int i = 0; i < copies; ++i) stx<FULL>(dst + (int64_t)i * ldm, acc, n);
@@ -345,7 +346,7 @@ hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* 
     const int r = 2 * s + 1, groups = P / r;
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
     allow_large_lds<encode_rep_generic_kernel>();
-    hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, throttle_lds(1, 0, 0), stream, G, ldg, Z, ldm, groups,
+    hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, throttle_lds(2, 0, 0), stream, G, ldg, Z, ldm, groups,
                        r * m, r, d);
     return hipGetLastError();
 }
