@@ -166,8 +166,10 @@ int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, i
  *                entry per complex coordinate, drawn by the caller
  *   sum_dev      [d] fp32 out
  *   mask_host    as above: the located set V
+ * A node whose message holds NaN or Inf is flagged outright (it is one of the
+ * at most s adversaries) and the sum is still recovered.
  * Returns DRACO_LOCATE_FAILED if no set of at most s nodes explains the
- * syndromes, or if a projection is not finite.  For s <= 16 the small linear
+ * syndromes.  For s <= 16 the small linear
  * algebra of phi and b runs in one fp64 wavefront between the two streaming
  * kernels, so the whole call is stream-ordered and waits for `stream` only
  * once, at the end, to fetch mask and status; for larger s it is

@@ -356,16 +356,23 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     account for the syndromes, i.e. leave them zero after a least-squares fit.
     In exact arithmetic t has exactly |V| non-zeros and this is the same set.
     Returns (mask, t, status); LOCATE_FAILED when no leading part of length
-    <= s accounts for the syndromes (more than s liars, or non-finite input),
-    with mask = the s largest |t_j| as a best effort.
+    <= s accounts for the syndromes (more than s liars), with mask = the s
+    largest |t_j| as a best effort.  Non-finite projections: see the first
+    lines of the body.
     """
-    gamma = np.asarray(gamma, dtype=np.complex128)
+    gamma = np.array(gamma, dtype=np.complex128)
     P = gamma.shape[0]
     mask = np.zeros(P, dtype=bool)
     t = np.zeros(P, dtype=np.complex128)
+    # A message with NaN or Inf entries is no vector of R^d: its node is flagged outright
+    # and its projection taken as 0, which leaves an ordinary error f.(-z_j) at a known node
+    # for the steps below to account for like any other.
+    broken = ~np.isfinite(gamma)
+    gamma[broken] = 0.0
+    mask |= broken
     if s == 0:
-        return mask, t, OK
-    if not np.all(np.isfinite(gamma)):
+        return mask, t, (LOCATE_FAILED if broken.any() else OK)
+    if int(broken.sum()) > s:
         return mask, t, LOCATE_FAILED
     rho = float(np.median(np.abs(gamma)))
     hk = syndromes(gamma, s)
@@ -392,7 +399,7 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     for a in range(1, s + 1):
         if _unexplained(hk, P, s, order[:a]) <= tau_h * rho:
             mask[order[:a]] = True
-            return mask, t, OK
+            return mask, t, (OK if int(mask.sum()) <= s else LOCATE_FAILED)
     mask[order] = True
     return mask, t, LOCATE_FAILED
 
@@ -463,14 +470,16 @@ def solve_b(P: int, s: int, U: list, mode: str = "min_norm") -> np.ndarray:
 def decode_cyclic_complex(Rc: np.ndarray, f: np.ndarray, s: int, b_mode: str = "min_norm"):
     """Algorithm 1 on packed messages: V = phi(R); U = complement; b from
     ``solve_b``; u_hat = R_{.,U} b.  Returns (u_hat complex [h], mask, status).
-    status LOCATE_FAILED comes from phi (more than s nodes lied, or a
-    non-finite projection); u_hat is then not to be trusted."""
+    status LOCATE_FAILED comes from phi (more than s nodes lied); u_hat is
+    then not to be trusted."""
     Rc = np.asarray(Rc, dtype=np.complex128)
     P = Rc.shape[0]
     check_params("cyc", P, s)
     gamma = project(Rc, f)
     mask, _, status = phi_from_projection(gamma, s)
     U = [j for j in range(P) if not mask[j]]
+    if len(U) < P - 2 * s:
+        return np.full(Rc.shape[1], np.nan, dtype=np.complex128), mask, LOCATE_FAILED
     b = solve_b(P, s, U, b_mode)
     u_hat = np.zeros(Rc.shape[1], dtype=np.complex128)
     for j in U:

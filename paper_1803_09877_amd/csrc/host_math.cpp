@@ -177,16 +177,26 @@ cplx_t CyclicCode::W(int k, int j) const {
     return rot[k] * taps[t];
 }
 
-bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
+bool cyclic_locate(int P, int s, const std::complex<double>* gamma_in, std::vector<uint8_t>& mask,
                    std::vector<std::complex<double>>& t_out) {
     mask.assign(P, 0);
     t_out.assign(P, std::complex<double>(0, 0));
-    if (s == 0) return true;
-    std::vector<double> mags(P);
+    // A message with NaN or Inf entries is no vector of R^d: its node is flagged outright and
+    // its projection taken as 0, which leaves an ordinary error at a known node.
+    std::vector<std::complex<double>> clean(gamma_in, gamma_in + P);
+    const std::complex<double>* gamma = clean.data();
+    int broken = 0;
     for (int j = 0; j < P; ++j) {
-        if (!std::isfinite(gamma[j].real()) || !std::isfinite(gamma[j].imag())) return false;
-        mags[j] = std::abs(gamma[j]);
+        if (!std::isfinite(clean[j].real()) || !std::isfinite(clean[j].imag())) {
+            clean[j] = 0;
+            mask[j] = 1;
+            ++broken;
+        }
     }
+    if (s == 0) return broken == 0;
+    if (broken > s) return false;
+    std::vector<double> mags(P);
+    for (int j = 0; j < P; ++j) mags[j] = std::abs(gamma[j]);
     std::sort(mags.begin(), mags.end());
     const real_t rho = (P % 2) ? (real_t)mags[P / 2] : ((real_t)mags[P / 2 - 1] + (real_t)mags[P / 2]) / 2;
     const real_t zero = (real_t)kTauH * rho;
@@ -248,7 +258,9 @@ bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<
         std::vector<int> V(order.begin(), order.begin() + a);
         if (unexplained(P, s, hk, V) <= zero) {
             for (int j : V) mask[j] = 1;
-            return true;
+            int total = 0;
+            for (int j = 0; j < P; ++j) total += mask[j];
+            return total <= s;
         }
     }
     for (int j : order) mask[j] = 1;

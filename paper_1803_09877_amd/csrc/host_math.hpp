@@ -34,8 +34,8 @@ constexpr double kTauH = 32.0 / 16777216.0;
 // phi steps 2-4 on the projections gamma (length P).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns
 // true on success, false when no set of at most s nodes accounts for the
-// syndromes (mask then holds the s largest |t_j|) or gamma is not finite
-// (mask empty).
+// syndromes (mask then holds the s largest |t_j|).  Nodes whose projection is
+// not finite are flagged outright and enter the algebra with projection 0.
 bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
                    std::vector<std::complex<double>>& t);
 

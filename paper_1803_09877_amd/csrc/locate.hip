@@ -106,24 +106,28 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     const double isq = 1.0 / sqrt((double)P);
     int status = 0;
 
-    bool finite = true;
+    // A message with NaN or Inf entries is no vector of R^d: its node is flagged outright and
+    // its projection taken as 0, which leaves an ordinary error at a known node.
+    int my_broken = 0;
     for (int j = lane; j < P; j += kW) {
-        const double2 g = gamma[j];
+        double2 g = gamma[j];
+        const bool ok = isfinite(g.x) && isfinite(g.y);
+        if (!ok) g = make_double2(0.0, 0.0);
+        my_broken += ok ? 0 : 1;
         sm.gam[j] = g;
-        finite = finite && isfinite(g.x) && isfinite(g.y);
         double sn, cs;
         sincospi(2.0 * (double)j / (double)P, &sn, &cs);
         sm.root[j] = make_double2(cs, sn);
         sm.mag[j] = hypot(g.x, g.y);
-        sm.mask[j] = 0;
+        sm.mask[j] = ok ? 0 : 1;
     }
     if (lane == 0) sm.nv = 0;
     DRACO_STAMP(0);
     __syncthreads();
-    const bool all_finite = __ballot(!finite) == 0ull;
+    const int broken = (int)wave_sum<kW>((double)my_broken);
 
-    if (s > 0 && !all_finite) status = 2;  // DRACO_LOCATE_FAILED, empty mask
-    if (s > 0 && all_finite) {
+    if (broken > s) status = 2;  // DRACO_LOCATE_FAILED: more broken messages than tolerated
+    if (s > 0 && broken <= s) {
         // rho = median |gamma_j| by rank counting
         for (int j = lane; j < P; j += kW) {
             const double mj = sm.mag[j];
@@ -296,6 +300,9 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             if (!found) status = 2;
             if (lane < take) sm.mask[sm.order[lane]] = 1;
             __syncthreads();
+            int mine = 0;
+            for (int j = lane; j < P; j += kW) mine += sm.mask[j];
+            if ((int)wave_sum<kW>((double)mine) > s) status = 2;
         }
     }
 
@@ -308,7 +315,10 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         sm.nv = a;
     }
     __syncthreads();
-    const int a = sm.nv;
+    // more than s flagged nodes only happens with status LOCATE_FAILED; the factorisation
+    // below has room for s columns, so a failed decode takes the first s of them
+    const int a = sm.nv <= s ? sm.nv : s;
+    if (sm.nv > s) status = 2;
     if (lane < 2 * s) sm.Bv[lane] = make_double2(0.0, 0.0);
     __syncthreads();
     if (a > 0) {

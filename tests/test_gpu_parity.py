@@ -199,9 +199,28 @@ def test_cyc_more_than_s_adversaries_is_reported():
     run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
 
 
-def test_cyc_nonfinite_message_is_reported():
+@pytest.mark.parametrize("bad", ["inf", "nan", "two_nodes", "with_other_liar"])
+def test_cyc_nonfinite_messages_are_flagged_and_survived(bad):
+    """A node that sends NaN or Inf is flagged outright and the sum is still recovered
+    (it is one of the at most s adversaries); more broken nodes than s is reported."""
     def edit(c):
-        c.R[2, 10] = float("inf")
+        if bad == "inf":
+            c.R[2, 10] = float("inf")
+        elif bad == "nan":
+            c.R[7, c.mlen - 1] = float("nan")
+        elif bad == "two_nodes":
+            c.R[2, 10] = float("inf")
+            c.R[3, 11] = float("nan")
+        else:
+            c.R[2, 10] = float("nan")
+            c.R[5, :c.mlen] *= -100.0
+    c = run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, check_true_sum=1e-5)
+
+
+def test_cyc_more_broken_messages_than_s_is_reported():
+    def edit(c):
+        for j in (1, 4, 6):
+            c.R[j, 3 + j] = float("nan")
     run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
 
 

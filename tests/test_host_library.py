@@ -100,9 +100,30 @@ def test_locator_reports_too_many_adversaries_and_nonfinite():
     omask, _, ost = o.phi_from_projection(gamma, s)
     assert st == B.LOCATE_FAILED and ost == o.LOCATE_FAILED
     assert np.array_equal(mask, omask)
-    gamma[1] = np.nan
+    gamma[1] = np.nan                                   # a fourth bad node, this one not even finite
     mask, _, st = plan.cyclic_locate(gamma)
-    assert st == B.LOCATE_FAILED and not mask.any()
+    omask, _, ost = o.phi_from_projection(gamma, s)
+    assert st == B.LOCATE_FAILED == ost and mask[1] and np.array_equal(mask, omask)
+
+
+def test_locator_flags_nonfinite_projections_and_still_locates():
+    P, s = 9, 2
+    plan = B.Plan(B.CODE_CYCLIC, P, s, 40)
+    rng = np.random.default_rng(4)
+    G = rng.standard_normal((P, 40)).astype(np.float32)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    f = np.ones(20)
+    for V, broken in [((2,), (2,)), ((2, 6), (6,)), ((0, 8), (0, 8))]:
+        Rc = Zc.copy()
+        for j in V:
+            Rc[j] = rng.standard_normal(20) * 50
+        gamma = o.project(Rc, f)
+        for j in broken:
+            gamma[j] = np.inf if j % 2 else np.nan
+        mask, _, st = plan.cyclic_locate(gamma)
+        omask, _, ost = o.phi_from_projection(gamma, s)
+        assert st == B.OK == ost
+        assert sorted(np.flatnonzero(mask)) == sorted(V) == sorted(np.flatnonzero(omask))
 
 
 @pytest.mark.parametrize("P,s", [(4, 1), (7, 2), (9, 4)])

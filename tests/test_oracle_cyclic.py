@@ -279,6 +279,31 @@ def test_definition2_every_adversary_subset(P, s, kind):
                 assert np.linalg.norm(u - ref) <= 1e-9 * np.linalg.norm(ref)
 
 
+@pytest.mark.parametrize("P,s", [(5, 1), (7, 2), (9, 4)])
+def test_definition2_with_nonfinite_messages(P, s):
+    """A NaN/Inf message is still one adversarial node: for every adversary subset, with each
+    adversary's message made non-finite somewhere, the decoder returns G 1_P and the set."""
+    d = 18
+    G = _grads(P, d, 3 * P + s)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Z = o.encode_cyclic(G, s)
+    f = _f(Z.shape[1] // 2, P)
+    rng = np.random.default_rng(P)
+    for a in range(1, s + 1):
+        for V in itertools.combinations(range(P), a):
+            R = Z.copy()
+            for n, j in enumerate(V):
+                if n % 2 == 0:
+                    R[j, int(rng.integers(R.shape[1]))] = np.nan if n % 4 == 0 else np.inf
+                else:
+                    R[j] = -100.0 * R[j]
+            with np.errstate(invalid="ignore"):
+                u, mask, st = o.decode_cyclic(R, f, s, d)
+            assert st == o.OK
+            assert sorted(np.flatnonzero(mask)) == sorted(V)
+            assert np.linalg.norm(u - ref) <= 1e-9 * np.linalg.norm(ref)
+
+
 def test_more_than_s_adversaries_is_reported():
     P, s, d = 9, 2, 40
     G = _grads(P, d, 77)
