@@ -157,11 +157,58 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
+    kernel_times = [c.plan.kernel_time(kind) for kind in range(len(KIND_NAMES))]
+
+    # The same step through the stream-ordered entry points (mask and status stay on the
+    # device, read once after the K steps), eagerly and as one captured HIP graph per step.
+    extra = {}
+    if w.decode:
+        mask_dev = torch.zeros(4, dtype=torch.int64, device=c.device)
+        status_dev = torch.zeros(1, dtype=torch.int32, device=c.device)
+
+        def async_step():
+            c.encode()
+            if w.code == "rep":
+                c.plan.decode_repetition_async(c.R, c.u, mask_dev, status_dev)
+            elif args.wide:
+                c.plan.decode_cyclic_wide_async(c.R, c.Rlo, c.f, c.u, mask_dev, status_dev)
+            else:
+                c.plan.decode_cyclic_async(c.R, c.f, c.u, mask_dev, status_dev)
+
+        if w.code == "rep" or w.s <= 16:
+            c.plan.set_timing(0)
+            for _ in range(args.warmup):
+                async_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                async_step()
+            torch.cuda.synchronize()
+            extra["async_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
+            assert int(status_dev.item()) == 0
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    async_step()
+            torch.cuda.synchronize()
+            for _ in range(args.warmup):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            extra["graph_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
+            assert int(status_dev.item()) == 0
+            words = B.mask_to_bool(mask_dev.cpu().numpy().view(np.uint64), w.P)
+            assert np.array_equal(words, c.expected_mask())
 
     abytes = algorithmic_bytes(w, c.mlen, n_honest, args.wide)
     kernels = {}
     for kind, name in enumerate(KIND_NAMES):
-        total_ms, n = c.plan.kernel_time(kind)
+        total_ms, n = kernel_times[kind]
         if n:
             avg = total_ms / n
             kernels[name] = {"avg_ms": avg, "launches": n, "algorithmic_bytes": abytes[name],
@@ -195,6 +242,7 @@ def main():
         "copy_kernel_ceiling_GBps": copy_gbps,
         "roofline": roof,
         "kernels": kernels,
+        "stream_ordered": extra,
     }
     c.close()
     if not args.no_cpu_baseline:

@@ -347,6 +347,29 @@ def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
         c.close()
 
 
+# ---------------------------------------------------------- random sweep -----
+def test_random_shapes_and_attacks():
+    """Seeded random (code, P, s, d, adversary count, attack mix, placement) cases."""
+    rng = np.random.default_rng(20180309877)
+    kinds = ["noise", "signflip", "offset", "constant"]
+    for case in range(40):
+        code = "rep" if case % 2 == 0 else "cyc"
+        s = int(rng.integers(0, 8))
+        r = 2 * s + 1
+        if code == "rep":
+            P = r * int(rng.integers(1, max(2, 60 // r)))
+        else:
+            P = int(rng.integers(r, 64))
+        d = int(rng.integers(1, 30_000))
+        a = int(rng.integers(0, s + 1))
+        attacks = tuple(rng.choice(kinds, a))
+        if code == "cyc" and P >= 40 and s >= 4:
+            attacks = tuple(k if k != "constant" else "signflip" for k in attacks)
+        sigma = float(rng.choice([1.0, 1e-2]))
+        w = wl(code, P, s, d, attacks, "any", sigma, seed=100 + case)
+        run_and_check(w)
+
+
 # ------------------------------------------------- B > P (per-sample rows) ----
 @pytest.mark.parametrize("code,P,s,m,d", [
     ("rep", 15, 2, 4, 3001), ("rep", 45, 2, 4, 20_003), ("rep", 9, 1, 16, 999), ("rep", 34, 8, 3, 777),
