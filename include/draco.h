@@ -178,6 +178,16 @@ int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_
                         const float* f_dev, float* sum_dev, uint64_t* mask_host,
                         void* stream);
 
+/* Speculative single-pass decode (cyclic code, s <= 16; on by default).  While
+ * the projection pass of draco_decode_cyclic* has a row in registers it can also
+ * accumulate the recombination for "no adversary" and write it to sum_dev; if
+ * phi then flags nobody -- the usual case in training -- that is the decoded sum
+ * (bit-identical to what the second pass would give) and the second pass over
+ * the messages is skipped, which halves the decode.  A plan speculates in a
+ * call when its previous decode was clean (the first call does), so a run with
+ * persistent adversaries pays for one wasted speculation only.  0 switches it off. */
+int draco_plan_set_speculation(draco_plan* plan, int enabled);
+
 /* Same, stream-ordered (s <= 16 only, else DRACO_EINVAL): mask_dev
  * [ceil(P/64)] and status_dev [1] are DEVICE outputs valid once `stream`
  * reaches the end of the call.  Does not wait, allocates nothing. */

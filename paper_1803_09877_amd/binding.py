@@ -41,7 +41,7 @@ EXPORTS = [
     "draco_decode_cyclic_wide", "draco_decode_cyclic_wide_async",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
-    "draco_copy_probe",
+    "draco_copy_probe", "draco_plan_set_speculation",
 ]
 
 
@@ -137,6 +137,8 @@ def lib() -> ctypes.CDLL:
     L.draco_strerror.restype = ctypes.c_char_p
     L.draco_last_hip_error.argtypes = []
     L.draco_last_hip_error.restype = ctypes.c_char_p
+    L.draco_plan_set_speculation.argtypes = [vp, i32]
+    L.draco_plan_set_speculation.restype = i32
     L.draco_copy_probe.argtypes = [vp, vp, i32, i64, i64, vp]
     L.draco_copy_probe.restype = i32
     L.draco_plan_set_timing.argtypes = [vp, i32]
@@ -303,6 +305,9 @@ class Plan:
         _check(lib().draco_decode_cyclic_wide_async(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), f.data_ptr(),
                                                     out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                     _stream_ptr(stream)))
+
+    def set_speculation(self, enabled: bool) -> None:
+        _check(lib().draco_plan_set_speculation(self._h, 1 if enabled else 0))
 
     def set_timing(self, max_records: int) -> None:
         _check(lib().draco_plan_set_timing(self._h, max_records))

@@ -41,6 +41,9 @@ struct draco_plan {
     double2* partial_dev = nullptr;  // project_tiles(d) * P
     double2* gamma_dev = nullptr;    // P
     double2* b_dev = nullptr;        // P
+    double2* b0_dev = nullptr;       // P: recombination vector when no node is flagged
+    int32_t* spec_dev = nullptr;     // 2 words: speculate next / speculated now (see cyc_decode.hip)
+    bool speculation = true;
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
     uint64_t* mask_dev = nullptr;    // kMaskWords
@@ -96,6 +99,21 @@ int prepare(draco_plan* p) {
         HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(p->d) * P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->gamma_dev, P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->b_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->b0_dev, P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->spec_dev, 2 * sizeof(int32_t)));
+        {
+            std::vector<uint8_t> none(P, 0);
+            std::vector<cplx_t> b0;
+            cyclic_recombination_vector(P, p->s, none, b0);
+            std::vector<double> t0(2 * P);
+            for (int j = 0; j < P; ++j) {
+                t0[2 * j] = (double)b0[j].real();
+                t0[2 * j + 1] = (double)b0[j].imag();
+            }
+            HIP_TRY(hipMemcpy(p->b0_dev, t0.data(), P * sizeof(double2), hipMemcpyHostToDevice));
+            const int32_t init[2] = {1, 0};  // optimistic: the first decode speculates
+            HIP_TRY(hipMemcpy(p->spec_dev, init, sizeof(init), hipMemcpyHostToDevice));
+        }
         HIP_TRY(hipMalloc(&p->idx_dev, (P + 1) * sizeof(int32_t)));
         HIP_TRY(hipHostMalloc(&p->gamma_pin, 2 * P * sizeof(double), hipHostMallocDefault));
         HIP_TRY(hipHostMalloc(&p->b_pin, 2 * P * sizeof(double), hipHostMallocDefault));
@@ -170,6 +188,8 @@ void draco_plan_destroy(draco_plan* p) {
         (void)hipFree(p->partial_dev);
         (void)hipFree(p->gamma_dev);
         (void)hipFree(p->b_dev);
+        (void)hipFree(p->b0_dev);
+        (void)hipFree(p->spec_dev);
         (void)hipFree(p->idx_dev);
         (void)hipFree(p->flags_dev);
         (void)hipFree(p->mask_dev);
@@ -361,15 +381,18 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     const float* lo = wide ? lo_dev : nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P;
+    int32_t* spec = p->speculation ? p->spec_dev : nullptr;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, spec, P,
+                                   p->d, st));
     }
-    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, mask_dev, status_dev, p->b_dev, p->idx_dev, p->idx_dev + P,
-                              st));
+    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
+                              p->idx_dev + P, spec, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev, p->d,
+                                     st));
     }
     return DRACO_OK;
 }
@@ -384,7 +407,8 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     const int P = p->P, s = p->s;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, P, p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, nullptr,
+                                   P, p->d, st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -409,7 +433,8 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, (P + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, sum_dev, p->d, st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, nullptr, P, sum_dev, p->d,
+                                     st));
     }
     HIP_TRY(hipStreamSynchronize(st));
     return located ? DRACO_OK : DRACO_LOCATE_FAILED;
@@ -511,6 +536,12 @@ const char* draco_strerror(int status) {
 }
 
 const char* draco_last_hip_error(void) { return g_hip_detail; }
+
+int draco_plan_set_speculation(draco_plan* p, int enabled) {
+    if (p == nullptr) return DRACO_EINVAL;
+    p->speculation = enabled != 0;
+    return DRACO_OK;
+}
 
 int draco_copy_probe(const float* src_dev, float* dst_dev, int rows, int64_t row_len, int64_t ld, void* stream) {
     if (src_dev == nullptr || dst_dev == nullptr || rows < 1 || row_len < 4) return DRACO_EINVAL;

@@ -9,13 +9,19 @@ namespace draco {
 // kBlock*kProjectLoads float4 (two complex numbers each) of every row, keeps
 // its slice of f in registers, and for each row forms a per-wavefront sum in
 // fp64; the four wavefront sums are added in fixed order and stored per tile.
-template <bool WIDE>
-__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
-                                                             const float* __restrict__ Rlo, int64_t ldm,
-                                                             const float* __restrict__ f,
-                                                             double2* __restrict__ partial, int P, int64_t d) {
+//
+// Speculation (SPEC): while a row is in registers the kernel also accumulates
+// u0 = sum_j b0_j r_j with b0 the recombination vector for "no adversary", and writes it to
+// the output.  If the locator then finds no adversary -- the usual case in training -- u0 IS
+// the decoded sum (same coefficients, same order, same instruction sequence as the
+// recombination kernel) and the second pass over the messages is skipped.
+template <bool WIDE, bool SPEC>
+__device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
+                                                 int64_t ldm, const float* __restrict__ f,
+                                                 double2* __restrict__ partial, const double2* __restrict__ b0,
+                                                 float* __restrict__ u, int P, int64_t d,
+                                                 double2 (*wsum)[kMaxNodes]) {
     constexpr int K = kProjectLoads;
-    __shared__ double2 wsum[kBlock / 64][kMaxNodes];
     const int64_t h = (d + 1) / 2;                                   // complex numbers per row
     const int64_t q0 = (int64_t)blockIdx.x * (kBlock * K) + threadIdx.x;  // my first float4
     const bool tile_full = ((int64_t)(blockIdx.x + 1) * (kBlock * K)) * 2 <= h;
@@ -29,6 +35,11 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
         f1[k] = (c + 1 < h) ? (double)f[c + 1] : 0.0;
         nflt[k] = (c + 1 < h) ? 4 : (c < h ? 2 : 0);
     }
+    double ure0[SPEC ? K : 1], uim0[SPEC ? K : 1], ure1[SPEC ? K : 1], uim1[SPEC ? K : 1];
+    if constexpr (SPEC) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) ure0[k] = uim0[k] = ure1[k] = uim1[k] = 0.0;
+    }
     const int wave = threadIdx.x >> 6;
     for (int j = 0; j < P; ++j) {
         const float* row = Rm + (int64_t)j * ldm + q0 * 4;
@@ -40,8 +51,8 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
 #pragma unroll
             for (int k = 0; k < K; ++k) x[k] = ld4_partial(row + (int64_t)k * kBlock * 4, nflt[k]);
         }
-        double are = 0.0, aim = 0.0;
-        if constexpr (WIDE) {  // wire value = hi + lo, exact in fp64
+        double xr0[K], xi0[K], xr1[K], xi1[K];  // the wire values in fp64 (hi + lo is exact)
+        if constexpr (WIDE) {
             const float* rowl = Rlo + (int64_t)j * ldm + q0 * 4;
             float4 xl[K];
             if (tile_full) {
@@ -53,18 +64,34 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
             }
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                are = fma(f0[k], (double)x[k].x + (double)xl[k].x, are);
-                aim = fma(f0[k], (double)x[k].y + (double)xl[k].y, aim);
-                are = fma(f1[k], (double)x[k].z + (double)xl[k].z, are);
-                aim = fma(f1[k], (double)x[k].w + (double)xl[k].w, aim);
+                xr0[k] = (double)x[k].x + (double)xl[k].x;
+                xi0[k] = (double)x[k].y + (double)xl[k].y;
+                xr1[k] = (double)x[k].z + (double)xl[k].z;
+                xi1[k] = (double)x[k].w + (double)xl[k].w;
             }
         } else {
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                are = fma(f0[k], (double)x[k].x, are);
-                aim = fma(f0[k], (double)x[k].y, aim);
-                are = fma(f1[k], (double)x[k].z, are);
-                aim = fma(f1[k], (double)x[k].w, aim);
+                xr0[k] = (double)x[k].x;
+                xi0[k] = (double)x[k].y;
+                xr1[k] = (double)x[k].z;
+                xi1[k] = (double)x[k].w;
+            }
+        }
+        double are = 0.0, aim = 0.0;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            are = fma(f0[k], xr0[k], are);
+            aim = fma(f0[k], xi0[k], aim);
+            are = fma(f1[k], xr1[k], are);
+            aim = fma(f1[k], xi1[k], aim);
+        }
+        if constexpr (SPEC) {
+            const double br = b0[j].x, bi = b0[j].y;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                cmac(br, bi, xr0[k], xi0[k], ure0[k], uim0[k]);
+                cmac(br, bi, xr1[k], xi1[k], ure1[k], uim1[k]);
             }
         }
 #pragma unroll
@@ -73,6 +100,16 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
             aim += __shfl_xor(aim, off);
         }
         if ((threadIdx.x & 63) == 0) wsum[wave][j] = make_double2(are, aim);
+    }
+    if constexpr (SPEC) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int64_t c0 = (q0 + (int64_t)k * kBlock) * 4;
+            const int nout = clamp4(d - c0);
+            const float4 out = make_float4((float)ure0[k], (float)uim0[k], (float)ure1[k], (float)uim1[k]);
+            if (nout == 4) st4(u + c0, out);
+            else st4_partial(u + c0, out, nout);
+        }
     }
     __syncthreads();
     if ((int)threadIdx.x < P) {
@@ -84,6 +121,23 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
         }
         partial[(int64_t)blockIdx.x * P + threadIdx.x] = a;
     }
+}
+
+// spec_state[0]: speculate in this call (set by the previous call's locator: 1 if that decode was
+// clean); spec_state[1]: whether this call speculated (read by the recombination kernel).
+// spec_state == nullptr: never speculate.
+template <bool WIDE>
+__global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
+                                                             const float* __restrict__ Rlo, int64_t ldm,
+                                                             const float* __restrict__ f,
+                                                             double2* __restrict__ partial,
+                                                             const double2* __restrict__ b0, float* __restrict__ u,
+                                                             int32_t* __restrict__ spec_state, int P, int64_t d) {
+    __shared__ double2 wsum[kBlock / 64][kMaxNodes];
+    const bool spec = spec_state != nullptr && spec_state[0] != 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && spec_state != nullptr) spec_state[1] = spec ? 1 : 0;
+    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, partial, b0, u, P, d, wsum);
+    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, partial, b0, u, P, d, wsum);
 }
 
 // gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
@@ -152,13 +206,17 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
     stx<FULL>(u + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
 }
 
+// If the projection pass speculated (spec_state[1]) and every node turned out honest
+// (*nu == P), the output already holds the answer: nothing to do.
 template <bool WIDE>
 __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm,
                                                                const float* __restrict__ Rlo, int64_t ldm,
                                                                const double2* __restrict__ b,
                                                                const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ nu,
+                                                               const int32_t* __restrict__ spec_state, int P,
                                                                float* __restrict__ u, int64_t d) {
+    if (spec_state != nullptr && spec_state[1] != 0 && *nu == P) return;
     if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
     else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
 }
@@ -196,14 +254,15 @@ int64_t project_tiles(int64_t d) {
 }
 
 hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, double2* partial,
-                              double2* gamma, int P, int64_t d, hipStream_t stream) {
+                              double2* gamma, const double2* b0, float* u, int32_t* spec_state, int P, int64_t d,
+                              hipStream_t stream) {
     const int64_t tiles = project_tiles(d);
     if (Rlo == nullptr)
         hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           partial, P, d);
+                           partial, b0, u, spec_state, P, d);
     else
         hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           partial, P, d);
+                           partial, b0, u, spec_state, P, d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
@@ -219,16 +278,17 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
 }
 
 hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
-                                const int32_t* nu, float* u, int64_t d, hipStream_t stream) {
+                                const int32_t* nu, const int32_t* spec_state, int P, float* u, int64_t d,
+                                hipStream_t stream) {
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
     if (Rlo == nullptr) {
         allow_large_lds<cyc_recombine_kernel<false>>();
         hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
-                           nu, u, d);
+                           nu, spec_state, P, u, d);
     } else {
         allow_large_lds<cyc_recombine_kernel<true>>();
         hipLaunchKernelGGL(cyc_recombine_kernel<true>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
-                           nu, u, d);
+                           nu, spec_state, P, u, d);
     }
     return hipGetLastError();
 }

@@ -47,18 +47,23 @@ hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float*
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
 int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
+// b0[P]: recombination vector for "no adversary"; u: output written speculatively when
+// spec_state[0] != 0 (spec_state: two device words, see cyc_decode.hip; nullptr = never).
 hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f,
-                              double2* partial, double2* gamma, int P, int64_t d, hipStream_t stream);
+                              double2* partial, double2* gamma, const double2* b0, float* u,
+                              int32_t* spec_state, int P, int64_t d, hipStream_t stream);
 // phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
 // gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
 // their count in *nu_out.  tau: relative zero threshold for syndromes.
-hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, uint64_t* mask_out,
-                             int32_t* status_out, double2* b_out, int32_t* idx_out, int32_t* nu_out,
-                             hipStream_t stream);
+// With no located node the coefficients are copied from b0 (bit-identical to the speculative pass);
+// spec_state[0] <- 1 if this decode was clean (the next call speculates), else 0.
+hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, const double2* b0,
+                             uint64_t* mask_out, int32_t* status_out, double2* b_out, int32_t* idx_out,
+                             int32_t* nu_out, int32_t* spec_state, hipStream_t stream);
 // u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
 hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b,
-                                const int32_t* idx, const int32_t* nu, float* u, int64_t d,
-                                hipStream_t stream);
+                                const int32_t* idx, const int32_t* nu, const int32_t* spec_state, int P,
+                                float* u, int64_t d, hipStream_t stream);
 
 // dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
 // (bandwidth / counter calibration).

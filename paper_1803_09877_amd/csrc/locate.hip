@@ -95,6 +95,8 @@ __device__ __forceinline__ void mgs_append(Smem& sm, int rows, int c, int lane) 
 }  // namespace
 
 __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restrict__ gamma, int P, int s, double tau,
+                                                        const double2* __restrict__ b0,
+                                                        int32_t* __restrict__ spec_state,
                                                         uint64_t* __restrict__ mask_out,
                                                         int32_t* __restrict__ status_out,
                                                         double2* __restrict__ b_out, int32_t* __restrict__ idx_out,
@@ -349,9 +351,13 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     for (int j = lane; j < P; j += kW) {
         double2 acc = make_double2(0.0, 0.0);
         if (!sm.mask[j]) {
-            acc = cconj(sm.root[((n - 1) * j) % P]);
-            for (int m = 0; m < 2 * s; ++m) acc = cadd(acc, cmul(cconj(sm.root[((n + m) * j) % P]), sm.Bv[m]));
-            acc = cscale(acc, isq);
+            if (sm.nv == 0) {
+                acc = b0[j];  // the table the speculative pass used: identical results either way
+            } else {
+                acc = cconj(sm.root[((n - 1) * j) % P]);
+                for (int m = 0; m < 2 * s; ++m) acc = cadd(acc, cmul(cconj(sm.root[((n + m) * j) % P]), sm.Bv[m]));
+                acc = cscale(acc, isq);
+            }
         }
         sm.h[j] = acc;  // reuse: b_j
     }
@@ -370,15 +376,17 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         DRACO_STAMP(8);
         *nu_out = nu;
+        if (spec_state != nullptr) spec_state[0] = (nu == P && status == 0) ? 1 : 0;
         for (int w = 0; w < (P + 63) / 64; ++w) mask_out[w] = words[w];
         *status_out = status;
     }
 }
 
-hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, uint64_t* mask_out, int32_t* status_out,
-                             double2* b_out, int32_t* idx_out, int32_t* nu_out, hipStream_t stream) {
-    hipLaunchKernelGGL(cyc_locate_kernel, dim3(1), dim3(kW), 0, stream, gamma, P, s, tau, mask_out, status_out, b_out,
-                       idx_out, nu_out);
+hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, const double2* b0, uint64_t* mask_out,
+                             int32_t* status_out, double2* b_out, int32_t* idx_out, int32_t* nu_out,
+                             int32_t* spec_state, hipStream_t stream) {
+    hipLaunchKernelGGL(cyc_locate_kernel, dim3(1), dim3(kW), 0, stream, gamma, P, s, tau, b0, spec_state, mask_out,
+                       status_out, b_out, idx_out, nu_out);
     return hipGetLastError();
 }
 

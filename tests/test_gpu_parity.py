@@ -248,6 +248,49 @@ def test_cyc_async_form_needs_no_host_value():
         c.close()
 
 
+def test_cyc_speculative_single_pass_decode():
+    """A plan speculates when its previous decode was clean.  Sequence on one plan: clean,
+    clean, two liars, two liars, clean, clean -- every result against the oracle, the clean
+    speculated ones bit-identical to the two-pass result, and the second pass then costs
+    next to nothing."""
+    w = wl("cyc", 45, 3, 2_000_001, (), "any", 1e-2)
+    c = Case(w)
+    ref = Case(w)
+    ref.plan.set_speculation(False)
+    try:
+        c.encode()
+        f = c.f.cpu().numpy()
+        c.plan.set_timing(16)
+        liars = [(10, "signflip"), (11, "noise")]
+        for step, adv in enumerate([[], [], liars, liars, [], []]):
+            c.R = c.Z.clone()
+            synth.apply_attacks(c.R, c.mlen, adv, w.seed + step)
+            ref.R = c.R
+            c.u.fill_(float("nan"))
+            mask, status = c.decode()
+            ref.u.fill_(float("nan"))
+            mask_ref, status_ref = ref.decode()
+            torch.cuda.synchronize()
+            proj_ms, _ = c.plan.kernel_time(B.KIND_PROJECT)
+            reco_ms, _ = c.plan.kernel_time(B.KIND_RECOMBINE)
+            uo, mo, so = o.decode_cyclic(c.R[:, :c.mlen].cpu().numpy(), f, w.s, w.d)
+            assert status == status_ref == so == 0
+            assert np.array_equal(mask, mo) and np.array_equal(mask_ref, mo)
+            assert sorted(np.flatnonzero(mask)) == sorted(j for j, _ in adv)
+            assert rel_l2(c.u[:w.d].cpu().numpy(), uo) <= 1e-4
+            assert torch.equal(c.u[:w.d], ref.u[:w.d]), step       # same bits with and without speculation
+            assert torch.isnan(c.u[w.d:]).all()
+            speculated_and_clean = not adv and (step == 0 or step == 1 or step == 5)
+            print(f"   step {step}: liars {len(adv)}  project {proj_ms:.3f} ms  recombine {reco_ms:.3f} ms", flush=True)
+            if speculated_and_clean:
+                assert reco_ms < 0.25 * proj_ms
+            else:
+                assert reco_ms > 0.5 * proj_ms
+    finally:
+        c.close()
+        ref.close()
+
+
 def test_cyc_large_s_takes_the_host_form():
     # s = 17 > 16: the default entry point falls back to host phi; the async form refuses
     w = wl("cyc", 40, 17, 1_001, ("noise", "signflip", "offset"), "any")
