@@ -204,7 +204,10 @@ class Plan:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the module globals may be gone
+            pass
 
     # ---- host-only ----
     @property
