@@ -163,7 +163,10 @@ int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, i
  * u = R_{.,U} b, unpacked to d reals.
  *   messages_dev [P][ld_m] fp32, complex interleaved (see draco_message_len)
  *   f_dev        [ceil(d/2)] fp32: the random vector f ~ N(1, I) of phi, one
- *                entry per complex coordinate, drawn by the caller
+ *                entry per complex coordinate, drawn by the caller; or NULL:
+ *                the projection kernel then makes the entries on the fly from
+ *                the plan's projection seed (draco_plan_set_projection_seed)
+ *                and no vector is read from memory
  *   sum_dev      [d] fp32 out
  *   mask_host    as above: the located set V
  * A node whose message holds NaN or Inf is flagged outright (it is one of the
@@ -177,6 +180,16 @@ int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, i
 int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_m,
                         const float* f_dev, float* sum_dev, uint64_t* mask_host,
                         void* stream);
+
+/* Seed of the generated projection vector used when f_dev is NULL (default 0).
+ * Entry i is a counter-based function of (seed, i): splitmix64's finaliser on
+ * seed + (i+1)*0x9E3779B97F4A7C15 gives two 24-bit uniforms u1 (top bits) and
+ * u2 (bits 16..39), and f_i = fp32(1 + sqrt(-2 ln u1) cos(2 pi u2)).  A fresh
+ * seed per decode keeps an adversary from preparing a message orthogonal to f.
+ * draco_projection_vector writes the ceil(d/2) entries for a seed to host
+ * memory (inspection, tests). */
+int draco_plan_set_projection_seed(draco_plan* plan, uint64_t seed);
+int draco_projection_vector(const draco_plan* plan, uint64_t seed, float* f_host);
 
 /* Speculative single-pass decode (cyclic code, s <= 16; on by default).  While
  * the projection pass of draco_decode_cyclic* has a row in registers it can also

@@ -313,6 +313,25 @@ def encode_cyclic(G: np.ndarray, s: int, pairing: str = "interleaved") -> np.nda
 # --------------------------------------------------------------------------
 # Cyclic code: the locator phi (Sec. 3) and a definition-level cross-check.
 # --------------------------------------------------------------------------
+def projection_vector(h: int, seed: int) -> np.ndarray:
+    """The counter-based f ~ N(1, I) of the library's boundary, entry i from (seed, i):
+    z = splitmix64's finaliser on seed + (i+1)*0x9E3779B97F4A7C15 (mod 2^64); u1 and u2
+    are its top 24 bits and its bits 16..39, each plus 1/2, over 2^24; Box-Muller in fp64,
+    f_i = fp32(1 + sqrt(-2 ln u1) cos(2 pi u2)).  Written out here independently of the
+    library so that both sides of a parity test can draw the same vector."""
+    M = (1 << 64) - 1
+    out = np.empty(h, dtype=np.float32)
+    for i in range(h):            # plain Python integers: exact 64-bit wrap-around
+        z = (seed + (i + 1) * 0x9E3779B97F4A7C15) & M
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        z ^= z >> 31
+        u1 = ((z >> 40) + 0.5) / 16777216.0
+        u2 = (((z >> 16) & 0xFFFFFF) + 0.5) / 16777216.0
+        out[i] = np.float32(1.0 + np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2))
+    return out
+
+
 def project(Rc: np.ndarray, f: np.ndarray) -> np.ndarray:
     """gamma'_j = sum_i f_i * r_j[i]  (the row vector f R of phi's first step);
     Rc is [P][h] complex, f is [h] real."""

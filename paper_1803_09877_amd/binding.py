@@ -42,6 +42,7 @@ EXPORTS = [
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe", "draco_plan_set_speculation",
+    "draco_plan_set_projection_seed", "draco_projection_vector",
 ]
 
 
@@ -137,6 +138,10 @@ def lib() -> ctypes.CDLL:
     L.draco_strerror.restype = ctypes.c_char_p
     L.draco_last_hip_error.argtypes = []
     L.draco_last_hip_error.restype = ctypes.c_char_p
+    L.draco_plan_set_projection_seed.argtypes = [vp, ctypes.c_uint64]
+    L.draco_plan_set_projection_seed.restype = i32
+    L.draco_projection_vector.argtypes = [vp, ctypes.c_uint64, vp]
+    L.draco_projection_vector.restype = i32
     L.draco_plan_set_speculation.argtypes = [vp, i32]
     L.draco_plan_set_speculation.restype = i32
     L.draco_copy_probe.argtypes = [vp, vp, i32, i64, i64, vp]
@@ -169,6 +174,10 @@ def _stream_ptr(stream) -> int:
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
+
+
+def _ptr_or_null(t):
+    return None if t is None else t.data_ptr()
 
 
 def mask_words(P: int) -> int:
@@ -268,20 +277,20 @@ class Plan:
 
     def decode_cyclic(self, messages, f, out_sum, stream=None):
         words = np.zeros(mask_words(self.P), dtype=np.uint64)
-        status = lib().draco_decode_cyclic(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+        status = lib().draco_decode_cyclic(self._h, messages.data_ptr(), messages.stride(0), _ptr_or_null(f),
                                            out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
         _check(status)
         return mask_to_bool(words, self.P), status
 
     def decode_cyclic_hostphi(self, messages, f, out_sum, stream=None):
         words = np.zeros(mask_words(self.P), dtype=np.uint64)
-        status = lib().draco_decode_cyclic_hostphi(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+        status = lib().draco_decode_cyclic_hostphi(self._h, messages.data_ptr(), messages.stride(0), _ptr_or_null(f),
                                                    out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
         _check(status)
         return mask_to_bool(words, self.P), status
 
     def decode_cyclic_async(self, messages, f, out_sum, mask_dev, status_dev, stream=None) -> None:
-        _check(lib().draco_decode_cyclic_async(self._h, messages.data_ptr(), messages.stride(0), f.data_ptr(),
+        _check(lib().draco_decode_cyclic_async(self._h, messages.data_ptr(), messages.stride(0), _ptr_or_null(f),
                                                out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                _stream_ptr(stream)))
 
@@ -298,16 +307,24 @@ class Plan:
     def decode_cyclic_wide(self, hi, lo, f, out_sum, stream=None):
         assert hi.stride(0) == lo.stride(0)
         words = np.zeros(mask_words(self.P), dtype=np.uint64)
-        status = lib().draco_decode_cyclic_wide(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), f.data_ptr(),
+        status = lib().draco_decode_cyclic_wide(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), _ptr_or_null(f),
                                                 out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
         _check(status)
         return mask_to_bool(words, self.P), status
 
     def decode_cyclic_wide_async(self, hi, lo, f, out_sum, mask_dev, status_dev, stream=None) -> None:
         assert hi.stride(0) == lo.stride(0)
-        _check(lib().draco_decode_cyclic_wide_async(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), f.data_ptr(),
+        _check(lib().draco_decode_cyclic_wide_async(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), _ptr_or_null(f),
                                                     out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                     _stream_ptr(stream)))
+
+    def set_projection_seed(self, seed: int) -> None:
+        _check(lib().draco_plan_set_projection_seed(self._h, seed))
+
+    def projection_vector(self, seed: int) -> np.ndarray:
+        f = np.zeros((self.d + 1) // 2, dtype=np.float32)
+        _check(lib().draco_projection_vector(self._h, seed, f.ctypes.data))
+        return f
 
     def set_speculation(self, enabled: bool) -> None:
         _check(lib().draco_plan_set_speculation(self._h, 1 if enabled else 0))

@@ -14,6 +14,7 @@
 
 #include "host_math.hpp"
 #include "kernels.hpp"
+#include "projection_rng.hpp"
 
 using namespace draco;
 
@@ -44,6 +45,7 @@ struct draco_plan {
     double2* b0_dev = nullptr;       // P: recombination vector when no node is flagged
     int32_t* spec_dev = nullptr;     // 2 words: speculate next / speculated now (see cyc_decode.hip)
     bool speculation = true;
+    uint64_t f_seed = 0;             // seed of the generated projection vector (f_dev == NULL)
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
     uint64_t* mask_dev = nullptr;    // kMaskWords
@@ -360,7 +362,7 @@ namespace {
 int check_cyclic_args(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
                       const float* f_dev, float* sum_dev) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
-    if (f_dev == nullptr || sum_dev == nullptr) return DRACO_EINVAL;
+    if (sum_dev == nullptr) return DRACO_EINVAL;
     int rc = check_slab(hi_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
     if (wide) {
@@ -384,7 +386,7 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     int32_t* spec = p->speculation ? p->spec_dev : nullptr;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, spec, P,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, spec, P,
                                    p->d, st));
     }
     HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
@@ -407,7 +409,7 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     const int P = p->P, s = p->s;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, nullptr,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, nullptr,
                                    P, p->d, st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
@@ -536,6 +538,19 @@ const char* draco_strerror(int status) {
 }
 
 const char* draco_last_hip_error(void) { return g_hip_detail; }
+
+int draco_plan_set_projection_seed(draco_plan* p, uint64_t seed) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
+    p->f_seed = seed;
+    return DRACO_OK;
+}
+
+int draco_projection_vector(const draco_plan* p, uint64_t seed, float* f_host) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC || f_host == nullptr) return DRACO_EINVAL;
+    const int64_t h = (p->d + 1) / 2;
+    for (int64_t i = 0; i < h; ++i) f_host[i] = projection_entry(seed, (uint64_t)i);
+    return DRACO_OK;
+}
 
 int draco_plan_set_speculation(draco_plan* p, int enabled) {
     if (p == nullptr) return DRACO_EINVAL;

@@ -2,6 +2,7 @@
 // projection f R of phi and the recombination R_{.,U} b -- and the plain copy kernel
 // used for calibration.
 #include "device_util.hpp"
+#include "projection_rng.hpp"
 
 namespace draco {
 
@@ -17,7 +18,7 @@ namespace draco {
 // recombination kernel) and the second pass over the messages is skipped.
 template <bool WIDE, bool SPEC>
 __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
-                                                 int64_t ldm, const float* __restrict__ f,
+                                                 int64_t ldm, const float* __restrict__ f, uint64_t f_seed,
                                                  double2* __restrict__ partial, const double2* __restrict__ b0,
                                                  float* __restrict__ u, int P, int64_t d,
                                                  double2 (*wsum)[kMaxNodes]) {
@@ -31,8 +32,13 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
     for (int k = 0; k < K; ++k) {
         const int64_t q = q0 + (int64_t)k * kBlock;
         const int64_t c = 2 * q;  // first complex index
-        f0[k] = (c < h) ? (double)f[c] : 0.0;
-        f1[k] = (c + 1 < h) ? (double)f[c + 1] : 0.0;
+        if (f != nullptr) {
+            f0[k] = (c < h) ? (double)f[c] : 0.0;
+            f1[k] = (c + 1 < h) ? (double)f[c + 1] : 0.0;
+        } else {  // no stored vector: make the two entries (once per tile, reused for all P rows)
+            f0[k] = (c < h) ? (double)projection_entry(f_seed, (uint64_t)c) : 0.0;
+            f1[k] = (c + 1 < h) ? (double)projection_entry(f_seed, (uint64_t)(c + 1)) : 0.0;
+        }
         nflt[k] = (c + 1 < h) ? 4 : (c < h ? 2 : 0);
     }
     double ure0[SPEC ? K : 1], uim0[SPEC ? K : 1], ure1[SPEC ? K : 1], uim1[SPEC ? K : 1];
@@ -129,15 +135,15 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
 template <bool WIDE>
 __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
                                                              const float* __restrict__ Rlo, int64_t ldm,
-                                                             const float* __restrict__ f,
+                                                             const float* __restrict__ f, uint64_t f_seed,
                                                              double2* __restrict__ partial,
                                                              const double2* __restrict__ b0, float* __restrict__ u,
                                                              int32_t* __restrict__ spec_state, int P, int64_t d) {
     __shared__ double2 wsum[kBlock / 64][kMaxNodes];
     const bool spec = spec_state != nullptr && spec_state[0] != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0 && spec_state != nullptr) spec_state[1] = spec ? 1 : 0;
-    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, partial, b0, u, P, d, wsum);
-    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, partial, b0, u, P, d, wsum);
+    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, P, d, wsum);
+    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, P, d, wsum);
 }
 
 // gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
@@ -253,16 +259,16 @@ int64_t project_tiles(int64_t d) {
     return (nvec + per - 1) / per;
 }
 
-hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, double2* partial,
-                              double2* gamma, const double2* b0, float* u, int32_t* spec_state, int P, int64_t d,
-                              hipStream_t stream) {
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, uint64_t f_seed,
+                              double2* partial, double2* gamma, const double2* b0, float* u, int32_t* spec_state,
+                              int P, int64_t d, hipStream_t stream) {
     const int64_t tiles = project_tiles(d);
     if (Rlo == nullptr)
         hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           partial, b0, u, spec_state, P, d);
+                           f_seed, partial, b0, u, spec_state, P, d);
     else
         hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           partial, b0, u, spec_state, P, d);
+                           f_seed, partial, b0, u, spec_state, P, d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);

@@ -49,9 +49,10 @@ int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
 // b0[P]: recombination vector for "no adversary"; u: output written speculatively when
 // spec_state[0] != 0 (spec_state: two device words, see cyc_decode.hip; nullptr = never).
+// f == nullptr: the entries of f are generated from f_seed (projection_rng.hpp).
 hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f,
-                              double2* partial, double2* gamma, const double2* b0, float* u,
-                              int32_t* spec_state, int P, int64_t d, hipStream_t stream);
+                              uint64_t f_seed, double2* partial, double2* gamma, const double2* b0,
+                              float* u, int32_t* spec_state, int P, int64_t d, hipStream_t stream);
 // phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
 // gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
 // their count in *nu_out.  tau: relative zero threshold for syndromes.

@@ -291,6 +291,52 @@ def test_cyc_speculative_single_pass_decode():
         ref.close()
 
 
+@pytest.mark.parametrize("P,s,d,attacks,sigma,seed", [
+    (15, 2, 10_007, ("offset", "noise"), 1.0, 0),
+    (45, 3, 70_002, ("signflip", "noise", "noise"), 1e-2, 0x9E3779B97F4A7C15),
+    (9, 4, 515, ("noise",) * 4, 1.0, 2**64 - 1),
+    (45, 3, 40_000, (), 1e-2, 12345),
+])
+def test_cyc_generated_projection_vector(P, s, d, attacks, sigma, seed):
+    """f_dev = NULL: the projection kernel draws f itself from (seed, index).  The oracle
+    draws the same vector with its own implementation of the generator and decodes with it."""
+    w = wl("cyc", P, s, d, attacks, "any", sigma)
+    print(f"case {w.name} generated f, seed={seed}", flush=True)
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        torch.cuda.synchronize()
+        R_host = c.R[:, :c.mlen].cpu().numpy()
+        fo = o.projection_vector((d + 1) // 2, seed)
+        uo, mo, so = o.decode_cyclic(R_host, fo, s, d)
+        assert so == o.OK and np.array_equal(mo, c.expected_mask())
+        c.plan.set_projection_seed(seed)
+        for form in ("device", "host"):
+            c.u.fill_(float("nan"))
+            fn = c.plan.decode_cyclic if form == "device" else c.plan.decode_cyclic_hostphi
+            mask, status = fn(c.R, None, c.u)
+            torch.cuda.synchronize()
+            assert status == B.OK and np.array_equal(mask, mo), form
+            assert rel_l2(c.u[:d].cpu().numpy(), uo) <= TOL_SUM["cyc"], form
+        # the generated vector is the one the host routine reports: feeding that one in by
+        # pointer gives the same projections, hence bit-identical output
+        u_gen = c.u.clone()
+        f_dev = torch.from_numpy(c.plan.projection_vector(seed)).to(c.device)
+        mask2, _ = c.plan.decode_cyclic_hostphi(c.R, f_dev, c.u)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask2, mo)
+        assert rel_l2(c.u[:d].cpu().numpy(), u_gen[:d].cpu().numpy()) <= 1e-6
+        # another seed: another f, same answer
+        c.plan.set_projection_seed(seed ^ 0x5555)
+        mask3, status3 = c.plan.decode_cyclic(c.R, None, c.u)
+        torch.cuda.synchronize()
+        assert status3 == B.OK and np.array_equal(mask3, mo)
+        assert rel_l2(c.u[:d].cpu().numpy(), uo) <= TOL_SUM["cyc"]
+    finally:
+        c.close()
+
+
 def test_cyc_large_s_takes_the_host_form():
     # s = 17 > 16: the default entry point falls back to host phi; the async form refuses
     w = wl("cyc", 40, 17, 1_001, ("noise", "signflip", "offset"), "any")

@@ -189,6 +189,24 @@ def test_fp32_wire_locator_matches_oracle_on_workload_shapes():
         assert sorted(np.flatnonzero(mask)) == sorted(j for j, _ in advs)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 0x9E3779B97F4A7C15, 2**64 - 1])
+def test_generated_projection_vector_matches_the_oracles_generator(seed):
+    """The library's counter-based f and the oracle's own implementation of the same
+    definition: identical fp32 values up to the last bit of libm's log/cos (at most one
+    fp32 ulp, on a vanishing fraction of entries)."""
+    d = 20_001
+    plan = B.Plan(B.CODE_CYCLIC, 5, 1, d)
+    f = plan.projection_vector(seed)
+    fo = o.projection_vector((d + 1) // 2, seed)
+    assert f.shape == fo.shape == (10_001,)
+    ulp = np.abs(f.view(np.int32).astype(np.int64) - fo.view(np.int32).astype(np.int64))
+    assert ulp.max() <= 1 and (ulp != 0).mean() <= 1e-3
+    plan2 = B.Plan(B.CODE_CYCLIC, 5, 1, 64)            # entry i does not depend on d
+    assert np.array_equal(plan2.projection_vector(seed), f[:32])
+    with pytest.raises(B.DracoError):
+        B.Plan(B.CODE_REPETITION, 3, 1, 8).projection_vector(seed)
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-GPU failure mode")
 def test_device_entry_points_fail_loudly_without_a_gpu():
     plan = B.Plan(B.CODE_REPETITION, 3, 1, 8)
