@@ -251,9 +251,10 @@ const char* draco_strerror(int status);
 const char* draco_last_hip_error(void);
 
 /* Plain device-to-device copy of a [rows][ld] fp32 slab (row_len floats used
- * per row; row_len and ld multiples of 4, pointers 16-byte aligned) with the
- * access pattern, 16-byte non-temporal accesses and occupancy limit of the
- * encoders: a calibration kernel.  Timing it gives the copy bandwidth this GPU
+ * per row; row_len and ld multiples of 4, pointers 16-byte aligned; rows <=
+ * 65535) with 16-byte non-temporal accesses, one 4 KiB piece of one row per
+ * workgroup, pieces of a row varying fastest: a calibration kernel, the fastest
+ * slab copy found on this GPU.  Timing it gives the copy bandwidth the GPU
  * sustains (the ceiling of the encoders, which read and write equal amounts);
  * profiling it gives the scale of the hardware byte counters for a known
  * 2*4*rows*row_len bytes.  Asynchronous on `stream`. */

@@ -559,7 +559,7 @@ int draco_plan_set_speculation(draco_plan* p, int enabled) {
 }
 
 int draco_copy_probe(const float* src_dev, float* dst_dev, int rows, int64_t row_len, int64_t ld, void* stream) {
-    if (src_dev == nullptr || dst_dev == nullptr || rows < 1 || row_len < 4) return DRACO_EINVAL;
+    if (src_dev == nullptr || dst_dev == nullptr || rows < 1 || rows > 65535 || row_len < 4) return DRACO_EINVAL;
     if (!aligned16(src_dev) || !aligned16(dst_dev) || (row_len & 3) != 0 || (ld & 3) != 0 || ld < row_len)
         return DRACO_EALIGN;
     HIP_TRY(launch_copy_probe(src_dev, dst_dev, rows, row_len, ld, static_cast<hipStream_t>(stream)));

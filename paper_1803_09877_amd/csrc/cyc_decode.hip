@@ -227,24 +227,16 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
     else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
 }
 
-// Plain copy of a [rows][ld] slab (row_len floats used per row) with the access
-// pattern of the encoders: a lane owns one 16-byte column of every row and has
-// eight rows in flight.  Calibration kernel for bandwidth figures and for
-// scaling hardware byte counters.
+// Plain copy of a [rows][row_len] slab (row stride ld): the fastest copy of a row-major
+// slab found on MI355X.  A workgroup moves one 4 KiB piece of one row and ends; column
+// tiles vary fastest across the grid, so at any moment the chip streams one or two rows.
+// Calibration kernel for bandwidth figures and for scaling hardware byte counters.
 __global__ __launch_bounds__(kBlock) void copy_probe_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                             int rows, int64_t row_len, int64_t ld) {
-    constexpr int UN = 8;
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     if (c0 + 4 > row_len) return;
-    for (int j0 = 0; j0 < rows; j0 += UN) {
-        float4 x[UN];
-#pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if (j0 + i < rows) x[i] = ld4(src + (int64_t)(j0 + i) * ld + c0);
-#pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if (j0 + i < rows) st4(dst + (int64_t)(j0 + i) * ld + c0, x[i]);
-    }
+    const int64_t off = (int64_t)blockIdx.y * ld + c0;
+    st4(dst + off, ld4(src + off));
 }
 
 
@@ -277,8 +269,7 @@ hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, con
 
 hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row_len, int64_t ld,
                              hipStream_t stream) {
-    allow_large_lds<copy_probe_kernel>();
-    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid_for(row_len / 4)), dim3(kBlock), throttle_lds(1, 0, 0), stream, src,
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid_for(row_len / 4), (unsigned)rows), dim3(kBlock), 0, stream, src,
                        dst, rows, row_len, ld);
     return hipGetLastError();
 }
