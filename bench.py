@@ -39,7 +39,7 @@ MEASURED_TRAFFIC_RATIO = {
 def algorithmic_bytes(w, mlen, n_honest, wide=False):
     """Bytes each kernel must move per launch (every input read once, every output written once).
     On the wide wire every message float is two fp32 words."""
-    P, d, h = w.P, w.d, (w.d + 1) // 2
+    P, d, h = w.P, w.d, mlen // 2   # h: complex entries per message = entries of f
     words = 2 if wide else 1
     return {
         "encode": (P * d + words * P * mlen) * 4,
@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the five benchmark workloads (default 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wide", action="store_true", help="cyclic workloads on the two-word (hi+lo) wire")
+    ap.add_argument("--unpacked", action="store_true",
+                    help="cyclic workloads on the unpacked wire (d complex entries per message)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the P nodes are message slabs in one GPU's HBM); "
@@ -120,7 +122,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     w = synth.WORKLOADS[args.config]
-    c = Case(w, "cuda:0", wide=args.wide)
+    c = Case(w, "cuda:0", wide=args.wide, unpacked=args.unpacked)
     c.encode()
     c.receive()
     torch.cuda.synchronize()
@@ -129,13 +131,12 @@ def main():
         mask, status = c.decode()
         assert status == 0 and np.array_equal(mask, c.expected_mask()), "decode did not find the planted adversaries"
 
-    # copy-kernel ceiling of this GPU on the same slabs (G -> Z, which the next encode overwrites)
-    ld = min(c.ld_g, c.ld_m)
-    row_len = min(w.d, c.mlen) // 4 * 4
-    assert c.ld_g == c.ld_m == ld
+    # copy-kernel ceiling of this GPU on the same slabs (R -> Z, which the next encode overwrites)
+    ld = c.ld_m
+    row_len = c.mlen // 4 * 4
 
     def copy_once():
-        B.draco_copy_probe(c.G, c.Z, w.P, row_len, ld)
+        B.draco_copy_probe(c.R, c.Z, w.P, row_len, ld)
 
     for _ in range(2):
         copy_once()
@@ -216,7 +217,7 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
     roof = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": kernels[dominant]["GBps"] / HBM_PEAK_GBS, "traffic": None}
-    ratio = None if args.wide else MEASURED_TRAFFIC_RATIO.get(w.name, {}).get(dominant)
+    ratio = None if (args.wide or args.unpacked) else MEASURED_TRAFFIC_RATIO.get(w.name, {}).get(dominant)
     if ratio is not None:
         roof["traffic"] = ratio * kernels[dominant]["algorithmic_bytes"]
 
@@ -234,7 +235,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if w.code == "rep" else "f64",
         "data": "synthetic",
-        "config": {"workload": w.name + ("+wide_wire" if args.wide else ""), "code": w.code, "P": w.P, "s": w.s,
+        "config": {"workload": w.name + ("+wide_wire" if args.wide else "") + ("+unpacked_wire" if args.unpacked else ""), "code": w.code, "P": w.P, "s": w.s,
                    "d": w.d, "wire_words": 2 if args.wide else 1,
                    "adversaries": [[int(j), a] for j, a in c.adversaries],
                    "step": "encode(all nodes) + decode" if w.decode else "encode(all nodes)"},

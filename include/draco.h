@@ -46,6 +46,11 @@ enum draco_code {
     DRACO_CODE_CYCLIC = 1      /* Sec. 3, "Cyclic Code" */
 };
 
+enum draco_wire {
+    DRACO_WIRE_PACKED = 0,   /* ceil(d/2) complex entries per message (remark closing Sec. 3); default */
+    DRACO_WIRE_UNPACKED = 1  /* d complex entries per message: Z = G W on the real gradients, as Sec. 3 defines E^Cyc */
+};
+
 enum draco_status {
     DRACO_OK = 0,
     DRACO_NO_MAJORITY = 1,   /* repetition: a group has more than s nodes that differ from its vote */
@@ -69,6 +74,20 @@ enum draco_status {
  * Host-only: works without a GPU.  *out is set only on success. */
 int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d);
 
+/* Cyclic code: choose what a message carries, before the plan is prepared
+ * (DRACO_EINVAL afterwards, for the repetition code, or for an unknown value).
+ * DRACO_WIRE_PACKED (default): pairs of real coordinates ride in one complex
+ * number, 2*ceil(d/2) floats per message.
+ * DRACO_WIRE_UNPACKED: the encoder multiplies the real gradients by W directly,
+ * a message is d complex numbers (2d floats, re/im interleaved) -- the form in
+ * which Sec. 3 states the code and proves Theorem 5, at twice the bytes.  The
+ * decoder is the same (projection on f with one entry per complex coordinate,
+ * i.e. d entries; locate; recombine) and writes the real part of R_{.,U} b to
+ * sum_dev[d].  In this mode draco_encode and every draco_decode_cyclic* form
+ * work as documented below with draco_message_len() = 2d; the wide wire,
+ * draco_encode_node and draco_encode_samples with B > P return DRACO_EINVAL. */
+int draco_plan_set_wire(draco_plan* plan, int wire);
+
 /* Allocate the plan's device-side tables and scratch on the current device
  * (a few MB: per-node coefficients, per-wave partial projections, flag
  * words).  Called implicitly by the first encode/decode if omitted; after it
@@ -81,8 +100,8 @@ void draco_plan_destroy(draco_plan* plan);
 /* Floats per message row: d for the repetition code; 2*ceil(d/2) for the
  * cyclic code (ceil(d/2) complex numbers, real and imaginary part interleaved;
  * complex coordinate i packs real coordinates 2i and 2i+1 -- the packing at
- * the end of Sec. 3 with adjacent instead of half-apart pairs).  < 0 on a
- * null plan. */
+ * the end of Sec. 3 with adjacent instead of half-apart pairs), or 2*d on
+ * the unpacked wire (draco_plan_set_wire).  < 0 on a null plan. */
 int64_t draco_message_len(const draco_plan* plan);
 
 /* A_host[j*P + k] = 1 if node j is assigned gradient k, else 0 (P*P bytes). */

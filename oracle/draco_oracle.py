@@ -510,3 +510,20 @@ def decode_cyclic(R: np.ndarray, f: np.ndarray, s: int, d: int, b_mode: str = "m
     """Wire messages [P][2h] (interleaved re/im) -> (u fp64 [d], mask, status)."""
     u_hat, mask, status = decode_cyclic_complex(wire_to_complex(R), f, s, b_mode)
     return unpack_complex(u_hat, d, "interleaved"), mask, status
+
+
+# --------------------------------------------------------------------------
+# Cyclic code on the real gradients directly (Sec. 3 before its closing remark
+# on packing): messages carry d complex entries.
+# --------------------------------------------------------------------------
+def encode_cyclic_unpacked(G: np.ndarray, s: int) -> np.ndarray:
+    """Z = G W with the real G [P][d] taken as complex; wire [P][2d] (re/im interleaved)."""
+    return complex_to_wire(encode_cyclic_complex(np.asarray(G, dtype=np.float64).astype(np.complex128), s))
+
+
+def decode_cyclic_unpacked(R: np.ndarray, f: np.ndarray, s: int, b_mode: str = "min_norm"):
+    """Wire messages [P][2d] -> (u fp64 [d] = Re(R_{.,U} b), mask, status, residual), f of
+    length d.  G 1_P is real, so the imaginary part of the recombination carries only
+    rounding; its largest magnitude is returned as `residual` for tests to bound."""
+    u_hat, mask, status = decode_cyclic_complex(wire_to_complex(R), f, s, b_mode)
+    return u_hat.real.copy(), mask, status, float(np.max(np.abs(u_hat.imag))) if u_hat.size else 0.0

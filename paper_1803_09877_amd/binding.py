@@ -28,6 +28,7 @@ HEADERS = [os.path.join(_HERE, "csrc", n) for n in (
 BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
+WIRE_PACKED, WIRE_UNPACKED = 0, 1
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
 EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
 KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE = 0, 1, 2, 3
@@ -42,7 +43,7 @@ EXPORTS = [
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe", "draco_plan_set_speculation",
-    "draco_plan_set_projection_seed", "draco_projection_vector",
+    "draco_plan_set_projection_seed", "draco_projection_vector", "draco_plan_set_wire",
 ]
 
 
@@ -138,6 +139,8 @@ def lib() -> ctypes.CDLL:
     L.draco_strerror.restype = ctypes.c_char_p
     L.draco_last_hip_error.argtypes = []
     L.draco_last_hip_error.restype = ctypes.c_char_p
+    L.draco_plan_set_wire.argtypes = [vp, i32]
+    L.draco_plan_set_wire.restype = i32
     L.draco_plan_set_projection_seed.argtypes = [vp, ctypes.c_uint64]
     L.draco_plan_set_projection_seed.restype = i32
     L.draco_projection_vector.argtypes = [vp, ctypes.c_uint64, vp]
@@ -318,11 +321,14 @@ class Plan:
                                                     out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                     _stream_ptr(stream)))
 
+    def set_wire(self, wire: int) -> None:
+        _check(lib().draco_plan_set_wire(self._h, wire))
+
     def set_projection_seed(self, seed: int) -> None:
         _check(lib().draco_plan_set_projection_seed(self._h, seed))
 
     def projection_vector(self, seed: int) -> np.ndarray:
-        f = np.zeros((self.d + 1) // 2, dtype=np.float32)
+        f = np.zeros(self.message_len // 2, dtype=np.float32)
         _check(lib().draco_projection_vector(self._h, seed, f.ctypes.data))
         return f
 

@@ -46,6 +46,7 @@ struct draco_plan {
     int32_t* spec_dev = nullptr;     // 2 words: speculate next / speculated now (see cyc_decode.hip)
     bool speculation = true;
     uint64_t f_seed = 0;             // seed of the generated projection vector (f_dev == NULL)
+    int wire = DRACO_WIRE_PACKED;    // cyclic code: packed (ceil(d/2) complex) or unpacked (d complex)
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
     uint64_t* mask_dev = nullptr;    // kMaskWords
@@ -69,9 +70,16 @@ int check_slab(const void* p, int64_t ld, int64_t row_len) {
     return DRACO_OK;
 }
 
+bool unpacked(const draco_plan* p) { return p->wire == DRACO_WIRE_UNPACKED; }
+
 int64_t message_len(const draco_plan* p) {
-    return p->code == DRACO_CODE_REPETITION ? p->d : 2 * ((p->d + 1) / 2);
+    if (p->code == DRACO_CODE_REPETITION) return p->d;
+    return unpacked(p) ? 2 * p->d : 2 * ((p->d + 1) / 2);
 }
+
+// Cyclic code: how many floats of a message the decode kernels treat as packed pairs
+// (they see the unpacked wire as the packed wire of a gradient twice as long).
+int64_t paired_len(const draco_plan* p) { return unpacked(p) ? 2 * p->d : p->d; }
 
 // Text of the last HIP failure seen by this thread (for draco_last_hip_error).
 thread_local char g_hip_detail[256] = "";
@@ -98,7 +106,7 @@ int prepare(draco_plan* p) {
     HIP_TRY(hipHostMalloc(&p->mask_pin, (kMaskWords + 1) * sizeof(uint64_t), hipHostMallocDefault));
     if (p->code == DRACO_CODE_CYCLIC) {
         HIP_TRY(hipMalloc(&p->coef_dev, (size_t)P * r * sizeof(double2)));
-        HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(p->d) * P * sizeof(double2)));
+        HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(paired_len(p)) * P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->gamma_dev, P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->b_dev, P * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->b0_dev, P * sizeof(double2)));
@@ -249,7 +257,7 @@ namespace {
 int encode_impl(draco_plan* p, const float* grads_dev, int64_t ld_g, float* hi_dev, float* lo_dev, bool wide,
                 int64_t ld_m, void* stream) {
     if (p == nullptr) return DRACO_EINVAL;
-    if (wide && p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
+    if (wide && (p->code != DRACO_CODE_CYCLIC || unpacked(p))) return DRACO_EINVAL;
     int rc = check_slab(grads_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
     rc = check_slab(hi_dev, ld_m, message_len(p));
@@ -264,6 +272,8 @@ int encode_impl(draco_plan* p, const float* grads_dev, int64_t ld_g, float* hi_d
     Timed timed(p, kEncode, st);
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep(grads_dev, ld_g, hi_dev, ld_m, p->P, p->s, p->d, st));
+    else if (unpacked(p))
+        HIP_TRY(launch_encode_cyc_real(grads_dev, ld_g, hi_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
     else
         HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, ld_m, p->coef_dev, p->P, p->s,
                                   p->d, st));
@@ -285,6 +295,7 @@ int draco_encode_wide(draco_plan* p, const float* grads_dev, int64_t ld_g, float
 int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g, float* messages_dev,
                          int64_t ld_m, void* stream) {
     if (p == nullptr || B < p->P || B % p->P != 0 || B / p->P > (1 << 20)) return DRACO_EINVAL;
+    if (unpacked(p) && B != p->P) return DRACO_EINVAL;
     const int m = (int)(B / p->P);
     if (m == 1) return encode_impl(p, samples_dev, ld_g, messages_dev, nullptr, false, ld_m, stream);
     int rc = check_slab(samples_dev, ld_g, p->d);
@@ -304,7 +315,7 @@ int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int
 
 int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
                       void* stream) {
-    if (p == nullptr || node < 0 || node >= p->P) return DRACO_EINVAL;
+    if (p == nullptr || node < 0 || node >= p->P || unpacked(p)) return DRACO_EINVAL;
     int rc = check_slab(node_grads_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
     if (message_dev == nullptr) return DRACO_EINVAL;
@@ -362,7 +373,7 @@ namespace {
 int check_cyclic_args(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,
                       const float* f_dev, float* sum_dev) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
-    if (sum_dev == nullptr) return DRACO_EINVAL;
+    if (sum_dev == nullptr || (wide && unpacked(p))) return DRACO_EINVAL;
     int rc = check_slab(hi_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
     if (wide) {
@@ -386,15 +397,15 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     int32_t* spec = p->speculation ? p->spec_dev : nullptr;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, spec, P,
-                                   p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+                                   sum_dev, unpacked(p), spec, P, paired_len(p), st));
     }
     HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
                               p->idx_dev + P, spec, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev, p->d,
-                                     st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev,
+                                     unpacked(p), paired_len(p), st));
     }
     return DRACO_OK;
 }
@@ -409,8 +420,8 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     const int P = p->P, s = p->s;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev, sum_dev, nullptr,
-                                   P, p->d, st));
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+                                   sum_dev, unpacked(p), nullptr, P, paired_len(p), st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -435,8 +446,8 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, (P + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, nullptr, P, sum_dev, p->d,
-                                     st));
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, nullptr, P, sum_dev,
+                                     unpacked(p), paired_len(p), st));
     }
     HIP_TRY(hipStreamSynchronize(st));
     return located ? DRACO_OK : DRACO_LOCATE_FAILED;
@@ -539,6 +550,13 @@ const char* draco_strerror(int status) {
 
 const char* draco_last_hip_error(void) { return g_hip_detail; }
 
+int draco_plan_set_wire(draco_plan* p, int wire) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC || p->prepared) return DRACO_EINVAL;
+    if (wire != DRACO_WIRE_PACKED && wire != DRACO_WIRE_UNPACKED) return DRACO_EINVAL;
+    p->wire = wire;
+    return DRACO_OK;
+}
+
 int draco_plan_set_projection_seed(draco_plan* p, uint64_t seed) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
     p->f_seed = seed;
@@ -547,7 +565,7 @@ int draco_plan_set_projection_seed(draco_plan* p, uint64_t seed) {
 
 int draco_projection_vector(const draco_plan* p, uint64_t seed, float* f_host) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC || f_host == nullptr) return DRACO_EINVAL;
-    const int64_t h = (p->d + 1) / 2;
+    const int64_t h = message_len(p) / 2;
     for (int64_t i = 0; i < h; ++i) f_host[i] = projection_entry(seed, (uint64_t)i);
     return DRACO_OK;
 }

@@ -20,7 +20,7 @@ template <bool WIDE, bool SPEC>
 __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
                                                  int64_t ldm, const float* __restrict__ f, uint64_t f_seed,
                                                  double2* __restrict__ partial, const double2* __restrict__ b0,
-                                                 float* __restrict__ u, int P, int64_t d,
+                                                 float* __restrict__ u, bool realout, int P, int64_t d,
                                                  double2 (*wsum)[kMaxNodes]) {
     constexpr int K = kProjectLoads;
     const int64_t h = (d + 1) / 2;                                   // complex numbers per row
@@ -111,10 +111,16 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int64_t c0 = (q0 + (int64_t)k * kBlock) * 4;
-            const int nout = clamp4(d - c0);
-            const float4 out = make_float4((float)ure0[k], (float)uim0[k], (float)ure1[k], (float)uim1[k]);
-            if (nout == 4) st4(u + c0, out);
-            else st4_partial(u + c0, out, nout);
+            if (realout) {  // unpacked wire: the sum is the real part, one float per complex entry
+                const int64_t c = c0 / 2;
+                if (c < h) u[c] = (float)ure0[k];
+                if (c + 1 < h) u[c + 1] = (float)ure1[k];
+            } else {
+                const int nout = clamp4(d - c0);
+                const float4 out = make_float4((float)ure0[k], (float)uim0[k], (float)ure1[k], (float)uim1[k]);
+                if (nout == 4) st4(u + c0, out);
+                else st4_partial(u + c0, out, nout);
+            }
         }
     }
     __syncthreads();
@@ -138,12 +144,13 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
                                                              const float* __restrict__ f, uint64_t f_seed,
                                                              double2* __restrict__ partial,
                                                              const double2* __restrict__ b0, float* __restrict__ u,
-                                                             int32_t* __restrict__ spec_state, int P, int64_t d) {
+                                                             int realout, int32_t* __restrict__ spec_state, int P,
+                                                             int64_t d) {
     __shared__ double2 wsum[kBlock / 64][kMaxNodes];
     const bool spec = spec_state != nullptr && spec_state[0] != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0 && spec_state != nullptr) spec_state[1] = spec ? 1 : 0;
-    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, P, d, wsum);
-    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, P, d, wsum);
+    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, realout != 0, P, d, wsum);
+    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, false, P, d, wsum);
 }
 
 // gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
@@ -177,7 +184,7 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
                                                    int64_t ldm,
                                                    const double2* __restrict__ b, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ nu_ptr, float* __restrict__ u,
-                                                   int64_t d) {
+                                                   bool realout, int64_t d) {
     constexpr int UN = 8;
     const int nu = *nu_ptr;  // honest nodes; written by the locator (device) or copied in by the host path
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
@@ -209,7 +216,13 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
             }
         }
     }
-    stx<FULL>(u + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
+    if (realout) {  // unpacked wire: the sum is the real part, one float per complex entry
+        const int64_t c = c0 / 2;
+        if (FULL || 2 * c < d) u[c] = (float)are0;
+        if (FULL || 2 * c + 2 < d) u[c + 1] = (float)are1;
+    } else {
+        stx<FULL>(u + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout);
+    }
 }
 
 // If the projection pass speculated (spec_state[1]) and every node turned out honest
@@ -221,10 +234,10 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
                                                                const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ nu,
                                                                const int32_t* __restrict__ spec_state, int P,
-                                                               float* __restrict__ u, int64_t d) {
+                                                               float* __restrict__ u, int realout, int64_t d) {
     if (spec_state != nullptr && spec_state[1] != 0 && *nu == P) return;
-    if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
-    else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, d);
+    if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
 }
 
 // Plain copy of a [rows][row_len] slab (row stride ld): the fastest copy of a row-major
@@ -252,15 +265,15 @@ int64_t project_tiles(int64_t d) {
 }
 
 hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, uint64_t f_seed,
-                              double2* partial, double2* gamma, const double2* b0, float* u, int32_t* spec_state,
-                              int P, int64_t d, hipStream_t stream) {
+                              double2* partial, double2* gamma, const double2* b0, float* u, bool realout,
+                              int32_t* spec_state, int P, int64_t d, hipStream_t stream) {
     const int64_t tiles = project_tiles(d);
     if (Rlo == nullptr)
         hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           f_seed, partial, b0, u, spec_state, P, d);
+                           f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
     else
         hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
-                           f_seed, partial, b0, u, spec_state, P, d);
+                           f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cyc_project_reduce_kernel, dim3((unsigned)P), dim3(kBlock), 0, stream, partial, gamma, P, tiles);
@@ -275,17 +288,17 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
 }
 
 hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
-                                const int32_t* nu, const int32_t* spec_state, int P, float* u, int64_t d,
-                                hipStream_t stream) {
+                                const int32_t* nu, const int32_t* spec_state, int P, float* u, bool realout,
+                                int64_t d, hipStream_t stream) {
     const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
     if (Rlo == nullptr) {
         allow_large_lds<cyc_recombine_kernel<false>>();
         hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
-                           nu, spec_state, P, u, d);
+                           nu, spec_state, P, u, realout ? 1 : 0, d);
     } else {
         allow_large_lds<cyc_recombine_kernel<true>>();
         hipLaunchKernelGGL(cyc_recombine_kernel<true>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
-                           nu, spec_state, P, u, d);
+                           nu, spec_state, P, u, realout ? 1 : 0, d);
     }
     return hipGetLastError();
 }

@@ -47,6 +47,35 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 
 
 
+// One node on the unpacked wire (real gradients, d complex entries out), any window
+// width; the all-node path for r > 2*kMaxS+1.  Same operation order as the windowed kernel.
+__global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const float* __restrict__ G, int64_t ldg,
+                                                                      float* __restrict__ z,
+                                                                      const double2* __restrict__ cn, int node,
+                                                                      int P, int r, int64_t d) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (c0 >= d) return;
+    const int nin = clamp4(d - c0);
+    double re[4] = {0.0, 0.0, 0.0, 0.0}, im[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < r; ++t) {
+        int k = node + t;
+        if (k >= P) k -= P;
+        const float* p = G + (int64_t)k * ldg + c0;
+        const float4 raw = (nin == 4) ? ld4(p) : ld4_partial(p, nin);
+        const double g[4] = {(double)raw.x, (double)raw.y, (double)raw.z, (double)raw.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            re[c] = fma(cn[t].x, g[c], re[c]);
+            im[c] = fma(cn[t].y, g[c], im[c]);
+        }
+    }
+    float* dst = z + 2 * c0;
+    st4_partial(dst, make_float4((float)re[0], (float)im[0], (float)re[1], (float)im[1]), clamp4(2 * (int64_t)nin));
+    st4_partial(dst + 4, make_float4((float)re[2], (float)im[2], (float)re[3], (float)im[3]),
+                clamp4(2 * (int64_t)nin - 4));
+}
+
+
 // ---------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------
@@ -65,6 +94,24 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
                                    Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, 1, d);
+    }
+#undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef, int P,
+                                  int s, int64_t d, hipStream_t stream) {
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const int r = 2 * s + 1;
+    const bool one_per_cu = s <= 3 && P >= 32;
+#define DRACO_CASE(S) \
+    case S: return launch_encode_cyc_real_s<S>(one_per_cu, grid, stream, G, ldg, Z, ldm, coef, P, d);
+    switch (s) {
+        DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        default:
+            for (int j = 0; j < P; ++j)
+                hipLaunchKernelGGL(encode_cyc_real_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
+                                   coef + (int64_t)j * r, j, P, r, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();

@@ -103,6 +103,114 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
     else encode_cyc_body<S, NB, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
 }
 
+// E^Cyc on the real gradients as Sec. 3 states it, without the packing remark that closes
+// the section: z_n = sum_t coef[n][t] * g_{(n+t) mod P} with real g, so a message has d
+// complex entries (2d floats, re/im interleaved).  Same sliding window and prefetch ring
+// as above, on four reals per lane instead of two complex numbers (two FMAs per tap and
+// coordinate).  A message row is twice as long as a gradient row, so a lane owns two PAIRS
+// of real coordinates half a wavefront span apart (8-byte loads): their complex outputs
+// are 16 bytes each and every store instruction of a wavefront writes 1 KiB contiguously.
+template <int S, int NB, bool FULL>
+__device__ __forceinline__ void encode_cyc_real_body(const float* __restrict__ G, int64_t ldg,
+                                                     float* __restrict__ Z, int64_t ldm,
+                                                     const double2* __restrict__ coef, int P, int64_t d,
+                                                     float4* head /* LDS [2S][kBlock] */) {
+    constexpr int R = 2 * S + 1;
+    // the wavefront covers 256 consecutive real coordinates; mine are cA, cA+1, cA+128, cA+129
+    const int64_t cA = (int64_t)blockIdx.x * (kBlock * 4) + (threadIdx.x >> 6) * 256 + (threadIdx.x & 63) * 2;
+    const int64_t cB = cA + 128;
+    if (!FULL && cA >= d) return;
+    const int nA = FULL ? 2 : (d - cA >= 2 ? 2 : (int)(d - cA));
+    const int nB = FULL ? 2 : (d - cB >= 2 ? 2 : (d - cB <= 0 ? 0 : (int)(d - cB)));
+
+    auto fetch = [&](int row) -> float4 {
+        const float* p = G + (int64_t)row * ldg;
+        float2 a, b;
+        if constexpr (FULL) {
+            a = ld2(p + cA);
+            b = ld2(p + cB);
+        } else {
+            a = ld2_partial(p + cA, nA);
+            b = ld2_partial(p + cB, nB);
+        }
+        return make_float4(a.x, a.y, b.x, b.y);
+    };
+
+    double w[R][4];  // window slot = row index mod R
+    auto put = [&](int slot, const float4& raw) {
+        w[slot][0] = (double)raw.x;
+        w[slot][1] = (double)raw.y;
+        w[slot][2] = (double)raw.z;
+        w[slot][3] = (double)raw.w;
+    };
+    auto issue = [&](int n0, float4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int kk = n0 + uu + 2 * S;
+            if (n0 + uu < P) {
+                if (kk < P) buf[uu] = fetch(kk);
+                else buf[uu] = head[(kk - P) * kBlock + threadIdx.x];
+            }
+        }
+    };
+    auto consume = [&](int n0, const float4 (&buf)[R]) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                put((uu + 2 * S) % R, buf[uu]);
+                const double2* cn = coef + (int64_t)n * R;
+                double re[4] = {0.0, 0.0, 0.0, 0.0}, im[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    const double cr = cn[t].x, ci = cn[t].y;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        re[c] = fma(cr, w[slot][c], re[c]);
+                        im[c] = fma(ci, w[slot][c], im[c]);
+                    }
+                }
+                float* dst = Z + (int64_t)n * ldm;
+                stx<FULL>(dst + 2 * cA, make_float4((float)re[0], (float)im[0], (float)re[1], (float)im[1]), 2 * nA);
+                stx<FULL>(dst + 2 * cB, make_float4((float)re[2], (float)im[2], (float)re[3], (float)im[3]), 2 * nB);
+            }
+        }
+    };
+
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const float4 raw = fetch(k);
+        head[k * kBlock + threadIdx.x] = raw;
+        put(k, raw);
+    }
+    float4 buf[NB][R];
+#pragma unroll
+    for (int b = 0; b < NB - 1; ++b)
+        if (b * R < P) issue(b * R, buf[b]);
+    for (int n0 = 0; n0 < P; n0 += NB * R) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int cur = n0 + b * R;
+            if (cur < P) {
+                const int nxt = cur + (NB - 1) * R;
+                if (nxt < P) issue(nxt, buf[(b + NB - 1) % NB]);
+                consume(cur, buf[b]);
+            }
+        }
+    }
+}
+
+template <int S, int NB>
+__global__ __launch_bounds__(kBlock) void encode_cyc_real_kernel(const float* __restrict__ G, int64_t ldg,
+                                                                 float* __restrict__ Z, int64_t ldm,
+                                                                 const double2* __restrict__ coef, int P,
+                                                                 int64_t d) {
+    extern __shared__ float4 head[];  // [2S][kBlock]
+    if (block_is_full(d)) encode_cyc_real_body<S, NB, true>(G, ldg, Z, ldm, coef, P, d, head);
+    else encode_cyc_real_body<S, NB, false>(G, ldg, Z, ldm, coef, P, d, head);
+}
+
 // E^Cyc when every unit gradient is the sum of m = B/P per-sample gradients (rows k*m ..
 // k*m+m-1 of the sample slab): the same sliding window, but a window entry is the fp64
 // sum of m rows, formed as the rows arrive; the first 2s unit sums are parked in LDS in
@@ -211,6 +319,10 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* _
 template <int S>
 hipError_t launch_encode_cyc_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg, float* Z,
                                float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
+// Same for the unpacked wire (real gradients in, d complex entries out).
+template <int S>
+hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg,
+                                    float* Z, int64_t ldm, const double2* coef, int P, int64_t d);
 // Same for the B > P form (m per-sample rows per unit gradient).
 template <int S>
 hipError_t launch_encode_cyc_multi_s(dim3 grid, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,

@@ -30,6 +30,19 @@ __device__ __forceinline__ void st4(float* p, float4 v) {
     __builtin_nontemporal_store(w, reinterpret_cast<vfloat4*>(p));
 }
 
+typedef float vfloat2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float2 ld2(const float* p) {
+    const vfloat2 v = __builtin_nontemporal_load(reinterpret_cast<const vfloat2*>(p));
+    return make_float2(v.x, v.y);
+}
+// Guarded load of up to 2 floats; missing ones read as 0.
+__device__ __forceinline__ float2 ld2_partial(const float* p, int n) {
+    float2 v = make_float2(0.f, 0.f);
+    if (n > 0) v.x = p[0];
+    if (n > 1) v.y = p[1];
+    return v;
+}
+
 // Guarded load of up to 4 floats; missing ones read as 0.
 __device__ __forceinline__ float4 ld4_partial(const float* p, int n) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);

@@ -41,6 +41,9 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
 // Zlo / zlo / Rlo below: second word of the wide wire (message = hi + lo), or nullptr.
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm,
                              const double2* coef, int P, int s, int64_t d, hipStream_t stream);
+// Unpacked wire: real gradients [P][d] in, messages of d complex entries (2d floats) out.
+hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
+                                  int P, int s, int64_t d, hipStream_t stream);
 // Gn holds only the node's 2s+1 gradients, in assignment order.
 hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef,
                                   int node, int P, int s, int64_t d, hipStream_t stream);
@@ -50,9 +53,12 @@ int64_t project_tiles(int64_t d);
 // b0[P]: recombination vector for "no adversary"; u: output written speculatively when
 // spec_state[0] != 0 (spec_state: two device words, see cyc_decode.hip; nullptr = never).
 // f == nullptr: the entries of f are generated from f_seed (projection_rng.hpp).
+// d is the number of floats a message carries (odd d: one more, zero); realout (unpacked
+// wire, messages of d/2 complex entries): u receives only the real parts, d/2 floats.
 hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f,
                               uint64_t f_seed, double2* partial, double2* gamma, const double2* b0,
-                              float* u, int32_t* spec_state, int P, int64_t d, hipStream_t stream);
+                              float* u, bool realout, int32_t* spec_state, int P, int64_t d,
+                              hipStream_t stream);
 // phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
 // gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
 // their count in *nu_out.  tau: relative zero threshold for syndromes.
@@ -64,7 +70,7 @@ hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, con
 // u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
 hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b,
                                 const int32_t* idx, const int32_t* nu, const int32_t* spec_state, int P,
-                                float* u, int64_t d, hipStream_t stream);
+                                float* u, bool realout, int64_t d, hipStream_t stream);
 
 // dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
 // (bandwidth / counter calibration).

@@ -20,14 +20,18 @@ class Case:
     f  [ceil(d/2)] phi's random projection vector (cyclic code)
     """
 
-    def __init__(self, w: synth.Workload, device: str = "cuda:0", wide: bool = False):
-        """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word)."""
+    def __init__(self, w: synth.Workload, device: str = "cuda:0", wide: bool = False, unpacked: bool = False):
+        """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word);
+        unpacked: cyclic code with d complex entries per message (f then has d entries)."""
         self.w = w
         self.wide = wide
-        assert not (wide and w.code != "cyc")
+        self.unpacked = unpacked
+        assert not ((wide or unpacked) and w.code != "cyc") and not (wide and unpacked)
         self.device = torch.device(device)
         code = B.CODE_REPETITION if w.code == "rep" else B.CODE_CYCLIC
         self.plan = B.Plan(code, w.P, w.s, w.d)
+        if unpacked:
+            self.plan.set_wire(B.WIRE_UNPACKED)
         self.mlen = self.plan.message_len
         self.ld_g = synth.padded_len(w.d)
         self.ld_m = synth.padded_len(self.mlen)
@@ -39,7 +43,7 @@ class Case:
         self.u = torch.zeros(synth.padded_len(w.d), dtype=torch.float32, device=self.device)
         self.f = None
         if w.code == "cyc":
-            self.f = synth.make_projection((w.d + 1) // 2, w.seed, device=self.device)
+            self.f = synth.make_projection(self.mlen // 2, w.seed, device=self.device)
         self.adversaries = w.adversaries()
         self.plan.prepare()
 

@@ -135,6 +135,54 @@ def test_full_size_cyclic_wide_wire_end_to_end():
         c.close()
 
 
+def test_full_size_cyclic_unpacked_wire():
+    """Config 4 (P=45, s=3, d=25.6M) on the unpacked wire (messages of d complex entries,
+    9.2 GB): encoder windows against the oracle's Z = G W, the mask against the oracle's
+    phi on the whole-slab projection, recombined windows against the oracle's b."""
+    w = synth.WORKLOADS[4]
+    print(f"full-size unpacked {w.name}", flush=True)
+    c = Case(w, unpacked=True)
+    try:
+        d = w.d
+        c.encode()
+        torch.cuda.synchronize()
+        wins = [(0, 2048), (d // 2 + 1025, d // 2 + 1025 + 1501), (d - 1201, d)]
+        for a, b in wins:
+            Zo = o.encode_cyclic_unpacked(c.G[:, a:b].cpu().numpy(), w.s)
+            Zg = c.Z[:, 2 * a:2 * b].cpu().numpy()
+            for j in range(w.P):
+                assert rel_l2(Zg[j], Zo[j]) <= 1e-6, (a, b, j)
+        assert torch.isfinite(c.Z[:, :c.mlen]).all()
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        assert torch.isfinite(c.u[:d]).all()
+        f = c.f.cpu().numpy()
+        gamma = np.zeros(w.P, dtype=np.complex128)
+        step = 1 << 20
+        for a in range(0, d, step):
+            b = min(d, a + step)
+            gamma += o.project(o.wire_to_complex(c.R[:, 2 * a:2 * b].cpu().numpy()), f[a:b])
+        mo, _, so = o.phi_from_projection(gamma, w.s)
+        assert so == 0 and np.array_equal(mo, mask)
+        bo = o.solve_b(w.P, w.s, [j for j in range(w.P) if not mo[j]], "min_norm")
+        for a, b in wins:
+            Rc = o.wire_to_complex(c.R[:, 2 * a:2 * b].cpu().numpy())
+            uh = np.zeros(b - a, dtype=np.complex128)
+            for j in range(w.P):
+                if not mo[j]:
+                    uh += bo[j] * Rc[j]
+            assert rel_l2(c.u[a:b].cpu().numpy(), uh.real) <= 1e-4
+        ref = c.G[:, :d].double().sum(0)
+        err = float((c.u[:d].double() - ref).norm() / ref.norm())
+        print(f"   end-to-end rel-L2 vs true sum (unpacked wire): {err:.3e}", flush=True)
+        assert err <= 1e-3
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("code,P,s,d,attacks,placement,sigma", [
     ("rep", 45, 2, 11_173_001, ("signflip", "signflip"), "distinct_groups", 1e-2),   # ResNet-18's count + 1: odd, ragged
     ("cyc", 15, 2, 4_000_001, ("offset", "offset"), "any", 1.0),

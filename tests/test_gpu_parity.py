@@ -337,6 +337,93 @@ def test_cyc_generated_projection_vector(P, s, d, attacks, sigma, seed):
         c.close()
 
 
+@pytest.mark.parametrize("P,s,d,attacks,sigma", [
+    (5, 1, 1, ("noise",), 1.0),
+    (5, 2, 7, ("signflip", "noise"), 1.0),
+    (15, 2, 10_007, ("offset", "offset"), 1.0),
+    (15, 2, 4096, (), 1.0),
+    (45, 3, 30_001, ("noise", "signflip", "noise"), 1e-2),
+    (9, 4, 2050, ("noise",) * 4, 1.0),
+    (15, 7, 1030, ("signflip",) * 7, 1.0),
+    (17, 8, 515, ("noise",) * 8, 1.0),                # window wider than the register kernels: per-node path
+    (66, 1, 777, ("noise",), 1.0),
+])
+def test_cyc_unpacked_wire(P, s, d, attacks, sigma):
+    """Sec. 3's cyclic code on the real gradients (messages of d complex entries): encoder
+    against the oracle's Z = G W, decoder (device and host locator) against the oracle on
+    the same received messages, and Definition 2 end to end."""
+    w = wl("cyc", P, s, d, attacks, "any", sigma)
+    print(f"case {w.name} unpacked attacks={attacks}", flush=True)
+    c = Case(w, unpacked=True)
+    try:
+        assert c.mlen == 2 * d and c.f.numel() == d
+        c.Z.fill_(float("nan"))
+        c.encode()
+        torch.cuda.synchronize()
+        Zg = c.Z[:, :c.mlen].cpu().numpy()
+        Zo = o.encode_cyclic_unpacked(c.G[:, :d].cpu().numpy(), s)
+        for j in range(P):
+            assert rel_l2(Zg[j], Zo[j]) <= TOL_MSG, f"message {j}"
+        if c.ld_m > c.mlen:
+            assert torch.isnan(c.Z[:, c.mlen:]).all()
+        c.receive()
+        R_host = c.R[:, :c.mlen].cpu().numpy()
+        uo, mo, so, resid = o.decode_cyclic_unpacked(R_host, c.f.cpu().numpy(), s)
+        assert so == o.OK and np.array_equal(mo, c.expected_mask())
+        forms = ((False, True) if s <= 16 else (True,))
+        for hostphi in forms:
+            c.u.fill_(float("nan"))
+            mask, status = c.decode(hostphi=hostphi)
+            torch.cuda.synchronize()
+            assert status == B.OK and np.array_equal(mask, mo), hostphi
+            ug = c.u[:d].cpu().numpy()
+            assert np.isfinite(ug).all()
+            assert rel_l2(ug, uo) <= TOL_SUM["cyc"], hostphi
+            if c.u.numel() > d:
+                assert torch.isnan(c.u[d:]).all()
+        if s <= 16:   # stream-ordered form and the generated f
+            mask_dev = torch.zeros(4, dtype=torch.int64, device=c.device)
+            status_dev = torch.full((1,), -7, dtype=torch.int32, device=c.device)
+            c.plan.set_projection_seed(99)
+            c.u.fill_(float("nan"))
+            c.plan.decode_cyclic_async(c.R, None, c.u, mask_dev, status_dev)
+            torch.cuda.synchronize()
+            assert int(status_dev.item()) == 0
+            words = mask_dev.cpu().numpy().view(np.uint64)
+            assert np.array_equal(B.mask_to_bool(words, P), mo)
+            u2, m2, s2, _ = o.decode_cyclic_unpacked(R_host, o.projection_vector(d, 99), s)
+            assert rel_l2(c.u[:d].cpu().numpy(), u2) <= TOL_SUM["cyc"]
+        ref = c.G[:, :d].double().sum(0).cpu().numpy()     # Definition 2 up to the fp32 wire
+        assert rel_l2(c.u[:d].cpu().numpy(), ref) <= (2e-3 if P >= 45 else 1e-4)
+    finally:
+        c.close()
+
+
+def test_cyc_unpacked_wire_rejects_what_it_does_not_support():
+    w = wl("cyc", 9, 2, 100)
+    c = Case(w, unpacked=True)
+    try:
+        lo = torch.zeros_like(c.Z)
+        with pytest.raises(B.DracoError) as e:
+            c.plan.encode_wide(c.G, c.Z, lo)
+        assert e.value.status == B.EINVAL
+        with pytest.raises(B.DracoError) as e:
+            c.plan.decode_cyclic_wide(c.Z, lo, c.f, c.u)
+        assert e.value.status == B.EINVAL
+        with pytest.raises(B.DracoError) as e:
+            c.plan.encode_node(0, c.G[:5], c.Z[0])
+        assert e.value.status == B.EINVAL
+        with pytest.raises(B.DracoError) as e:                  # the wire is fixed once the plan is prepared
+            c.plan.set_wire(B.WIRE_PACKED)
+        assert e.value.status == B.EINVAL
+        narrow = torch.zeros((9, 104), dtype=torch.float32, device=c.device)   # a packed-size slab is too short
+        with pytest.raises(B.DracoError) as e:
+            c.plan.encode(c.G, narrow)
+        assert e.value.status == B.EALIGN
+    finally:
+        c.close()
+
+
 def test_cyc_large_s_takes_the_host_form():
     # s = 17 > 16: the default entry point falls back to host phi; the async form refuses
     w = wl("cyc", 40, 17, 1_001, ("noise", "signflip", "offset"), "any")

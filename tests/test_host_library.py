@@ -41,6 +41,23 @@ def test_strerror_and_message_len():
     assert B.Plan(B.CODE_CYCLIC, 6, 1, 12).message_len == 12
 
 
+def test_wire_selection():
+    plan = B.Plan(B.CODE_CYCLIC, 6, 1, 11)
+    assert plan.message_len == 12
+    plan.set_wire(B.WIRE_UNPACKED)
+    assert plan.message_len == 22
+    assert plan.projection_vector(3).shape == (11,)
+    plan.set_wire(B.WIRE_PACKED)
+    assert plan.message_len == 12
+    for bad in (2, -1):
+        with pytest.raises(B.DracoError) as e:
+            plan.set_wire(bad)
+        assert e.value.status == B.EINVAL
+    with pytest.raises(B.DracoError) as e:
+        B.Plan(B.CODE_REPETITION, 6, 1, 11).set_wire(B.WIRE_UNPACKED)
+    assert e.value.status == B.EINVAL
+
+
 @pytest.mark.parametrize("P,s", [(3, 1), (15, 1), (15, 2), (45, 2), (15, 7), (6, 0)])
 def test_repetition_plan_matches_oracle(P, s):
     plan = B.Plan(B.CODE_REPETITION, P, s, 16)

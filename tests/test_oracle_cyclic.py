@@ -412,3 +412,56 @@ def test_projection_generator_is_standard_normal_about_one():
     assert abs(np.corrcoef(f, g)[0, 1]) < 0.01
     assert np.abs(f - 1.0).max() < 5.9 and np.isfinite(f).all()
     assert len(np.unique(f)) > 0.98 * n
+
+
+# ------------------------------------------------------------ unpacked wire --
+@pytest.mark.parametrize("P,s", TINY)
+@pytest.mark.parametrize("kind", ["noise", "signflip", "one_coord"])
+def test_unpacked_definition2_every_adversary_subset(P, s, kind):
+    """Sec. 3 as stated (Z = G W on the real gradients, d complex entries per message):
+    every adversary set of size <= s is located and Re(R_U b) = G 1_P; the imaginary
+    part of the recombination is rounding only."""
+    d = 11
+    G = _grads(P, d, 3 * P + s)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Z = o.encode_cyclic_unpacked(G, s)
+    assert Z.shape == (P, 2 * d)
+    f = _f(d, P + 3)
+    rng = np.random.default_rng(P * 19 + s)
+    for a in range(0, s + 1):
+        for V in itertools.combinations(range(P), a):
+            R = Z.copy()
+            for j in V:
+                _attack64(R, j, kind, rng)
+            u, mask, st, resid = o.decode_cyclic_unpacked(R, f, s)
+            assert st == o.OK
+            assert sorted(np.flatnonzero(mask)) == sorted(V)
+            assert np.linalg.norm(u - ref) <= 1e-9 * np.linalg.norm(ref)
+            assert resid <= 1e-9 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("P,s,d", [(7, 2, 10), (9, 4, 13), (15, 2, 32)])
+def test_packing_is_a_linear_recombination_of_the_unpacked_messages(P, s, d):
+    """The remark closing Sec. 3: packing coordinates (a, b) into a + ib commutes with the
+    linear encoder, so the packed message is z[a] + i z[b] of the unpacked one, entry by
+    entry -- for the library's adjacent pairing and for the paper's half-apart pairing."""
+    G = _grads(P, d, 77 + P)
+    Zu = o.wire_to_complex(o.encode_cyclic_unpacked(G, s))                      # [P][d] complex
+    dp = d + (d & 1)
+    Zu_pad = np.concatenate([Zu, np.zeros((P, dp - d), dtype=complex)], axis=1)
+    Zp = o.wire_to_complex(o.encode_cyclic(G, s, "interleaved"))
+    assert np.allclose(Zp, Zu_pad[:, 0::2] + 1j * Zu_pad[:, 1::2], rtol=0, atol=1e-12 * np.abs(Zp).max())
+    Zh = o.wire_to_complex(o.encode_cyclic(G, s, "halves"))
+    h = (d + 1) // 2
+    assert np.allclose(Zh, Zu_pad[:, :h] + 1j * Zu_pad[:, h:], rtol=0, atol=1e-12 * np.abs(Zh).max())
+
+
+def test_unpacked_messages_of_real_gradients_have_hermitian_structure_in_W_only():
+    """An unpacked message is W_{.,j}^T applied to real numbers: its real and imaginary
+    parts are the real gradients times Re W and Im W separately."""
+    P, s, d = 9, 2, 6
+    G = _grads(P, d, 5).astype(np.float64)
+    W = o.cyclic_weights(P, s)
+    Zc = o.wire_to_complex(o.encode_cyclic_unpacked(G, s))
+    assert np.allclose(Zc.real, W.real.T @ G, atol=1e-12 * np.abs(Zc).max())
+    assert np.allclose(Zc.imag, W.imag.T @ G, atol=1e-12 * np.abs(Zc).max())
