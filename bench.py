@@ -28,11 +28,11 @@ KIND_NAMES = ["encode", "vote", "project", "recombine"]
 
 # HBM bytes per launch divided by the algorithmic bytes, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this file, each counter scaled by what it
-# reads for the library's plain copy kernel (fetch x2.0000, write x1.0000);
+# reads for the library's plain copy kernel (fetch x2.0000, write x0.9995);
 # the figures are in profiles/<workload>_kernels.md.
 MEASURED_TRAFFIC_RATIO = {
-    "rep_P45_s2_d11.2M": {"encode": 1.0000, "vote": 1.0030},
-    "cyc_P45_s3_d25.6M": {"encode": 1.0001, "project": 1.0005, "recombine": 1.0000},
+    "rep_P45_s2_d11.2M": {"encode": 0.9998, "vote": 1.0000},
+    "cyc_P45_s3_d25.6M": {"encode": 0.9999, "project": 1.0022, "recombine": 1.0000},
 }
 
 
