@@ -55,13 +55,16 @@ enum draco_status {
     DRACO_OK = 0,
     DRACO_NO_MAJORITY = 1,   /* repetition: a group has more than s nodes that differ from its vote */
     DRACO_LOCATE_FAILED = 2, /* cyclic: no set of at most s nodes accounts for the syndromes */
-    DRACO_EINVAL = -1,       /* null pointer, P < 1, s < 0, 2s+1 > P, (2s+1) does not divide P (repetition), d < 1, P > DRACO_MAX_NODES, wrong code for the call */
+    DRACO_EINVAL = -1,       /* null pointer, P < 1, s < 0, 2s+1 > P, (2s+1) does not divide P (repetition), d < 1, P > DRACO_MAX_NODES, d > DRACO_MAX_DIM, wrong code for the call */
     DRACO_EALIGN = -2,       /* pointer or stride alignment (see above) */
     DRACO_EHIP = -3,         /* a HIP runtime call failed (no device, out of memory, launch failure) */
     DRACO_ENOMEM = -4        /* host allocation failed */
 };
 
 #define DRACO_MAX_NODES 256
+/* Largest gradient dimension: the kernels index rows with 64-bit offsets, the
+ * limit is the launch size of the one-coordinate-per-lane kernels (2^32 lanes). */
+#define DRACO_MAX_DIM 4294963200LL
 
 /* ---- plan ------------------------------------------------------------- */
 

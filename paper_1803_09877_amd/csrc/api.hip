@@ -171,7 +171,7 @@ extern "C" {
 int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d) {
     if (out == nullptr) return DRACO_EINVAL;
     if (code != DRACO_CODE_REPETITION && code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
-    if (P < 1 || P > DRACO_MAX_NODES || s < 0 || d < 1) return DRACO_EINVAL;
+    if (P < 1 || P > DRACO_MAX_NODES || s < 0 || d < 1 || d > DRACO_MAX_DIM) return DRACO_EINVAL;
     if (2 * (int64_t)s + 1 > P) return DRACO_EINVAL;                               // corollary to Theorem 1
     if (code == DRACO_CODE_REPETITION && P % (2 * s + 1) != 0) return DRACO_EINVAL; // "Suppose 2s+1 divides P"
     draco_plan* p = new (std::nothrow) draco_plan();

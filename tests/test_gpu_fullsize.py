@@ -228,6 +228,58 @@ def test_odd_and_unaligned_lengths_at_scale(code, P, s, d, attacks, placement, s
         c.close()
 
 
+@pytest.mark.parametrize("code", ["rep", "cyc"])
+def test_dimension_beyond_two_to_the_31(code):
+    """d = 2^31 + 5003 (odd): every float offset inside a row, and every byte offset, needs
+    64 bits.  P = 3, s = 1 keeps the three slabs at 26 GB each.  Windows at the head, across
+    the 2^31 boundary and at the ragged tail against the oracle; Definition 2 over the
+    whole vector, accumulated on the GPU in fp64 chunk by chunk."""
+    d = (1 << 31) + 5003
+    w = synth.Workload(name=f"{code}_huge", code=code, P=3, s=1, d=d, sigma=1.0, attacks=("signflip",),
+                       placement="any", seed=synth.SEED_BASE + 77)
+    print(f"huge-d {code}: d={d}", flush=True)
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        wins = [(0, 2048), ((1 << 31) - 1030, (1 << 31) + 1030), (d - 1501 - (d - 1501) % 2, d)]
+        U = [j for j in range(3) if not mask[j]]
+        for a, b in wins:
+            G = c.G[:, a:b].cpu().numpy()
+            if code == "rep":
+                Zo = o.encode_repetition(G, 1)
+                Zg = c.Z[:, a:b].cpu().numpy()
+                uo, mo, so = o.decode_repetition(c.R[:, a:b].cpu().numpy(), 1)
+                assert so == 0 and np.array_equal(mo, mask)
+                tol = 1e-5
+            else:
+                Zo = o.encode_cyclic(G, 1)
+                Zg = c.Z[:, a:a + Zo.shape[1]].cpu().numpy()
+                Rc = o.wire_to_complex(c.R[:, a:a + Zo.shape[1]].cpu().numpy())
+                bo = o.solve_b(3, 1, U, "min_norm")
+                uo = o.unpack_complex(sum(bo[j] * Rc[j] for j in U), b - a)
+                tol = 1e-4
+            for j in range(3):
+                assert rel_l2(Zg[j], Zo[j]) <= 1e-6, (a, b, j)
+            assert rel_l2(c.u[a:b].cpu().numpy(), uo) <= tol, (a, b)
+        num = den = 0.0
+        step = 1 << 28
+        for a in range(0, d, step):
+            b = min(d, a + step)
+            ref = c.G[:, a:b].double().sum(0)
+            num += float((c.u[a:b].double() - ref).pow(2).sum())
+            den += float(ref.pow(2).sum())
+        assert np.isfinite(num) and (num / den) ** 0.5 <= 1e-6
+        if c.u.numel() > d:
+            assert torch.isnan(c.u[d:]).all()
+    finally:
+        c.close()
+
+
 def _time_ms(fn, reps=5):
     fn()
     torch.cuda.synchronize()

@@ -112,6 +112,7 @@ def test_rep_config0_exact_recipe():
     (34, 8, 777, ("signflip", "noise", "constant"), "any"),
     (66, 1, 555, ("noise",), "any"),                   # more than 64 nodes: second mask word
     (255, 2, 300, ("noise", "signflip"), "distinct_groups"),
+    (256, 0, 1030, (), "any"),                         # the largest P the library takes (r = 1: plain sum)
 ])
 def test_rep_parity(P, s, d, attacks, placement):
     for seed in range(2):
@@ -184,6 +185,9 @@ def test_rep_async_form_and_determinism():
     (15, 7, 6_001, ("noise", "signflip", "offset", "constant", "noise", "signflip", "offset"), "any", 1.0, 1e-5),
     (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0, 1e-4),   # r = 17: generic encoder path
     (70, 2, 2_001, ("noise", "signflip"), "any", 1.0, None),       # second mask word
+    (256, 1, 301, ("noise",), "any", 1.0, 1e-3),                   # the largest P the library takes
+    (128, 2, 999, ("signflip", "noise"), "any", 1.0, None),        # wide dynamic range of W
+    (200, 3, 500, ("noise", "noise"), "any", 1.0, None),           # the fp32 wire drowns the sum here; parity still holds
 ])
 def test_cyc_parity(P, s, d, attacks, placement, sigma, e2e):
     for seed in range(2):

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("code,P,s,d", [
-    (0, 10, 1, 8), (0, 4, 2, 8), (1, 4, 2, 8), (1, 0, 0, 8), (0, 5, -1, 8), (2, 3, 1, 8), (1, 5, 1, 0), (1, 300, 1, 8)])
+    (0, 10, 1, 8), (0, 4, 2, 8), (1, 4, 2, 8), (1, 0, 0, 8), (0, 5, -1, 8), (2, 3, 1, 8), (1, 5, 1, 0), (1, 300, 1, 8), (0, 3, 1, 2**32)])
 def test_plan_create_rejects_bad_parameters(code, P, s, d):
     with pytest.raises(B.DracoError) as e:
         B.Plan(code, P, s, d)
