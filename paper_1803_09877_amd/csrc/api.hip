@@ -49,13 +49,12 @@ struct draco_plan {
     int wire = DRACO_WIRE_PACKED;    // cyclic code: packed (ceil(d/2) complex) or unpacked (d complex)
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
-    uint64_t* mask_dev = nullptr;    // kMaskWords
-    int32_t* status_dev = nullptr;   // 1
     // pinned host staging
     double* gamma_pin = nullptr;     // 2P
     double* b_pin = nullptr;         // 2P
     int32_t* idx_pin = nullptr;      // P
-    uint64_t* mask_pin = nullptr;    // kMaskWords + 1 (status in the last word)
+    uint64_t* mask_pin = nullptr;    // pinned, device-mapped: kMaskWords + 1 (status in the last word)
+    uint64_t* mask_pin_dev = nullptr;  // the same memory as the device addresses it
 
     Timer timers[kKinds];
 };
@@ -101,9 +100,10 @@ int prepare(draco_plan* p) {
     const int P = p->P, r = 2 * p->s + 1;
     HIP_TRY(hipMalloc(&p->flags_dev, kMaskWords * sizeof(uint64_t)));
     HIP_TRY(hipMemset(p->flags_dev, 0, kMaskWords * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&p->mask_dev, kMaskWords * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&p->status_dev, sizeof(int32_t)));
-    HIP_TRY(hipHostMalloc(&p->mask_pin, (kMaskWords + 1) * sizeof(uint64_t), hipHostMallocDefault));
+    // The synchronous decoders let the last kernel write mask and status straight into
+    // mapped host memory: the host reads them after the stream wait, no copy commands.
+    HIP_TRY(hipHostMalloc(&p->mask_pin, (kMaskWords + 1) * sizeof(uint64_t), hipHostMallocMapped));
+    HIP_TRY(hipHostGetDevicePointer(reinterpret_cast<void**>(&p->mask_pin_dev), p->mask_pin, 0));
     if (p->code == DRACO_CODE_CYCLIC) {
         HIP_TRY(hipMalloc(&p->coef_dev, (size_t)P * r * sizeof(double2)));
         HIP_TRY(hipMalloc(&p->partial_dev, (size_t)project_tiles(paired_len(p)) * P * sizeof(double2)));
@@ -202,8 +202,6 @@ void draco_plan_destroy(draco_plan* p) {
         (void)hipFree(p->spec_dev);
         (void)hipFree(p->idx_dev);
         (void)hipFree(p->flags_dev);
-        (void)hipFree(p->mask_dev);
-        (void)hipFree(p->status_dev);
         (void)hipHostFree(p->gamma_pin);
         (void)hipHostFree(p->b_pin);
         (void)hipHostFree(p->idx_pin);
@@ -355,12 +353,11 @@ int draco_decode_repetition(draco_plan* p, const float* messages_dev, int64_t ld
     if (p == nullptr || mask_host == nullptr) return DRACO_EINVAL;
     int rc = prepare(p);
     if (rc != DRACO_OK) return rc;
-    rc = draco_decode_repetition_async(p, messages_dev, ld_m, sum_dev, p->mask_dev, p->status_dev, stream);
+    rc = draco_decode_repetition_async(p, messages_dev, ld_m, sum_dev, p->mask_pin_dev,
+                                       reinterpret_cast<int32_t*>(p->mask_pin_dev + kMaskWords), stream);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int words = (p->P + 63) / 64;
-    HIP_TRY(hipMemcpyAsync(p->mask_pin, p->mask_dev, words * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipMemcpyAsync(p->mask_pin + kMaskWords, p->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     for (int w = 0; w < words; ++w) mask_host[w] = p->mask_pin[w];
     int32_t status;
@@ -460,12 +457,11 @@ int decode_cyclic_impl(draco_plan* p, const float* hi_dev, const float* lo_dev, 
         return decode_cyclic_hostphi_impl(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev, mask_host, stream);
     int rc = prepare(p);
     if (rc != DRACO_OK) return rc;
-    rc = decode_cyclic_async_impl(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev, p->mask_dev, p->status_dev, stream);
+    rc = decode_cyclic_async_impl(p, hi_dev, lo_dev, wide, ld_m, f_dev, sum_dev, p->mask_pin_dev,
+                                  reinterpret_cast<int32_t*>(p->mask_pin_dev + kMaskWords), stream);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int words = (p->P + 63) / 64;
-    HIP_TRY(hipMemcpyAsync(p->mask_pin, p->mask_dev, words * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipMemcpyAsync(p->mask_pin + kMaskWords, p->status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     for (int w = 0; w < words; ++w) mask_host[w] = p->mask_pin[w];
     int32_t status;
