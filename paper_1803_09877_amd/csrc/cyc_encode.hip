@@ -47,6 +47,72 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 
 
 
+// All nodes for any window width r = 2s+1 (used when r exceeds the register-window
+// kernels): the window lives in LDS as a ring of r raw rows per lane (each lane reads back
+// only what it wrote: no barrier), rows are fetched Q ahead into registers, and the last
+// 2s nodes re-read rows 0..2s-1 from memory (2s/P more reads than the register kernels).
+// Same operation order as the one-node kernel: results are bit-identical to it.
+template <bool FULL>
+__device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G, int64_t ldg,
+                                                     float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
+                                                     const double2* __restrict__ coef, int P, int r, int64_t d,
+                                                     float4* ring /* LDS [r][kBlock] */) {
+    constexpr int Q = 4;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (!FULL && c0 >= mlen) return;
+    const int nin = FULL ? 4 : clamp4(d - c0);
+    const int nout = FULL ? 4 : clamp4(mlen - c0);
+    float4* mine = ring + threadIdx.x;
+    auto fetch = [&](int row) -> float4 {  // row index may run past P: the circle wraps
+        if (row >= P) row -= P;
+        return ldx<FULL>(G + (int64_t)row * ldg + c0, nin);
+    };
+    for (int k = 0; k < r - 1; ++k) mine[k * kBlock] = fetch(k);
+    float4 ahead[Q];  // rows n+r-1 .. n+r-1+Q-1 for the current n
+#pragma unroll
+    for (int q = 0; q < Q; ++q) ahead[q] = fetch(r - 1 + q);
+    int first = 0;      // ring slot of row n
+    int last = r - 1;   // ring slot that receives row n+r-1
+    for (int n0 = 0; n0 < P; n0 += Q) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int n = n0 + q;
+            if (n < P) {
+                mine[last * kBlock] = ahead[q];
+                if (n + Q < P) ahead[q] = fetch(n + Q + r - 1);
+                const double2* cn = coef + (int64_t)n * r;
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+                int slot = first;
+                for (int t = 0; t < r; ++t) {
+                    const float4 x = mine[slot * kBlock];
+                    cmac(cn[t].x, cn[t].y, (double)x.x, (double)x.y, are0, aim0);
+                    cmac(cn[t].x, cn[t].y, (double)x.z, (double)x.w, are1, aim1);
+                    if (++slot == r) slot = 0;
+                }
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if (Zlo != nullptr) {
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
+                if (++first == r) first = 0;
+                if (++last == r) last = 0;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void encode_cyc_ring_kernel(const float* __restrict__ G, int64_t ldg,
+                                                                 float* __restrict__ Z, float* __restrict__ Zlo,
+                                                                 int64_t ldm, const double2* __restrict__ coef,
+                                                                 int P, int r, int64_t d) {
+    extern __shared__ float4 ring[];  // [r][kBlock]
+    if (block_is_full(d)) encode_cyc_ring_body<true>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
+    else encode_cyc_ring_body<false>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
+}
+
 // One node on the unpacked wire (real gradients, d complex entries out), any window
 // width; the all-node path for r > 2*kMaxS+1.  Same operation order as the windowed kernel.
 __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const float* __restrict__ G, int64_t ldg,
@@ -90,10 +156,19 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
     case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
-        default:
-            for (int j = 0; j < P; ++j)
-                hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, 1, d);
+        default: {
+            const size_t ring_bytes = (size_t)r * kBlock * sizeof(float4);
+            if (ring_bytes <= lds_per_cu()) {
+                allow_large_lds<encode_cyc_ring_kernel>();
+                hipLaunchKernelGGL(encode_cyc_ring_kernel, grid, block, ring_bytes, stream, G, ldg, Z, Zlo, ldm, coef,
+                                   P, r, d);
+            } else {  // windows too wide for LDS: one launch per node
+                for (int j = 0; j < P; ++j)
+                    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
+                                       Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, 1,
+                                       d);
+            }
+        }
     }
 #undef DRACO_CASE
     return hipGetLastError();
