@@ -509,7 +509,7 @@ def test_cyc_determinism():
 
 
 # ------------------------------------------------------ one-node encoder ----
-@pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7)])
+@pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7), ("cyc", 20, 8, 2051), ("cyc", 45, 16, 1030)])
 def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
     w = wl(code, P, s, d)
     c = Case(w)
