@@ -63,35 +63,40 @@ def cpu_baseline(w):
     G = synth.make_gradients(ws.P, d_s, ws.sigma, ws.seed, device="cpu")[:, :d_s].numpy()
     f = synth.make_projection((d_s + 1) // 2, ws.seed).numpy()
     proc = psutil.Process()
-    c0, t0 = proc.cpu_times(), time.perf_counter()
-    if ws.code == "rep":
-        Z = o.encode_repetition(G, ws.s).astype(np.float32)
-    else:
-        Z = o.encode_cyclic(G, ws.s).astype(np.float32)
-    t_enc = time.perf_counter() - t0
-    R = torch.from_numpy(Z)
-    synth.apply_attacks(R, Z.shape[1], ws.adversaries(), ws.seed)
-    t1 = time.perf_counter()
-    t_dec = 0.0
-    if ws.decode:
+    c0 = proc.cpu_times()
+    t_enc = t_dec = 0.0
+    reps = 0
+    while reps < 20 and (reps == 0 or t_enc + t_dec < 10.0):      # about 10 s of oracle work
+        t0 = time.perf_counter()
         if ws.code == "rep":
-            _, mask, st = o.decode_repetition(R.numpy(), ws.s)
+            Z = o.encode_repetition(G, ws.s).astype(np.float32)
         else:
-            _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s)
-        t_dec = time.perf_counter() - t1
-        assert st == 0 and sorted(np.flatnonzero(mask)) == sorted(j for j, _ in ws.adversaries())
+            Z = o.encode_cyclic(G, ws.s).astype(np.float32)
+        t_enc += time.perf_counter() - t0
+        R = torch.from_numpy(Z)
+        synth.apply_attacks(R, Z.shape[1], ws.adversaries(), ws.seed)
+        if ws.decode:
+            t1 = time.perf_counter()
+            if ws.code == "rep":
+                _, mask, st = o.decode_repetition(R.numpy(), ws.s)
+            else:
+                _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s)
+            t_dec += time.perf_counter() - t1
+            assert st == 0 and sorted(np.flatnonzero(mask)) == sorted(j for j, _ in ws.adversaries())
+        reps += 1
     c1 = proc.cpu_times()
     wall = t_enc + t_dec
     busy = (c1.user + c1.system) - (c0.user + c0.system)
     return {
-        "value": ws.P * d_s * 4 / wall / 1e9,
+        "value": reps * ws.P * d_s * 4 / wall / 1e9,
         "unit": "GB/s",
         "cores": max(1, round(busy / max(wall, 1e-9))),
         "cores_available": len(os.sched_getaffinity(0)),
         "kind": "oracle",
-        "sample": f"same recipe at d={d_s} (of {w.d}), P={ws.P}, s={ws.s}; encode {t_enc:.2f} s + decode {t_dec:.2f} s",
-        "encode_s": t_enc,
-        "decode_s": t_dec,
+        "sample": f"same recipe at d={d_s} (of {w.d}), P={ws.P}, s={ws.s}, {reps} passes; "
+                  f"per pass encode {t_enc / reps:.2f} s + decode {t_dec / reps:.2f} s",
+        "encode_s": t_enc / reps,
+        "decode_s": t_dec / reps,
     }
 
 
