@@ -27,7 +27,8 @@
  *     concurrently; calls on ONE plan must not overlap (a plan owns scratch
  *     memory that its decode calls reuse).
  *   - The device that is current when a plan first touches the GPU
- *     (draco_plan_prepare or the first encode/decode) owns the plan.
+ *     (draco_plan_prepare or the first encode/decode) owns the plan; calling
+ *     it with another device current returns DRACO_EINVAL.
  */
 #ifndef DRACO_H
 #define DRACO_H

@@ -364,3 +364,66 @@ def draco_decode_repetition(plan: Plan, messages, out_sum, stream=None):
 
 def draco_decode_cyclic(plan: Plan, messages, f, out_sum, stream=None):
     return plan.decode_cyclic(messages, f, out_sum, stream)
+
+
+# ---------------------------------------------------------------------------
+# One-shot forms with the argument lists the method's description uses --
+# encode(assign, grads) -> messages; decode(messages, P, s) -> (sum, mask) --
+# on torch tensors.  They keep one plan per (code, P, s, d, device) and
+# allocate the outputs; every step of the work is the library's.
+# ---------------------------------------------------------------------------
+_PLANS: dict = {}
+
+
+def cached_plan(code: int, P: int, s: int, d: int, device) -> Plan:
+    import torch
+    dev = torch.device(device)
+    key = (code, P, s, d, dev.index if dev.index is not None else torch.cuda.current_device())
+    plan = _PLANS.get(key)
+    if plan is None:
+        with torch.cuda.device(key[4]):
+            plan = Plan(code, P, s, d)
+            plan.prepare()
+        _PLANS[key] = plan
+    return plan
+
+
+def _row_stride(n: int) -> int:
+    return (n + 3) // 4 * 4
+
+
+def encode(code: int, s: int, grads):
+    """grads [P][>= d] fp32 on the GPU (d = grads.shape[1]) -> messages [P][message_len]."""
+    import torch
+    P, d = grads.shape
+    plan = cached_plan(code, P, s, d, grads.device)
+    with torch.cuda.device(grads.device):
+        out = torch.empty((P, _row_stride(plan.message_len)), dtype=torch.float32, device=grads.device)
+        plan.encode(grads, out)
+    return out[:, :plan.message_len]
+
+
+def decode_repetition(messages, P: int, s: int):
+    """messages [P][d] -> (sum [d], mask bool[P], status)."""
+    import torch
+    assert messages.shape[0] == P
+    d = messages.shape[1]
+    plan = cached_plan(CODE_REPETITION, P, s, d, messages.device)
+    with torch.cuda.device(messages.device):
+        out = torch.empty(_row_stride(d), dtype=torch.float32, device=messages.device)
+        mask, status = plan.decode_repetition(messages, out)
+    return out[:d], mask, status
+
+
+def decode_cyclic(messages, P: int, s: int, d: int, f=None, seed: int = 0):
+    """messages [P][2*ceil(d/2)] -> (sum [d], mask bool[P], status); the projection vector is
+    `f` if given, else generated inside the library from `seed`."""
+    import torch
+    assert messages.shape[0] == P
+    plan = cached_plan(CODE_CYCLIC, P, s, d, messages.device)
+    with torch.cuda.device(messages.device):
+        out = torch.empty(_row_stride(d), dtype=torch.float32, device=messages.device)
+        if f is None:
+            plan.set_projection_seed(seed)
+        mask, status = plan.decode_cyclic(messages, f, out)
+    return out[:d], mask, status

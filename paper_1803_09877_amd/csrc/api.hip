@@ -95,7 +95,11 @@ thread_local char g_hip_detail[256] = "";
     } while (0)
 
 int prepare(draco_plan* p) {
-    if (p->prepared) return DRACO_OK;
+    if (p->prepared) {  // a plan stays with the device that was current when it was prepared
+        int dev = -1;
+        HIP_TRY(hipGetDevice(&dev));
+        return dev == p->device ? DRACO_OK : DRACO_EINVAL;
+    }
     HIP_TRY(hipGetDevice(&p->device));
     const int P = p->P, r = 2 * p->s + 1;
     HIP_TRY(hipMalloc(&p->flags_dev, kMaskWords * sizeof(uint64_t)));

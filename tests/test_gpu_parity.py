@@ -586,6 +586,28 @@ def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d)
 
 
 # ------------------------------------------------------------ arguments -----
+def test_one_shot_forms():
+    """encode(code, s, grads) -> messages and decode(messages, P, s) -> (sum, mask) with cached plans."""
+    dev = torch.device("cuda:0")
+    for code, P, s, d in ((B.CODE_REPETITION, 15, 2, 4099), (B.CODE_CYCLIC, 15, 2, 4099), (B.CODE_CYCLIC, 15, 2, 4100)):
+        G = synth.make_gradients(P, d, 1.0, 4242, device=dev)
+        Gv = G[:, :d]
+        Z = B.encode(code, s, Gv)
+        R = Z.clone() if Z.is_contiguous() else Z.contiguous()
+        R = torch.nn.functional.pad(R, (0, (-R.shape[1]) % 4))          # rows 16-byte aligned
+        mlen = Z.shape[1]
+        R[3, :mlen] = -100.0 * R[3, :mlen]
+        ref = Gv.double().sum(0).cpu().numpy()
+        for _ in range(2):                                                 # second call reuses the plan
+            if code == B.CODE_REPETITION:
+                u, mask, status = B.decode_repetition(R[:, :mlen], P, s)
+            else:
+                u, mask, status = B.decode_cyclic(R[:, :mlen], P, s, d, seed=5)
+            assert status == B.OK and list(np.flatnonzero(mask)) == [3]
+            assert u.shape == (d,) and rel_l2(u.cpu().numpy(), ref) <= 1e-5
+    assert len(B._PLANS) >= 3
+
+
 def test_alignment_and_argument_errors():
     w = wl("rep", 6, 1, 100)
     c = Case(w)
