@@ -356,8 +356,12 @@ def test_cyc_unpacked_wire(P, s, d, attacks, sigma):
     """Sec. 3's cyclic code on the real gradients (messages of d complex entries): encoder
     against the oracle's Z = G W, decoder (device and host locator) against the oracle on
     the same received messages, and Definition 2 end to end."""
-    w = wl("cyc", P, s, d, attacks, "any", sigma)
-    print(f"case {w.name} unpacked attacks={attacks}", flush=True)
+    run_unpacked(wl("cyc", P, s, d, attacks, "any", sigma))
+
+
+def run_unpacked(w, e2e=None):
+    P, s, d, attacks = w.P, w.s, w.d, w.attacks
+    print(f"case {w.name} unpacked attacks={attacks} seed={w.seed}", flush=True)
     c = Case(w, unpacked=True)
     try:
         assert c.mlen == 2 * d and c.f.numel() == d
@@ -398,7 +402,7 @@ def test_cyc_unpacked_wire(P, s, d, attacks, sigma):
             u2, m2, s2, _ = o.decode_cyclic_unpacked(R_host, o.projection_vector(d, 99), s)
             assert rel_l2(c.u[:d].cpu().numpy(), u2) <= TOL_SUM["cyc"]
         ref = c.G[:, :d].double().sum(0).cpu().numpy()     # Definition 2 up to the fp32 wire
-        assert rel_l2(c.u[:d].cpu().numpy(), ref) <= (2e-3 if P >= 45 else 1e-4)
+        assert rel_l2(c.u[:d].cpu().numpy(), ref) <= (e2e if e2e is not None else (2e-3 if P >= 45 else 1e-4))
     finally:
         c.close()
 
@@ -457,7 +461,11 @@ def test_cyc_wide_wire(P, s, d, attacks, placement, sigma):
     """Two-word wire: hi + lo carries the fp64 message to 48 bits, so the decoded
     sum meets Definition 2 END TO END (against the true gradient sum) far inside
     the 1e-4 bar also at P = 45, where the one-word wire cannot."""
-    w = wl("cyc", P, s, d, attacks, placement, sigma)
+    run_wide(wl("cyc", P, s, d, attacks, placement, sigma))
+
+
+def run_wide(w):
+    P = w.P
     print(f"wide case {w.name} attacks={w.attacks} seed={w.seed}", flush=True)
     c = Case(w, wide=True)
     try:
@@ -548,6 +556,23 @@ def test_random_shapes_and_attacks():
         sigma = float(rng.choice([1.0, 1e-2]))
         w = wl(code, P, s, d, attacks, "any", sigma, seed=100 + case)
         run_and_check(w)
+
+
+def test_random_shapes_and_attacks_on_the_other_wires():
+    """The same kind of sweep for the cyclic code's wide and unpacked wires."""
+    rng = np.random.default_rng(1803098770)
+    kinds = ["noise", "signflip", "offset"]
+    for case in range(24):
+        s = int(rng.integers(0, 7))
+        P = int(rng.integers(2 * s + 1, 48))
+        d = int(rng.integers(1, 20_000))
+        a = int(rng.integers(0, s + 1))
+        attacks = tuple(rng.choice(kinds, a))
+        w = wl("cyc", P, s, d, attacks, "any", float(rng.choice([1.0, 1e-2])), seed=500 + case)
+        if case % 2 == 0:
+            run_wide(w)
+        else:
+            run_unpacked(w, e2e=1.0)          # the fp32-wire floor depends on (P, s); parity is the check here
 
 
 # ------------------------------------------------- B > P (per-sample rows) ----
