@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
 __global__ __launch_bounds__(kBlock) void copy_probe_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                             int rows, int64_t row_len, int64_t ld) {
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
-    if (c0 + 4 > row_len) return;
+    if (c0 + 4 > row_len || (int)blockIdx.y >= rows) return;
     const int64_t off = (int64_t)blockIdx.y * ld + c0;
     st4(dst + off, ld4(src + off));
 }

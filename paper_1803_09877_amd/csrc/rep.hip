@@ -73,6 +73,7 @@ __device__ __forceinline__ void encode_rep_generic_body(const float* __restrict_
     const int n = FULL ? 4 : clamp4(d - c0);
     {
         const int g = (int)blockIdx.y;   // one group per workgroup (grid.y = groups)
+        if (g >= groups) return;
         const float* src = G + (int64_t)g * rows * ldg + c0;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         int i0 = 0;
