@@ -13,7 +13,9 @@
  *     none of them after the call returns.
  *   - `ld*` is a row stride in floats.  Every slab base pointer must be
  *     16-byte aligned and every stride a multiple of 4 floats and at least
- *     the row length; otherwise DRACO_EALIGN is returned.
+ *     the row length; otherwise DRACO_EALIGN is returned.  For full speed
+ *     make strides multiples of 32 floats (rows 128-byte aligned): rows that
+ *     are only 16-byte aligned cost up to 11 % of the bandwidth.
  *   - `stream` is a hipStream_t (NULL = the null stream).  Kernels are
  *     enqueued on it.  Entry points that return data to the host
  *     (draco_decode_repetition, draco_decode_cyclic) wait for `stream`
