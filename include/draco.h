@@ -65,8 +65,8 @@ enum draco_status {
 };
 
 #define DRACO_MAX_NODES 256
-/* Largest gradient dimension: the kernels index rows with 64-bit offsets, the
- * limit is the launch size of the one-coordinate-per-lane kernels (2^32 lanes). */
+/* Largest gradient dimension accepted.  The kernels index rows with 64-bit
+ * offsets (tested beyond 2^31); the limit keeps every launch below 2^32 lanes. */
 #define DRACO_MAX_DIM 4294963200LL
 
 /* ---- plan ------------------------------------------------------------- */

@@ -259,38 +259,77 @@ __global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restr
     publish_flags(wflags, flags);
 }
 
-// Any r: one coordinate per lane, copies re-read from cache for the count.
-__global__ __launch_bounds__(kBlock) void decode_rep_generic_kernel(const float* __restrict__ Rm, int64_t ldm,
-                                                                    float* __restrict__ u, uint64_t* __restrict__ flags,
-                                                                    int groups, int r, int64_t d) {
-    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    WaveFlags wflags;
-    const bool active = c < d;
-    float acc = 0.f;
+// Any r: the copies of a group stream through Algorithm 2's two words of state per
+// coordinate (candidate, counter), eight rows in flight, so every message byte is read
+// once.  Only where some lane of the wavefront saw a copy differ from the first one is the
+// group read again, to flag the nodes that differ from the winner.
+template <bool FULL>
+__device__ __forceinline__ void decode_rep_stream_body(const float* __restrict__ Rm, int64_t ldm,
+                                                       float* __restrict__ u, WaveFlags& wflags, int groups,
+                                                       int r, int64_t d) {
+    constexpr int UN = 8;
+    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const bool active = FULL || c0 < d;
+    const int n = FULL ? 4 : (active ? clamp4(d - c0) : 0);
+    auto fetch = [&](const float* p) -> uint4 {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);   // lanes past the end vote on zeros
+        if (active) t = ldx<FULL>(p, n);
+        return make_uint4(__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w));
+    };
+    auto step = [](uint32_t v, uint32_t& ma, int& counter) {
+        if (counter == 0) {
+            ma = v;
+            counter = 1;
+        } else if (v == ma) {
+            ++counter;
+        } else {
+            --counter;
+        }
+    };
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int g = 0; g < groups; ++g) {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(Rm) + (int64_t)g * r * ldm + c;
-        uint32_t ma = 0;
-        int counter = 0;
-        if (active) {
-            for (int i = 0; i < r; ++i) {
-                const uint32_t v = src[(int64_t)i * ldm];
-                if (counter == 0) {
-                    ma = v;
-                    counter = 1;
-                } else if (v == ma) {
-                    ++counter;
-                } else {
-                    --counter;
+        const float* src = Rm + (int64_t)g * r * ldm + c0;
+        uint4 ma = make_uint4(0u, 0u, 0u, 0u), first = ma;
+        int cx = 0, cy = 0, cz = 0, cw = 0;
+        uint32_t differ = 0;
+        for (int i0 = 0; i0 < r; i0 += UN) {
+            uint4 x[UN];
+#pragma unroll
+            for (int i = 0; i < UN; ++i)
+                if (i0 + i < r) x[i] = fetch(src + (int64_t)(i0 + i) * ldm);
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                if (i0 + i < r) {
+                    if (i0 + i == 0) first = x[i];
+                    differ |= (x[i].x ^ first.x) | (x[i].y ^ first.y) | (x[i].z ^ first.z) | (x[i].w ^ first.w);
+                    step(x[i].x, ma.x, cx);
+                    step(x[i].y, ma.y, cy);
+                    step(x[i].z, ma.z, cz);
+                    step(x[i].w, ma.w, cw);
                 }
             }
         }
-        for (int i = 0; i < r; ++i) {
-            const bool bad = active && src[(int64_t)i * ldm] != ma;
-            if (__ballot(bad) != 0ull) wflags.set(g * r + i);
+        if (__ballot(differ != 0) != 0ull) {
+            for (int i = 0; i < r; ++i) {
+                const uint4 x = fetch(src + (int64_t)i * ldm);
+                const bool bad = (x.x != ma.x) | (x.y != ma.y) | (x.z != ma.z) | (x.w != ma.w);
+                if (__ballot(bad) != 0ull) wflags.set(g * r + i);
+            }
         }
-        acc += __uint_as_float(ma);
+        acc.x += __uint_as_float(ma.x);
+        acc.y += __uint_as_float(ma.y);
+        acc.z += __uint_as_float(ma.z);
+        acc.w += __uint_as_float(ma.w);
     }
-    if (active) u[c] = acc;
+    if (active) stx<FULL>(u + c0, acc, n);
+}
+
+__global__ __launch_bounds__(kBlock) void decode_rep_generic_kernel(const float* __restrict__ Rm, int64_t ldm,
+                                                                    float* __restrict__ u, uint64_t* __restrict__ flags,
+                                                                    int groups, int r, int64_t d) {
+    WaveFlags wflags;
+    if (block_is_full(d)) decode_rep_stream_body<true>(Rm, ldm, u, wflags, groups, r, d);
+    else decode_rep_stream_body<false>(Rm, ldm, u, wflags, groups, r, d);
     publish_flags(wflags, flags);
 }
 
@@ -346,9 +385,11 @@ hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm,
     }
     DRACO_REP_DISPATCH(DRACO_LAUNCH, 8, 2, 1, 1)
 #undef DRACO_LAUNCH
-    if (generic)
-        hipLaunchKernelGGL(encode_rep_generic_kernel, dim3(tiles, (unsigned)groups), block, 0, stream, G, ldg, Z, ldm,
-                           groups, r, r, d);
+    if (generic) {
+        allow_large_lds<encode_rep_generic_kernel>();
+        hipLaunchKernelGGL(encode_rep_generic_kernel, dim3(tiles, (unsigned)groups), block, throttle_lds(2, 0, 0),
+                           stream, G, ldg, Z, ldm, groups, r, r, d);
+    }
     return hipGetLastError();
 }
 
@@ -384,8 +425,10 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
     DRACO_REP_DISPATCH(DRACO_LAUNCH, 4, 1, 1, 2)
 #undef DRACO_LAUNCH
     if (generic) {
-        const dim3 g1((unsigned)((d + kBlock - 1) / kBlock));
-        hipLaunchKernelGGL(decode_rep_generic_kernel, g1, block, 0, stream, R, ldm, u, flags, groups, r, d);
+        allow_large_lds<decode_rep_generic_kernel>(kMaskWords * sizeof(unsigned long long));
+        hipLaunchKernelGGL(decode_rep_generic_kernel, grid, block,
+                           throttle_lds(2, kMaskWords * sizeof(unsigned long long), 0), stream, R, ldm, u, flags,
+                           groups, r, d);
     }
     return hipGetLastError();
 }
