@@ -145,6 +145,33 @@ def test_rep_more_than_s_liars_is_reported():
     run_and_check(wl("rep", 10, 2, 999), extra_edit=edit, expect_status=B.NO_MAJORITY)
 
 
+@pytest.mark.parametrize("code", ["rep", "cyc"])
+def test_a_failed_decode_leaves_no_state_behind(code):
+    """A decode that reports too many adversaries, then a good one on the same plan: the
+    second is as if the first had never run (flag words, speculation state, scratch)."""
+    P, s, d = (10, 2, 3001) if code == "rep" else (9, 2, 3001)
+    w = wl(code, P, s, d, ("signflip",))
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        good = c.R.clone()
+        for j in (0, 2, 4) if code == "rep" else (0, 3, 6):
+            c.R[j, :c.mlen] = float(j + 1) if code == "rep" else torch.randn(c.mlen, device=c.device) * 100
+        mask, status = c.decode()
+        assert status == (B.NO_MAJORITY if code == "rep" else B.LOCATE_FAILED)
+        c.R.copy_(good)
+        uo, mo, so = oracle_decode(c, good[:, :c.mlen].cpu().numpy())
+        for _ in range(2):
+            c.u.fill_(float("nan"))
+            mask, status = c.decode()
+            torch.cuda.synchronize()
+            assert status == B.OK == so and np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
+            assert rel_l2(c.u[:d].cpu().numpy(), uo) <= TOL_SUM[code]
+    finally:
+        c.close()
+
+
 def test_rep_async_form_and_determinism():
     w = wl("rep", 45, 2, 123_457, ("signflip", "signflip"), "distinct_groups")
     c = Case(w)
