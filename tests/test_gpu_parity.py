@@ -585,6 +585,43 @@ def test_random_shapes_and_attacks():
         run_and_check(w)
 
 
+def test_many_small_random_decodes():
+    """300 small seeded cases (P < 64, s <= 7, d < 600, 0..s adversaries adding noise of
+    0.03 to 1000 times the message scale): both decoder forms against the oracle on the same
+    fp32 messages -- status and mask exact, sum within tolerance."""
+    rng = np.random.default_rng(11)
+    dev = torch.device("cuda:0")
+    for case in range(300):
+        s = int(rng.integers(1, 8))
+        P = int(rng.integers(2 * s + 1, 64))
+        d = int(rng.integers(8, 600))
+        plan = B.Plan(B.CODE_CYCLIC, P, s, d)
+        try:
+            mlen = plan.message_len
+            ld = synth.padded_len(mlen)
+            G = rng.standard_normal((P, d)).astype(np.float32)
+            Z = np.zeros((P, ld), dtype=np.float32)
+            Z[:, :mlen] = o.encode_cyclic(G, s).astype(np.float32)
+            a = int(rng.integers(0, s + 1))
+            V = rng.choice(P, a, replace=False)
+            mag = 10.0 ** rng.uniform(-1.5, 3)
+            scale = np.median(np.abs(Z[:, :mlen]))
+            for j in V:
+                Z[j, :mlen] += (rng.standard_normal(mlen) * mag * scale).astype(np.float32)
+            f = (rng.standard_normal(mlen // 2) + 1).astype(np.float32)
+            uo, mo, so = o.decode_cyclic(Z[:, :mlen], f, s, d)
+            assert so == o.OK and sorted(np.flatnonzero(mo)) == sorted(V), (case, P, s, d, a, mag)
+            R = torch.from_numpy(Z).to(dev)
+            fd = torch.from_numpy(f).to(dev)
+            u = torch.zeros(synth.padded_len(d), device=dev)
+            for fn in (plan.decode_cyclic, plan.decode_cyclic_hostphi):
+                m, st = fn(R, fd, u)
+                assert st == B.OK and np.array_equal(m, mo), (case, P, s, d, a, mag)
+                assert rel_l2(u[:d].cpu().numpy(), uo) <= TOL_SUM["cyc"], (case, P, s, d, a, mag)
+        finally:
+            plan.close()
+
+
 def test_random_shapes_and_attacks_on_the_other_wires():
     """The same kind of sweep for the cyclic code's wide and unpacked wires."""
     rng = np.random.default_rng(1803098770)
