@@ -622,6 +622,54 @@ def test_many_small_random_decodes():
             plan.close()
 
 
+def test_many_small_random_votes():
+    """300 small seeded repetition cases: 0..s liars per group (sometimes more, then the status
+    must say so), edits from one flipped bit in one coordinate to whole-row noise, sometimes
+    colluding liars that send the same wrong vector."""
+    rng = np.random.default_rng(12)
+    dev = torch.device("cuda:0")
+    for case in range(300):
+        s = int(rng.integers(0, 9))
+        r = 2 * s + 1
+        P = r * int(rng.integers(1, max(2, 70 // r)))
+        d = int(rng.integers(1, 700))
+        plan = B.Plan(B.CODE_REPETITION, P, s, d)
+        try:
+            ld = synth.padded_len(d)
+            G = rng.standard_normal((P, d)).astype(np.float32)
+            Z = np.zeros((P, ld), dtype=np.float32)
+            Z[:, :d] = o.encode_repetition(G, s).astype(np.float32)
+            overload = s > 0 and rng.random() < 0.1
+            for g in range(P // r):
+                a = int(rng.integers(0, s + 1)) if not (overload and g == 0) else s + 1
+                liars = g * r + rng.choice(r, a, replace=False)
+                shared = rng.standard_normal(d).astype(np.float32)
+                collude = rng.random() < 0.3
+                for j in liars:
+                    kind = int(rng.integers(0, 3))
+                    if collude:
+                        Z[j, :d] = shared
+                    elif kind == 0:
+                        Z[j, :d].view(np.uint32)[int(rng.integers(d))] ^= np.uint32(1) << np.uint32(rng.integers(32))
+                    elif kind == 1:
+                        Z[j, :d] = rng.standard_normal(d).astype(np.float32) * 100
+                    else:
+                        Z[j, :d] *= np.float32(-100)
+                        Z[j, int(rng.integers(d))] += np.float32(1)     # also differs where the message is 0
+            uo, mo, so = o.decode_repetition(Z[:, :d], s)
+            R = torch.from_numpy(Z).to(dev)
+            u = torch.zeros(ld, device=dev)
+            m, st = plan.decode_repetition(R, u)
+            assert st == so, (case, P, s, d)
+            if so == o.OK:
+                assert np.array_equal(m, mo), (case, P, s, d)
+                got = u[:d].cpu().numpy()
+                ok = np.isfinite(uo)
+                assert rel_l2(got[ok], uo[ok]) <= TOL_SUM["rep"], (case, P, s, d)
+        finally:
+            plan.close()
+
+
 def test_random_shapes_and_attacks_on_the_other_wires():
     """The same kind of sweep for the cyclic code's wide and unpacked wires."""
     rng = np.random.default_rng(1803098770)
