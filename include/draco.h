@@ -242,7 +242,10 @@ int draco_decode_cyclic_hostphi(draco_plan* plan, const float* messages_dev, int
 
 /* D^Cyc on the wide wire of draco_encode_wide: the received message of node j
  * is messages_hi[j] + messages_lo[j] (added exactly in fp64).  Otherwise as
- * draco_decode_cyclic / draco_decode_cyclic_async. */
+ * draco_decode_cyclic / draco_decode_cyclic_async, except that the locator
+ * counts a syndrome as zero below DRACO_TAU_WIDE (instead of DRACO_TAU) times
+ * the median projection: the wide wire's clean syndromes sit near 1e-14, so
+ * much smaller lies can be told from rounding. */
 int draco_decode_cyclic_wide(draco_plan* plan, const float* messages_hi_dev,
                              const float* messages_lo_dev, int64_t ld_m, const float* f_dev,
                              float* sum_dev, uint64_t* mask_host, void* stream);
@@ -259,6 +262,12 @@ int draco_decode_cyclic_wide_async(draco_plan* plan, const float* messages_hi_de
  * DRACO_LOCATE_FAILED.  Host-only. */
 int draco_cyclic_locate(const draco_plan* plan, const double* gamma_host,
                         uint64_t* mask_host, double* t_host);
+/* Same with the relative zero threshold of the syndromes given (0 < tau < 1):
+ * DRACO_TAU is what the one-word decoders use, DRACO_TAU_WIDE the wide ones. */
+#define DRACO_TAU (32.0 / 16777216.0)        /* 32 ulps of an fp32 wire */
+#define DRACO_TAU_WIDE (1.0 / 68719476736.0) /* 2^-36 */
+int draco_cyclic_locate_tol(const draco_plan* plan, const double* gamma_host, double tau,
+                            uint64_t* mask_host, double* t_host);
 
 /* The minimum-norm b with C_L[:, U] b_U = e_last (proof of Lemma 1) for
  * U = nodes whose mask bit is clear; b_host[2j], b_host[2j+1] = re, im of b_j,

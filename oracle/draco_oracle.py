@@ -48,6 +48,9 @@ LOCATE_FAILED = 2    # cyclic: the locator's answer does not explain the syndrom
 # leaves clean syndromes near 1e-7 * rho; the smallest attack the benchmark
 # workloads make is near 1e-1 * rho.
 TAU_H = 32.0 * 2.0 ** -24   # syndromes with max|h_m| <= TAU_H * rho count as zero (32 fp32 ulps)
+# The same threshold for messages carried to 48 bits (two fp32 words): their clean syndromes
+# sit near 1e-14 * rho, the rounding of the fp64 projection itself.
+TAU_H_WIDE = 2.0 ** -36
 
 
 # --------------------------------------------------------------------------
@@ -486,7 +489,8 @@ def solve_b(P: int, s: int, U: list, mode: str = "min_norm") -> np.ndarray:
     return b
 
 
-def decode_cyclic_complex(Rc: np.ndarray, f: np.ndarray, s: int, b_mode: str = "min_norm"):
+def decode_cyclic_complex(Rc: np.ndarray, f: np.ndarray, s: int, b_mode: str = "min_norm",
+                          tau_h: float = TAU_H):
     """Algorithm 1 on packed messages: V = phi(R); U = complement; b from
     ``solve_b``; u_hat = R_{.,U} b.  Returns (u_hat complex [h], mask, status).
     status LOCATE_FAILED comes from phi (more than s nodes lied); u_hat is
@@ -495,7 +499,7 @@ def decode_cyclic_complex(Rc: np.ndarray, f: np.ndarray, s: int, b_mode: str = "
     P = Rc.shape[0]
     check_params("cyc", P, s)
     gamma = project(Rc, f)
-    mask, _, status = phi_from_projection(gamma, s)
+    mask, _, status = phi_from_projection(gamma, s, tau_h)
     U = [j for j in range(P) if not mask[j]]
     if len(U) < P - 2 * s:
         return np.full(Rc.shape[1], np.nan, dtype=np.complex128), mask, LOCATE_FAILED
@@ -506,9 +510,10 @@ def decode_cyclic_complex(Rc: np.ndarray, f: np.ndarray, s: int, b_mode: str = "
     return u_hat, mask, status
 
 
-def decode_cyclic(R: np.ndarray, f: np.ndarray, s: int, d: int, b_mode: str = "min_norm"):
+def decode_cyclic(R: np.ndarray, f: np.ndarray, s: int, d: int, b_mode: str = "min_norm",
+                  tau_h: float = TAU_H):
     """Wire messages [P][2h] (interleaved re/im) -> (u fp64 [d], mask, status)."""
-    u_hat, mask, status = decode_cyclic_complex(wire_to_complex(R), f, s, b_mode)
+    u_hat, mask, status = decode_cyclic_complex(wire_to_complex(R), f, s, b_mode, tau_h)
     return unpack_complex(u_hat, d, "interleaved"), mask, status
 
 

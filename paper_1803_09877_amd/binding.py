@@ -29,6 +29,7 @@ BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
 WIRE_PACKED, WIRE_UNPACKED = 0, 1
+TAU, TAU_WIDE = 32.0 / 16777216.0, 1.0 / 68719476736.0
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
 EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
 KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE = 0, 1, 2, 3
@@ -44,6 +45,7 @@ EXPORTS = [
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe", "draco_plan_set_speculation",
     "draco_plan_set_projection_seed", "draco_projection_vector", "draco_plan_set_wire",
+    "draco_cyclic_locate_tol",
 ]
 
 
@@ -139,6 +141,8 @@ def lib() -> ctypes.CDLL:
     L.draco_strerror.restype = ctypes.c_char_p
     L.draco_last_hip_error.argtypes = []
     L.draco_last_hip_error.restype = ctypes.c_char_p
+    L.draco_cyclic_locate_tol.argtypes = [vp, vp, ctypes.c_double, vp, vp]
+    L.draco_cyclic_locate_tol.restype = i32
     L.draco_plan_set_wire.argtypes = [vp, i32]
     L.draco_plan_set_wire.restype = i32
     L.draco_plan_set_projection_seed.argtypes = [vp, ctypes.c_uint64]
@@ -236,12 +240,16 @@ class Plan:
         _check(lib().draco_plan_weights(self._h, W.ctypes.data))
         return W[..., 0] + 1j * W[..., 1]
 
-    def cyclic_locate(self, gamma: np.ndarray):
-        """(mask bool[P], t complex[P], status) from the P projections."""
+    def cyclic_locate(self, gamma: np.ndarray, tau: float | None = None):
+        """(mask bool[P], t complex[P], status) from the P projections; tau: relative zero
+        threshold of the syndromes (default: the one-word wire's)."""
         g = np.ascontiguousarray(np.stack([gamma.real, gamma.imag], axis=-1), dtype=np.float64)
         words = np.zeros(mask_words(self.P), dtype=np.uint64)
         t = np.zeros((self.P, 2), dtype=np.float64)
-        status = lib().draco_cyclic_locate(self._h, g.ctypes.data, words.ctypes.data, t.ctypes.data)
+        if tau is None:
+            status = lib().draco_cyclic_locate(self._h, g.ctypes.data, words.ctypes.data, t.ctypes.data)
+        else:
+            status = lib().draco_cyclic_locate_tol(self._h, g.ctypes.data, tau, words.ctypes.data, t.ctypes.data)
         _check(status)
         return mask_to_bool(words, self.P), t[:, 0] + 1j * t[:, 1], status
 

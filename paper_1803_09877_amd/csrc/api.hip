@@ -401,7 +401,7 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
         HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev,
                                    sum_dev, unpacked(p), spec, P, paired_len(p), st));
     }
-    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
+    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
                               p->idx_dev + P, spec, st));
     {
         Timed timed(p, kRecombine, st);
@@ -430,7 +430,7 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     std::vector<std::complex<double>> gamma(P), t;
     for (int j = 0; j < P; ++j) gamma[j] = std::complex<double>(p->gamma_pin[2 * j], p->gamma_pin[2 * j + 1]);
     std::vector<uint8_t> mask;
-    const bool located = cyclic_locate(P, s, gamma.data(), mask, t);
+    const bool located = cyclic_locate(P, s, wide ? kTauHWide : kTauH, gamma.data(), mask, t);
     words_from_mask(mask, mask_host, P);
     std::vector<cplx_t> b;
     if (!cyclic_recombination_vector(P, s, mask, b)) return DRACO_LOCATE_FAILED;
@@ -504,13 +504,19 @@ int draco_decode_cyclic_wide_async(draco_plan* p, const float* messages_hi_dev, 
 }
 
 int draco_cyclic_locate(const draco_plan* p, const double* gamma_host, uint64_t* mask_host, double* t_host) {
+    return draco_cyclic_locate_tol(p, gamma_host, kTauH, mask_host, t_host);
+}
+
+int draco_cyclic_locate_tol(const draco_plan* p, const double* gamma_host, double tau, uint64_t* mask_host,
+                            double* t_host) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC || gamma_host == nullptr || mask_host == nullptr)
         return DRACO_EINVAL;
+    if (!(tau > 0.0 && tau < 1.0)) return DRACO_EINVAL;
     const int P = p->P;
     std::vector<std::complex<double>> gamma(P), t;
     for (int j = 0; j < P; ++j) gamma[j] = std::complex<double>(gamma_host[2 * j], gamma_host[2 * j + 1]);
     std::vector<uint8_t> mask;
-    const bool ok = cyclic_locate(P, p->s, gamma.data(), mask, t);
+    const bool ok = cyclic_locate(P, p->s, tau, gamma.data(), mask, t);
     words_from_mask(mask, mask_host, P);
     if (t_host != nullptr)
         for (int j = 0; j < P; ++j) {

@@ -177,7 +177,7 @@ cplx_t CyclicCode::W(int k, int j) const {
     return rot[k] * taps[t];
 }
 
-bool cyclic_locate(int P, int s, const std::complex<double>* gamma_in, std::vector<uint8_t>& mask,
+bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_in, std::vector<uint8_t>& mask,
                    std::vector<std::complex<double>>& t_out) {
     mask.assign(P, 0);
     t_out.assign(P, std::complex<double>(0, 0));
@@ -199,7 +199,7 @@ bool cyclic_locate(int P, int s, const std::complex<double>* gamma_in, std::vect
     for (int j = 0; j < P; ++j) mags[j] = std::abs(gamma[j]);
     std::sort(mags.begin(), mags.end());
     const real_t rho = (P % 2) ? (real_t)mags[P / 2] : ((real_t)mags[P / 2 - 1] + (real_t)mags[P / 2]) / 2;
-    const real_t zero = (real_t)kTauH * rho;
+    const real_t zero = (real_t)tau * rho;
     const real_t isq = 1 / std::sqrt((real_t)P);
 
     // [h_{P-2s}, ..., h_{P-1}] = (f R) C_R^dagger

@@ -30,13 +30,16 @@ struct CyclicCode {
 // Relative size below which a syndrome counts as zero (in units of the median
 // |projection|): 32 ulps of the fp32 wire.
 constexpr double kTauH = 32.0 / 16777216.0;
+// The same for the two-word wire, whose messages carry 48 bits: clean syndromes sit
+// near 1e-14 (the fp64 projection's own rounding); 2^-36 leaves three decimal orders.
+constexpr double kTauHWide = 1.0 / 68719476736.0;
 
-// phi steps 2-4 on the projections gamma (length P).  mask[j] = 1 for located
+// phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns
 // true on success, false when no set of at most s nodes accounts for the
 // syndromes (mask then holds the s largest |t_j|).  Nodes whose projection is
 // not finite are flagged outright and enter the algebra with projection 0.
-bool cyclic_locate(int P, int s, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
+bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
                    std::vector<std::complex<double>>& t);
 
 // Minimum-norm b with C_L[:, U] b_U = e_last, U = {j : mask[j] == 0}; needs

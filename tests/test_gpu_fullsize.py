@@ -131,6 +131,14 @@ def test_full_size_cyclic_wide_wire_end_to_end():
         err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
         print(f"   end-to-end rel-L2 vs true sum (wide wire): {err:.3e}", flush=True)
         assert err <= 1e-6
+        # the messages as sent: the projection's own rounding over 12.8 M terms must stay below
+        # the wide wire's (much tighter) zero threshold, or honest nodes would be flagged
+        for _ in range(2):                                        # second call: speculative single pass
+            mask, status = c.plan.decode_cyclic_wide(c.Z, c.Zlo, c.f, c.u)
+            torch.cuda.synchronize()
+            assert status == 0 and not mask.any()
+            err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
+            assert err <= 1e-6
     finally:
         c.close()
 

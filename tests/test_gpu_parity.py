@@ -511,7 +511,7 @@ def run_wide(w):
         mask, status = c.decode()
         torch.cuda.synchronize()
         Rw = c.R[:, :c.mlen].double().cpu().numpy() + c.Rlo[:, :c.mlen].double().cpu().numpy()
-        uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), w.s, w.d)
+        uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), w.s, w.d, tau_h=o.TAU_H_WIDE)
         assert status == so == 0
         assert np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
         ug = c.u[:w.d].cpu().numpy()
@@ -520,6 +520,40 @@ def run_wide(w):
         assert rel_l2(ug, ref) <= 1e-6                                   # fp32 output rounding is 6e-8
         if c.u.numel() > w.d:
             assert torch.isnan(c.u[w.d:]).all()
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("P,s,d,size", [(15, 2, 20_001, 1e-9), (45, 3, 30_000, 1e-8), (9, 4, 4099, 1e-8)])
+def test_cyc_wide_wire_tells_tiny_lies_from_rounding(P, s, d, size):
+    """On the two-word wire a lie of 1e-8 .. 1e-9 of the message size (far below an fp32
+    ulp: the adversary edits the second word) is located, with the wide wire's threshold on
+    both sides; the one-word threshold would wave it through."""
+    w = wl("cyc", P, s, d, (), "any", 1.0)
+    c = Case(w, wide=True)
+    try:
+        c.encode()
+        c.receive()
+        liars = [1, P - 1][:s]
+        scale = float(c.Z[:, :c.mlen].abs().median())
+        g = torch.Generator(device=c.device)
+        g.manual_seed(9)
+        for j in liars:
+            c.Rlo[j, :c.mlen] += torch.randn(c.mlen, generator=g, device=c.device) * (size * scale)
+        Rw = c.R[:, :c.mlen].double().cpu().numpy() + c.Rlo[:, :c.mlen].double().cpu().numpy()
+        f = c.f.cpu().numpy()
+        uo, mo, so = o.decode_cyclic(Rw, f, s, d, tau_h=o.TAU_H_WIDE)
+        assert so == o.OK and sorted(np.flatnonzero(mo)) == sorted(liars)
+        _, m_loose, _ = o.decode_cyclic(Rw, f, s, d)                      # the one-word threshold sees nothing
+        assert not m_loose.any()
+        for fn in (c.plan.decode_cyclic_wide,):
+            c.u.fill_(float("nan"))
+            mask, status = fn(c.R, c.Rlo, c.f, c.u)
+            torch.cuda.synchronize()
+            assert status == B.OK and np.array_equal(mask, mo)
+            assert rel_l2(c.u[:d].cpu().numpy(), uo) <= 1e-6
+        ref = c.G[:, :d].double().sum(0).cpu().numpy()
+        assert rel_l2(c.u[:d].cpu().numpy(), ref) <= 1e-6
     finally:
         c.close()
 

@@ -104,6 +104,31 @@ def test_locator_every_adversary_subset(P, s):
                 assert np.allclose(t, fN, atol=1e-8 * np.abs(fN).max())
 
 
+def test_locator_with_the_wide_wires_threshold():
+    P, s = 9, 3
+    plan = B.Plan(B.CODE_CYCLIC, P, s, 32)
+    rng = np.random.default_rng(21)
+    G = rng.standard_normal((P, 32)).astype(np.float32)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    f = (rng.standard_normal(16) + 1).astype(np.float32)
+    scale = np.median(np.abs(Zc))
+    for V in [(), (4,), (0, 8), (2, 3, 7)]:
+        Rc = Zc.copy()
+        for j in V:
+            Rc[j] += (rng.standard_normal(16) + 1j * rng.standard_normal(16)) * 1e-7 * scale
+        gamma = o.project(Rc, f)
+        mask, _, st = plan.cyclic_locate(gamma, tau=B.TAU_WIDE)
+        omask, _, ost = o.phi_from_projection(gamma, s, o.TAU_H_WIDE)
+        assert st == B.OK == ost and np.array_equal(mask, omask)
+        assert sorted(np.flatnonzero(mask)) == sorted(V)
+        loose, _, _ = plan.cyclic_locate(gamma)
+        assert not loose.any()
+    assert B.TAU == o.TAU_H and B.TAU_WIDE == o.TAU_H_WIDE
+    for bad in (0.0, 1.0, -1.0, float("nan")):
+        with pytest.raises(B.DracoError):
+            plan.cyclic_locate(np.ones(P, dtype=complex), tau=bad)
+
+
 def test_locator_reports_too_many_adversaries_and_nonfinite():
     P, s = 9, 2
     plan = B.Plan(B.CODE_CYCLIC, P, s, 40)

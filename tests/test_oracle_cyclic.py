@@ -465,3 +465,46 @@ def test_unpacked_messages_of_real_gradients_have_hermitian_structure_in_W_only(
     Zc = o.wire_to_complex(o.encode_cyclic_unpacked(G, s))
     assert np.allclose(Zc.real, W.real.T @ G, atol=1e-12 * np.abs(Zc).max())
     assert np.allclose(Zc.imag, W.imag.T @ G, atol=1e-12 * np.abs(Zc).max())
+
+
+# ------------------------------------------------ threshold of the wide wire --
+@pytest.mark.parametrize("P,s", [(5, 1), (7, 2), (9, 4)])
+def test_wide_threshold_every_adversary_subset_with_tiny_lies(P, s):
+    """Messages carried to 48 bits (hi + lo fp32 words): lies of 1e-7 of the message size,
+    every adversary set of size <= s.  With TAU_H_WIDE the set is located and the sum is
+    G 1_P; with the one-word TAU_H the lies pass as rounding."""
+    d = 16
+    G = _grads(P, d, 9 * P + s)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Z = o.encode_cyclic(G, s)
+    hi = Z.astype(np.float32)
+    lo = (Z - hi).astype(np.float32)
+    Zw = hi.astype(np.float64) + lo.astype(np.float64)
+    f = _f(d // 2, P + 1)
+    rng = np.random.default_rng(P + s)
+    scale = np.median(np.abs(Zw))
+    for a in range(0, s + 1):
+        for V in itertools.combinations(range(P), a):
+            R = Zw.copy()
+            for j in V:
+                R[j] += rng.standard_normal(d) * 1e-7 * scale
+            u, mask, st = o.decode_cyclic(R, f, s, d, tau_h=o.TAU_H_WIDE)
+            assert st == o.OK and sorted(np.flatnonzero(mask)) == sorted(V)
+            assert np.linalg.norm(u - ref) <= 1e-11 * np.linalg.norm(ref)
+            _, loose, st2 = o.decode_cyclic(R, f, s, d)
+            assert st2 == o.OK and not loose.any()
+
+
+def test_wide_threshold_sits_between_the_floors():
+    """Clean syndromes of a 48-bit wire are ~1e-14 of the median projection, those of an fp32
+    wire ~5e-8: TAU_H_WIDE lies three orders above the first and far below the second."""
+    P, s, d = 45, 3, 40_000
+    G = _grads(P, d, 4, 1e-2)
+    Z = o.encode_cyclic(G, s)
+    hi = Z.astype(np.float32)
+    wide = hi.astype(np.float64) + (Z - hi).astype(np.float32).astype(np.float64)
+    f = _f(d // 2, 8)
+    for R, lo_b, hi_b in ((wide, 0.0, 1e-3 * o.TAU_H_WIDE), (hi.astype(np.float64), 1e3 * o.TAU_H_WIDE, o.TAU_H / 8)):
+        gamma = o.project(o.wire_to_complex(R), f)
+        floor = np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma))
+        assert lo_b <= floor <= hi_b, floor
