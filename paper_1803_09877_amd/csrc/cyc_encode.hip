@@ -52,13 +52,13 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 // only what it wrote: no barrier), rows are fetched Q ahead into registers, and the last
 // 2s nodes re-read rows 0..2s-1 from memory (2s/P more reads than the register kernels).
 // Same operation order as the one-node kernel: results are bit-identical to it.
-template <bool FULL>
+template <int TB, bool FULL>
 __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G, int64_t ldg,
                                                      float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
                                                      const double2* __restrict__ coef, int P, int r, int64_t d,
-                                                     float4* ring /* LDS [r][kBlock] */) {
+                                                     float4* ring /* LDS [r][TB] */) {
     constexpr int Q = 4;
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = ((int64_t)blockIdx.x * TB + threadIdx.x) * 4;
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (!FULL && c0 >= mlen) return;
     const int nin = FULL ? 4 : clamp4(d - c0);
@@ -68,7 +68,7 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
         if (row >= P) row -= P;
         return ldx<FULL>(G + (int64_t)row * ldg + c0, nin);
     };
-    for (int k = 0; k < r - 1; ++k) mine[k * kBlock] = fetch(k);
+    for (int k = 0; k < r - 1; ++k) mine[k * TB] = fetch(k);
     float4 ahead[Q];  // rows n+r-1 .. n+r-1+Q-1 for the current n
 #pragma unroll
     for (int q = 0; q < Q; ++q) ahead[q] = fetch(r - 1 + q);
@@ -79,13 +79,13 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
         for (int q = 0; q < Q; ++q) {
             const int n = n0 + q;
             if (n < P) {
-                mine[last * kBlock] = ahead[q];
+                mine[last * TB] = ahead[q];
                 if (n + Q < P) ahead[q] = fetch(n + Q + r - 1);
                 const double2* cn = coef + (int64_t)n * r;
                 double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
                 int slot = first;
                 for (int t = 0; t < r; ++t) {
-                    const float4 x = mine[slot * kBlock];
+                    const float4 x = mine[slot * TB];
                     cmac(cn[t].x, cn[t].y, (double)x.x, (double)x.y, are0, aim0);
                     cmac(cn[t].x, cn[t].y, (double)x.z, (double)x.w, are1, aim1);
                     if (++slot == r) slot = 0;
@@ -104,13 +104,14 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
     }
 }
 
-__global__ __launch_bounds__(kBlock) void encode_cyc_ring_kernel(const float* __restrict__ G, int64_t ldg,
+template <int TB>
+__global__ __launch_bounds__(TB) void encode_cyc_ring_kernel(const float* __restrict__ G, int64_t ldg,
                                                                  float* __restrict__ Z, float* __restrict__ Zlo,
                                                                  int64_t ldm, const double2* __restrict__ coef,
                                                                  int P, int r, int64_t d) {
-    extern __shared__ float4 ring[];  // [r][kBlock]
-    if (block_is_full(d)) encode_cyc_ring_body<true>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
-    else encode_cyc_ring_body<false>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
+    extern __shared__ float4 ring[];  // [r][TB]
+    if ((int64_t)(blockIdx.x + 1) * (TB * 4) <= d) encode_cyc_ring_body<TB, true>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
+    else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
 }
 
 // One node on the unpacked wire (real gradients, d complex entries out), any window
@@ -157,11 +158,15 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         default: {
-            const size_t ring_bytes = (size_t)r * kBlock * sizeof(float4);
+            // one wavefront per workgroup: the ring is r KiB, so a CU holds 160/r of them and
+            // has that many wavefronts to hide the LDS and scalar-load latency of the tap loop
+            constexpr int TB = 64;
+            const size_t ring_bytes = (size_t)r * TB * sizeof(float4);
             if (ring_bytes <= lds_per_cu()) {
-                allow_large_lds<encode_cyc_ring_kernel>();
-                hipLaunchKernelGGL(encode_cyc_ring_kernel, grid, block, ring_bytes, stream, G, ldg, Z, Zlo, ldm, coef,
-                                   P, r, d);
+                allow_large_lds<encode_cyc_ring_kernel<TB>>();
+                const dim3 g64((unsigned)(((mlen + 3) / 4 + TB - 1) / TB));
+                hipLaunchKernelGGL(encode_cyc_ring_kernel<TB>, g64, dim3(TB), ring_bytes, stream, G, ldg, Z, Zlo, ldm,
+                                   coef, P, r, d);
             } else {  // windows too wide for LDS: one launch per node
                 for (int j = 0; j < P; ++j)
                     hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
