@@ -19,7 +19,7 @@ _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libdraco.so")
 SOURCES = [os.path.join(_HERE, "csrc", n) for n in (
     # slowest first: the per-s encoder units dominate the build time
-    "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
+    "cyc_encode_s10.hip", "cyc_encode_s9.hip", "cyc_encode_s8.hip", "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
     "cyc_encode_s2.hip", "cyc_encode_s1.hip", "cyc_encode_s0.hip", "rep.hip", "cyc_encode.hip", "cyc_decode.hip",
     "locate.hip", "api.hip", "host_math.cpp")]
 HEADERS = [os.path.join(_HERE, "csrc", n) for n in (

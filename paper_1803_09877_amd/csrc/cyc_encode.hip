@@ -7,7 +7,7 @@ namespace draco {
 // One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
 // wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
 // with wrap_rows == P it is the full [P][ldg] slab and row (node+t) mod P is
-// used (the all-node path for r > 2*kMaxS+1).  Same operation order as the
+// used (the all-node path for r > 2*kMaxCycS+1).  Same operation order as the
 // all-node kernel, so results are bit-identical.
 __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
                                                                  float* __restrict__ z, float* __restrict__ zlo,
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(TB) void encode_cyc_ring_kernel(const float* __rest
 }
 
 // One node on the unpacked wire (real gradients, d complex entries out), any window
-// width; the all-node path for r > 2*kMaxS+1.  Same operation order as the windowed kernel.
+// width; the all-node path for r > 2*kMaxCycS+1.  Same operation order as the windowed kernel.
 __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const float* __restrict__ G, int64_t ldg,
                                                                       float* __restrict__ z,
                                                                       const double2* __restrict__ cn, int node,
@@ -157,6 +157,7 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
     case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default: {
             // one wavefront per workgroup: the ring is r KiB, so a CU holds 160/r of them and
             // has that many wavefronts to hide the LDS and scalar-load latency of the tap loop
@@ -188,6 +189,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     case S: return launch_encode_cyc_real_s<S>(one_per_cu, grid, stream, G, ldg, Z, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_real_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
@@ -206,6 +208,7 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
     case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
+        DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,

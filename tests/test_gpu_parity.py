@@ -210,7 +210,11 @@ def test_rep_async_form_and_determinism():
     (45, 3, 70_002, ("signflip",), "any", 1e-2, 2e-3),
     (45, 1, 9_999, ("noise",), "any", 1e-2, 1e-4),
     (15, 7, 6_001, ("noise", "signflip", "offset", "constant", "noise", "signflip", "offset"), "any", 1.0, 1e-5),
-    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0, 1e-4),   # r = 17: generic encoder path
+    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0, 1e-4),   # r = 17
+    (23, 9, 2_051, ("noise", "signflip"), "any", 1.0, 1e-4),             # r = 19
+    (24, 10, 1_031, ("noise",) * 10, "any", 1.0, 1e-4),                  # r = 21: widest register window
+    (30, 11, 1_030, ("signflip", "noise"), "any", 1.0, 1e-3),            # r = 23: the LDS-ring encoder
+    (40, 16, 515, ("noise",) * 5, "any", 1.0, None),                     # r = 33: largest s of the device locator
     (70, 2, 2_001, ("noise", "signflip"), "any", 1.0, None),       # second mask word
     (256, 1, 301, ("noise",), "any", 1.0, 1e-3),                   # the largest P the library takes
     (128, 2, 999, ("signflip", "noise"), "any", 1.0, None),        # wide dynamic range of W
@@ -376,7 +380,9 @@ def test_cyc_generated_projection_vector(P, s, d, attacks, sigma, seed):
     (45, 3, 30_001, ("noise", "signflip", "noise"), 1e-2),
     (9, 4, 2050, ("noise",) * 4, 1.0),
     (15, 7, 1030, ("signflip",) * 7, 1.0),
-    (17, 8, 515, ("noise",) * 8, 1.0),                # window wider than the register kernels: per-node path
+    (17, 8, 515, ("noise",) * 8, 1.0),
+    (21, 10, 2_050, ("noise", "signflip"), 1.0),       # widest register window
+    (25, 11, 515, ("noise",) * 3, 1.0),                # window wider than the register kernels: per-node path
     (66, 1, 777, ("noise",), 1.0),
 ])
 def test_cyc_unpacked_wire(P, s, d, attacks, sigma):
@@ -481,7 +487,10 @@ def test_cyc_large_s_takes_the_host_form():
     (45, 3, 70_001, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2),
     (45, 3, 70_002, (), "any", 1e-2),
     (45, 5, 30_000, ("noise", "signflip", "offset", "constant", "noise"), "any", 1e-2),
-    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0),          # generic encoder path
+    (20, 8, 3_001, ("noise", "signflip", "offset"), "any", 1.0),
+    (30, 9, 2_051, ("noise", "signflip"), "any", 1.0),
+    (24, 10, 1_031, ("noise", "offset"), "any", 1.0),
+    (30, 12, 1_030, ("noise",), "any", 1.0),                              # LDS-ring encoder
     (40, 17, 1_001, ("noise", "signflip"), "any", 1.0),                  # host phi fallback
 ])
 def test_cyc_wide_wire(P, s, d, attacks, placement, sigma):
@@ -578,7 +587,7 @@ def test_cyc_determinism():
 
 
 # ------------------------------------------------------ one-node encoder ----
-@pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7), ("cyc", 20, 8, 2051), ("cyc", 45, 16, 1030)])
+@pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7), ("cyc", 20, 8, 2051), ("cyc", 21, 10, 1030), ("cyc", 45, 16, 1030)])
 def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
     w = wl(code, P, s, d)
     c = Case(w)
@@ -725,7 +734,7 @@ def test_random_shapes_and_attacks_on_the_other_wires():
 @pytest.mark.parametrize("code,P,s,m,d", [
     ("rep", 15, 2, 4, 3001), ("rep", 45, 2, 4, 20_003), ("rep", 9, 1, 16, 999), ("rep", 34, 8, 3, 777),
     ("cyc", 15, 2, 4, 3001), ("cyc", 45, 3, 4, 20_002), ("cyc", 45, 3, 16, 5_001), ("cyc", 15, 7, 2, 2_050),
-    ("cyc", 20, 8, 3, 1_001), ("cyc", 6, 0, 5, 4_099), ("cyc", 45, 5, 4, 8_000),
+    ("cyc", 20, 8, 3, 1_001), ("cyc", 6, 0, 5, 4_099), ("cyc", 45, 5, 4, 8_000), ("cyc", 21, 10, 2, 1_030), ("cyc", 25, 12, 2, 515),
 ])
 def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d):
     """B = m*P per-sample gradients (the paper runs B = 180 and 720 on P = 45): unit gradient k
