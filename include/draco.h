@@ -89,9 +89,9 @@ int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d);
  * which Sec. 3 states the code and proves Theorem 5, at twice the bytes.  The
  * decoder is the same (projection on f with one entry per complex coordinate,
  * i.e. d entries; locate; recombine) and writes the real part of R_{.,U} b to
- * sum_dev[d].  In this mode draco_encode and every draco_decode_cyclic* form
- * work as documented below with draco_message_len() = 2d; the wide wire,
- * draco_encode_node and draco_encode_samples with B > P return DRACO_EINVAL. */
+ * sum_dev[d].  In this mode draco_encode, every draco_decode_cyclic* form and
+ * draco_encode_node work as documented below with draco_message_len() = 2d;
+ * the wide wire and draco_encode_samples with B > P return DRACO_EINVAL. */
 int draco_plan_set_wire(draco_plan* plan, int wire);
 
 /* Allocate the plan's device-side tables and scratch on the current device

@@ -317,7 +317,7 @@ int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int
 
 int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
                       void* stream) {
-    if (p == nullptr || node < 0 || node >= p->P || unpacked(p)) return DRACO_EINVAL;
+    if (p == nullptr || node < 0 || node >= p->P) return DRACO_EINVAL;
     int rc = check_slab(node_grads_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
     if (message_dev == nullptr) return DRACO_EINVAL;
@@ -328,6 +328,8 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     Timed timed(p, kEncode, st);
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_node(node_grads_dev, ld_g, message_dev, p->s, p->d, st));
+    else if (unpacked(p))
+        HIP_TRY(launch_encode_cyc_real_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
     else
         HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, p->coef_dev, node, p->P, p->s, p->d,
                                        st));

@@ -114,12 +114,13 @@ __global__ __launch_bounds__(TB) void encode_cyc_ring_kernel(const float* __rest
     else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
 }
 
-// One node on the unpacked wire (real gradients, d complex entries out), any window
-// width; the all-node path for r > 2*kMaxCycS+1.  Same operation order as the windowed kernel.
+// One node on the unpacked wire (real gradients, d complex entries out), any window width:
+// with wrap_rows == 0 Gn holds only the node's r gradients in assignment order, with
+// wrap_rows == P it is the full slab (the all-node path for r > 2*kMaxCycS+1).  Same operation order as the windowed kernel.
 __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const float* __restrict__ G, int64_t ldg,
                                                                       float* __restrict__ z,
                                                                       const double2* __restrict__ cn, int node,
-                                                                      int P, int r, int64_t d) {
+                                                                      int P, int r, int wrap_rows, int64_t d) {
     const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
     if (c0 >= d) return;
     const int nin = clamp4(d - c0);
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const floa
     for (int t = 0; t < r; ++t) {
         int k = node + t;
         if (k >= P) k -= P;
-        const float* p = G + (int64_t)k * ldg + c0;
+        const float* p = G + (int64_t)(wrap_rows ? k : t) * ldg + c0;
         const float4 raw = (nin == 4) ? ld4(p) : ld4_partial(p, nin);
         const double g[4] = {(double)raw.x, (double)raw.y, (double)raw.z, (double)raw.w};
 #pragma unroll
@@ -193,7 +194,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_real_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   coef + (int64_t)j * r, j, P, r, d);
+                                   coef + (int64_t)j * r, j, P, r, P, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();
@@ -215,6 +216,15 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
                                    (float*)nullptr, coef + (int64_t)j * r, j, P, r, P, m, d);
     }
 #undef DRACO_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node, int P,
+                                       int s, int64_t d, hipStream_t stream) {
+    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const int r = 2 * s + 1;
+    hipLaunchKernelGGL(encode_cyc_real_node_kernel, grid, block, 0, stream, Gn, ldg, z, coef + (int64_t)node * r, node,
+                       P, r, 0, d);
     return hipGetLastError();
 }
 

@@ -46,6 +46,8 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
 hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
                                   int P, int s, int64_t d, hipStream_t stream);
 // Gn holds only the node's 2s+1 gradients, in assignment order.
+hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node,
+                                       int P, int s, int64_t d, hipStream_t stream);
 hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef,
                                   int node, int P, int s, int64_t d, hipStream_t stream);
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.

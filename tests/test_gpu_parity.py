@@ -440,6 +440,24 @@ def run_unpacked(w, e2e=None):
         c.close()
 
 
+@pytest.mark.parametrize("P,s,d", [(15, 2, 3001), (45, 3, 2048), (21, 10, 1030), (25, 11, 515)])
+def test_cyc_unpacked_encode_node_is_bit_identical_to_the_all_node_form(P, s, d):
+    w = wl("cyc", P, s, d)
+    c = Case(w, unpacked=True)
+    try:
+        c.encode()
+        r = w.r
+        for node in range(P):
+            Gn = c.G[[(node + t) % P for t in range(r)]].contiguous()
+            z = torch.full((c.ld_m,), float("nan"), dtype=torch.float32, device=c.device)
+            c.plan.encode_node(node, Gn, z)
+            torch.cuda.synchronize()
+            assert torch.equal(z[:c.mlen].view(torch.int32), c.Z[node, :c.mlen].view(torch.int32)), node
+            assert torch.isnan(z[c.mlen:]).all()
+    finally:
+        c.close()
+
+
 def test_cyc_unpacked_wire_rejects_what_it_does_not_support():
     w = wl("cyc", 9, 2, 100)
     c = Case(w, unpacked=True)
@@ -450,9 +468,6 @@ def test_cyc_unpacked_wire_rejects_what_it_does_not_support():
         assert e.value.status == B.EINVAL
         with pytest.raises(B.DracoError) as e:
             c.plan.decode_cyclic_wide(c.Z, lo, c.f, c.u)
-        assert e.value.status == B.EINVAL
-        with pytest.raises(B.DracoError) as e:
-            c.plan.encode_node(0, c.G[:5], c.Z[0])
         assert e.value.status == B.EINVAL
         with pytest.raises(B.DracoError) as e:                  # the wire is fixed once the plan is prepared
             c.plan.set_wire(B.WIRE_PACKED)
