@@ -211,8 +211,10 @@ int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_
  * seed + (i+1)*0x9E3779B97F4A7C15 gives two 24-bit uniforms u1 (top bits) and
  * u2 (bits 16..39), and f_i = fp32(1 + sqrt(-2 ln u1) cos(2 pi u2)).  A fresh
  * seed per decode keeps an adversary from preparing a message orthogonal to f.
- * draco_projection_vector writes the ceil(d/2) entries for a seed to host
- * memory (inspection, tests). */
+ * The seed travels as a kernel argument: a captured HIP graph replays the seed
+ * it was captured with (pass f_dev, refreshed by the caller, to vary f there).
+ * draco_projection_vector writes the entries for a seed (draco_message_len()/2
+ * of them) to host memory (inspection, tests). */
 int draco_plan_set_projection_seed(draco_plan* plan, uint64_t seed);
 int draco_projection_vector(const draco_plan* plan, uint64_t seed, float* f_host);
 
