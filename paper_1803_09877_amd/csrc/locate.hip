@@ -196,7 +196,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                         // to make them orthogonal to each other
                         const bool skip = ag == 0.0 || ag <= 1e-10 * sqrt(alpha * bet) ||
                                           (alpha <= zero * zero && bet <= zero * zero);
-                        if (__shfl(skip ? 1 : 0, 0) != 0) continue;   // lane 0's verdict, uniform
+                        if (__shfl(skip ? 1 : 0, 0) != 0) continue;   // lane 0's decision, uniform
                         rotated = true;
                         if (lane >= s) {   // nothing to rotate; keep the barrier count equal
                             __syncthreads();
