@@ -384,7 +384,7 @@ hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm,
         hipLaunchKernelGGL((encode_rep_kernel<R, GU>), dim3(tiles, (unsigned)((groups + GU - 1) / GU)),      \
                            block, throttle_lds(BPC, 0, 0), stream, G, ldg, Z, ldm, groups, d);               \
     }
-    DRACO_REP_DISPATCH(DRACO_LAUNCH, 8, 2, 1, 1, 1)
+    DRACO_REP_DISPATCH(DRACO_LAUNCH, 8, 2, 1, 1, 2)
 #undef DRACO_LAUNCH
     if (generic) {
         allow_large_lds<encode_rep_generic_kernel>();
