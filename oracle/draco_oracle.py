@@ -28,7 +28,8 @@ at the function that uses it):
 Pinned by tests/test_oracle_*.py against: Definition 2 by exhaustive
 enumeration of adversary subsets, the 4-point example of Fig. 1 (caption),
 Lemma 1, Lemma 4 (Orthogonal), the identity t = f N from the proof of Lemma 2,
-a brute-force locator, Lagrange closed forms and the plain sum.  The numeric
+a brute-force locator, Lagrange closed forms, a projection worked by hand and the
+plain sum.  The numeric
 coefficients drawn in Fig. 1 itself are not in the text: parity unpinned for
 that picture only.
 """

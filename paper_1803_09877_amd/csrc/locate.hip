@@ -11,11 +11,6 @@
 // products are wavefront reductions.  Limits: P <= 256, s <= kLocateMaxS.
 #include "kernels.hpp"
 
-// Phase marker for profiling builds (defined by a harness that includes this file); no-op otherwise.
-#ifndef DRACO_STAMP
-#define DRACO_STAMP(i)
-#endif
-
 namespace draco {
 
 namespace {
@@ -124,7 +119,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         sm.mask[j] = ok ? 0 : 1;
     }
     if (lane == 0) sm.nv = 0;
-    DRACO_STAMP(0);
     __syncthreads();
     const int broken = (int)wave_sum<kW>((double)my_broken);
 
@@ -140,7 +134,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
         const double rho = 0.5 * (sm.lo + sm.hi);
-        DRACO_STAMP(1);
         const double zero = tau * rho;
 
         // syndromes h_m = (1/sqrt P) sum_j gamma_j w^{-m j}, m = n .. P-1
@@ -163,7 +156,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
         const double hmax = wave_max(mymax);
-        DRACO_STAMP(2);
 
         if (hmax > zero) {
             // ---- beta: least squares on the s x s system, singular values <= zero dropped
@@ -198,10 +190,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                                           (alpha <= zero * zero && bet <= zero * zero);
                         if (__shfl(skip ? 1 : 0, 0) != 0) continue;   // lane 0's decision, uniform
                         rotated = true;
-                        if (lane >= s) {   // nothing to rotate; keep the barrier count equal
-                            __syncthreads();
-                            continue;
-                        }
                         const double2 ph = make_double2(g.x / ag, -g.y / ag);
                         const double zeta = (bet - alpha) / (2.0 * ag);
                         const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
@@ -236,7 +224,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             }
             if (lane < s) sm.beta[lane] = bk;
             __syncthreads();
-            DRACO_STAMP(3);
 
             // ---- recurrence h_l = sum_u beta_u h_{l+u-s}, l = 0 .. n-1: inherently serial, so one
             // lane runs it out of LDS (a wavefront's LDS accesses complete in order)
@@ -252,7 +239,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 }
             }
             __syncthreads();
-            DRACO_STAMP(4);
             // ---- t = C h, ranking by |t_j| (descending, ties to the lower index)
             for (int j = lane; j < P; j += kW) {
                 double2 acc = make_double2(0.0, 0.0);
@@ -272,7 +258,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 if (rank < s) sm.order[rank] = j;
             }
             __syncthreads();
-            DRACO_STAMP(5);
             // ---- shortest leading part of the ranking whose errors account for the syndromes
             int found = 0;
             for (int a = 1; a <= s; ++a) {
@@ -307,13 +292,14 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             if ((int)wave_sum<kW>((double)mine) > s) status = 2;
         }
     }
-
-    DRACO_STAMP(6);
     // ---- b: minimum-norm solution of C_L[:, U] b_U = e_last (see host_math.cpp)
     if (lane == 0) {
         int a = 0;
         for (int j = 0; j < P; ++j)
-            if (sm.mask[j]) sm.vlist[a++] = j;
+            if (sm.mask[j]) {  // a failed decode can flag any number of nodes; the list keeps the first 2s
+                if (a < 2 * kLocateMaxS) sm.vlist[a] = j;
+                ++a;
+            }
         sm.nv = a;
     }
     __syncthreads();
@@ -347,7 +333,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         }
         __syncthreads();
     }
-    DRACO_STAMP(7);
     for (int j = lane; j < P; j += kW) {
         double2 acc = make_double2(0.0, 0.0);
         if (!sm.mask[j]) {
@@ -374,7 +359,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 ++nu;
             }
         }
-        DRACO_STAMP(8);
         *nu_out = nu;
         if (spec_state != nullptr) spec_state[0] = (nu == P && status == 0) ? 1 : 0;
         for (int w = 0; w < (P + 63) / 64; ++w) mask_out[w] = words[w];

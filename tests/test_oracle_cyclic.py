@@ -377,6 +377,40 @@ def test_planted_mistakes_are_caught():
     assert np.abs(W @ b0 - 1).max() > 1e-3
 
 
+# ------------------------------------------------ phi step 1: the projection f R
+def test_project_against_hand_values_and_a_double_loop():
+    """phi's first step, gamma'_j = sum_i f_i r_j[i] with f REAL and the message row complex
+    (Sec. 3, phi: "f R").  A 3 x 4 case worked by hand, then a random case against an
+    explicit double loop.  The mistakes this rules out: conjugating the messages, summing
+    over nodes instead of coordinates (f R vs R f^T with the wrong axis), dropping the
+    imaginary part, weighting by |f| or f^2."""
+    Rc = np.array([[1 + 2j, 0 - 1j, 3 + 0j, -2 + 2j],
+                   [0 + 0j, 1 + 1j, -1 - 1j, 4 - 3j],
+                   [2 - 1j, 2 + 1j, 0 + 5j, 1 + 0j]])
+    f = np.array([1.0, -2.0, 0.5, 3.0])
+    # row 0: (1+2j) - 2(0-1j) + 0.5(3) + 3(-2+2j) = (1 + 1.5 - 6) + (2 + 2 + 6)j
+    # row 1: 0 - 2(1+1j) + 0.5(-1-1j) + 3(4-3j)   = (-2 - 0.5 + 12) + (-2 - 0.5 - 9)j
+    # row 2: (2-1j) - 2(2+1j) + 0.5(5j) + 3(1)    = (2 - 4 + 3) + (-1 - 2 + 2.5)j
+    want = np.array([-3.5 + 10j, 9.5 - 11.5j, 1.0 - 0.5j])
+    got = o.project(Rc, f)
+    assert got.shape == (3,) and got.dtype == np.complex128
+    assert np.array_equal(got, want)
+    rng = np.random.default_rng(3)
+    Rc = rng.standard_normal((5, 7)) + 1j * rng.standard_normal((5, 7))
+    f = rng.standard_normal(7) + 1.0
+    loop = np.zeros(5, dtype=np.complex128)
+    for j in range(5):
+        for i in range(7):
+            loop[j] += f[i] * Rc[j, i]
+    assert np.allclose(o.project(Rc, f), loop, rtol=0, atol=1e-14)
+    assert not np.allclose(o.project(Rc, f), np.conj(loop))           # conjugation would show
+    # linear in the messages and in f; fp32 inputs are taken up to fp64 exactly
+    assert np.allclose(o.project(2 * Rc, f) - o.project(Rc, 2 * f), 0, atol=1e-14)
+    R32 = Rc.astype(np.complex64)
+    f32 = f.astype(np.float32)
+    assert np.array_equal(o.project(R32, f32), o.project(R32.astype(np.complex128), f32.astype(np.float64)))
+
+
 # ------------------------------------------------ generated projection vector
 def test_projection_generator_first_entries_by_hand():
     """Entry 0 for seed 0 worked through with Python integers, step by step, against the
