@@ -182,6 +182,26 @@ int draco_decode_repetition_async(draco_plan* plan, const float* messages_dev, i
                                   float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
                                   void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: draco_decode_repetition_async without a
+ * plan and without any allocation, by the library or the HIP runtime on its behalf.  The
+ * node-flag words the vote needs (DRACO_MAX_NODES bits = 32 bytes) live in a device array
+ * inside the library's code object: every GPU the library runs on holds one copy until the
+ * process ends, and EVERY call on a GPU uses that GPU's copy, so two calls that overlap on
+ * one GPU (different streams, or graphs replayed concurrently) race on it and must be
+ * ordered by the caller.  The array is cleared by a small kernel at the start of each
+ * call.  The first call on a device looks up the array's address (no stream work): make
+ * that call outside stream capture.
+ *   P, s, d       the code, as for draco_plan_create with DRACO_CODE_REPETITION:
+ *                 1 <= P <= DRACO_MAX_NODES (the array's size: more nodes are rejected),
+ *                 (2s+1) | P, 1 <= d <= DRACO_MAX_DIM; otherwise DRACO_EINVAL, nothing runs
+ *   messages_dev, ld_m, sum_dev, mask_dev, status_dev, stream
+ *                 as draco_decode_repetition_async; results are bit-identical to it
+ * Does not wait. */
+int draco_decode_repetition_static(int P, int s, int64_t d, const float* messages_dev, int64_t ld_m,
+                                   float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
+                                   void* stream);
+
 /* D^Cyc (Algorithm 1): V = phi(R) (random projection f R, syndromes
  * f R C_R^dagger, the s x s system for beta, the recurrence for the remaining
  * h_l, IDFT), U = complement, b with W_{.,U} b = 1_P (minimum-norm), and

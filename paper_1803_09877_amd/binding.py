@@ -45,7 +45,7 @@ EXPORTS = [
     "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
     "draco_copy_probe", "draco_plan_set_speculation",
     "draco_plan_set_projection_seed", "draco_projection_vector", "draco_plan_set_wire",
-    "draco_cyclic_locate_tol",
+    "draco_cyclic_locate_tol", "draco_decode_repetition_static",
 ]
 
 
@@ -119,6 +119,8 @@ def lib() -> ctypes.CDLL:
     L.draco_decode_repetition.restype = i32
     L.draco_decode_repetition_async.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.draco_decode_repetition_async.restype = i32
+    L.draco_decode_repetition_static.argtypes = [i32, i32, i64, vp, i64, vp, vp, vp, vp]
+    L.draco_decode_repetition_static.restype = i32
     L.draco_decode_cyclic.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.draco_decode_cyclic.restype = i32
     L.draco_decode_cyclic_hostphi.argtypes = [vp, vp, i64, vp, vp, vp, vp]
@@ -355,6 +357,12 @@ class Plan:
 
 def draco_copy_probe(src, dst, rows: int, row_len: int, ld: int, stream=None) -> None:
     _check(lib().draco_copy_probe(src.data_ptr(), dst.data_ptr(), rows, row_len, ld, _stream_ptr(stream)))
+
+
+def draco_decode_repetition_static(P: int, s: int, d: int, messages, out_sum, mask_dev, status_dev, stream=None) -> None:
+    """The allocation-free repetition decoder (no plan); outputs stay on the device."""
+    _check(lib().draco_decode_repetition_static(P, s, d, messages.data_ptr(), messages.stride(0), out_sum.data_ptr(),
+                                                mask_dev.data_ptr(), status_dev.data_ptr(), _stream_ptr(stream)))
 
 
 # Names of the C entry points, module-level, same spelling as the header.

@@ -371,6 +371,19 @@ int draco_decode_repetition(draco_plan* p, const float* messages_dev, int64_t ld
     return status;
 }
 
+int draco_decode_repetition_static(int P, int s, int64_t d, const float* messages_dev, int64_t ld_m, float* sum_dev,
+                                   uint64_t* mask_dev, int32_t* status_dev, void* stream) {
+    if (P < 1 || P > DRACO_MAX_NODES || s < 0 || d < 1 || d > DRACO_MAX_DIM) return DRACO_EINVAL;
+    if (2 * (int64_t)s + 1 > P || P % (2 * s + 1) != 0) return DRACO_EINVAL;
+    if (sum_dev == nullptr || mask_dev == nullptr || status_dev == nullptr) return DRACO_EINVAL;
+    const int rc = check_slab(messages_dev, ld_m, d);
+    if (rc != DRACO_OK) return rc;
+    if (!aligned16(sum_dev)) return DRACO_EALIGN;
+    HIP_TRY(launch_decode_rep_static(messages_dev, ld_m, sum_dev, mask_dev, status_dev, P, s, d,
+                                     static_cast<hipStream_t>(stream)));
+    return DRACO_OK;
+}
+
 namespace {
 
 int check_cyclic_args(draco_plan* p, const float* hi_dev, const float* lo_dev, bool wide, int64_t ld_m,

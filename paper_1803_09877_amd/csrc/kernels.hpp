@@ -30,6 +30,10 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
 // mask_out <- flags; status_out <- NO_MAJORITY if a group has more than s flags; flags <- 0.
 hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t* status_out,
                                     int P, int s, hipStream_t stream);
+// The vote and its finish on flag words held in a device array of the library itself (one per
+// GPU, shared by every call on that GPU): no allocation anywhere.
+hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint64_t* mask_out,
+                                    int32_t* status_out, int P, int s, int64_t d, hipStream_t stream);
 
 // B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,

@@ -2,6 +2,8 @@
 // majority-vote decoder D^Rep with the streaming vote of Algorithm 2.
 #include "device_util.hpp"
 
+#include <mutex>
+
 namespace draco {
 
 // ===========================================================================
@@ -440,6 +442,60 @@ hipError_t launch_decode_rep_finish(uint64_t* flags, uint64_t* mask_out, int32_t
                                     hipStream_t stream) {
     hipLaunchKernelGGL(decode_rep_finish_kernel, dim3(1), dim3(64), 0, stream, flags, mask_out, status_out, P, s);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// D^Rep without any allocation: the node-flag words live in a device array that is part of
+// the loaded code object, one copy per GPU, kept until the process ends.
+// ---------------------------------------------------------------------------
+namespace {
+
+// Node flags of the allocation-free decoder: kMaskWords 64-bit words (one bit per node,
+// kMaxNodes nodes at most).  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) unsigned long long scratch[kMaskWords];
+
+constexpr int kMaxDevices = 64;
+uint64_t* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, resolved once
+std::mutex g_scratch_mutex;
+
+__global__ void clear_flags_kernel(uint64_t* __restrict__ flags) {
+    if (blockIdx.x == 0 && threadIdx.x < kMaskWords) flags[threadIdx.x] = 0;
+}
+
+// Address of the current device's copy of `scratch` (resolved on the first call per device).
+hipError_t static_flags(uint64_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<uint64_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint64_t* mask_out, int32_t* status_out,
+                                    int P, int s, int64_t d, hipStream_t stream) {
+    uint64_t* flags = nullptr;
+    hipError_t e = static_flags(&flags);
+    if (e != hipSuccess) return e;
+    // the array keeps what the last call left (zero after a call that ran to its end); a fill
+    // kernel, not a memset, so that the sequence can be captured in a HIP graph
+    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(64), 0, stream, flags);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_decode_rep_vote(R, ldm, u, flags, P, s, d, stream);
+    if (e != hipSuccess) return e;
+    return launch_decode_rep_finish(flags, mask_out, status_out, P, s, stream);
 }
 
 

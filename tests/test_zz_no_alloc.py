@@ -1,0 +1,84 @@
+"""The allocation-free repetition decoder against the plan-based stream-ordered one:
+same messages in, bit-identical sum, mask and status out, on two calls in a row (the
+second on a smaller input, so whatever the first left in the library's device array
+would show)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1803_09877_amd import binding as B
+from paper_1803_09877_amd import synth
+from paper_1803_09877_amd.runner import Case
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(w, edit=None):
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        if edit is not None:
+            edit(c)
+        dev = c.device
+        ref_u = torch.full_like(c.u, float("nan"))
+        ref_mask = torch.full((4,), -1, dtype=torch.int64, device=dev)
+        ref_status = torch.full((1,), -7, dtype=torch.int32, device=dev)
+        c.plan.decode_repetition_async(c.R, ref_u, ref_mask, ref_status)
+        u = torch.full_like(c.u, float("nan"))
+        mask = torch.full((4,), -1, dtype=torch.int64, device=dev)
+        status = torch.full((1,), -7, dtype=torch.int32, device=dev)
+        B.draco_decode_repetition_static(w.P, w.s, w.d, c.R, u, mask, status)
+        torch.cuda.synchronize()
+        words = B.mask_words(w.P)
+        assert int(status.item()) == int(ref_status.item())
+        assert torch.equal(mask[:words], ref_mask[:words])
+        assert torch.equal(u[:w.d].view(torch.int32), ref_u[:w.d].view(torch.int32))
+        if u.numel() > w.d:
+            assert torch.isnan(u[w.d:]).all()
+        return int(status.item()), B.mask_to_bool(mask.cpu().numpy().view(np.uint64), w.P), c.expected_mask()
+    finally:
+        c.close()
+
+
+def test_static_decoder_matches_the_plan_based_one_twice_in_a_row():
+    big = synth.Workload(name="rep_static_big", code="rep", P=45, s=2, d=300_007, sigma=1e-2,
+                         attacks=("signflip", "noise"), placement="distinct_groups", seed=synth.SEED_BASE + 901)
+    small = synth.Workload(name="rep_static_small", code="rep", P=9, s=1, d=1_001, sigma=1.0,
+                           attacks=("noise",), placement="any", seed=synth.SEED_BASE + 902)
+    for w in (big, small):
+        print(f"static decoder case {w.name} P={w.P} s={w.s} d={w.d}", flush=True)
+        st, m, want = _both(w)
+        assert st == B.OK and np.array_equal(m, want)
+
+
+def test_static_decoder_after_a_failed_vote_and_with_a_second_mask_word():
+    def too_many(c):
+        for j in (0, 1, 2):
+            c.R[j, :c.mlen] = float(j + 1)
+    w = synth.Workload(name="rep_static_fail", code="rep", P=10, s=2, d=2_050, sigma=1.0, attacks=(),
+                       placement="any", seed=synth.SEED_BASE + 903)
+    st, _, _ = _both(w, edit=too_many)
+    assert st == B.NO_MAJORITY
+    w2 = synth.Workload(name="rep_static_wide", code="rep", P=255, s=2, d=515, sigma=1.0,
+                        attacks=("noise", "signflip"), placement="distinct_groups", seed=synth.SEED_BASE + 904)
+    st, m, want = _both(w2)
+    assert st == B.OK and np.array_equal(m, want)
+
+
+def test_static_decoder_rejects_what_does_not_fit():
+    dev = torch.device("cuda:0")
+    R = torch.zeros((3, 8), dtype=torch.float32, device=dev)
+    u = torch.zeros(8, dtype=torch.float32, device=dev)
+    mask = torch.zeros(8, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    L = B.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    args = (R.data_ptr(), 8, u.data_ptr(), mask.data_ptr(), status.data_ptr(), st)
+    assert L.draco_decode_repetition_static(B.MAX_NODES + 1, 0, 8, *args) == B.EINVAL   # more nodes than the array has bits
+    assert L.draco_decode_repetition_static(4, 1, 8, *args) == B.EINVAL                  # 3 does not divide 4
+    assert L.draco_decode_repetition_static(3, 1, 0, *args) == B.EINVAL
+    assert L.draco_decode_repetition_static(3, 1, 8, R.data_ptr() + 4, 8, u.data_ptr(), mask.data_ptr(),
+                                            status.data_ptr(), st) == B.EALIGN
+    assert L.draco_decode_repetition_static(3, 1, 8, R.data_ptr(), 8, None, mask.data_ptr(), status.data_ptr(),
+                                            st) == B.EINVAL
