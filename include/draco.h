@@ -210,8 +210,8 @@ int draco_decode_repetition_static(int P, int s, int64_t d, const float* message
  *   f_dev        [ceil(d/2)] fp32: the random vector f ~ N(1, I) of phi, one
  *                entry per complex coordinate, drawn by the caller; or NULL:
  *                the projection kernel then makes the entries on the fly from
- *                the plan's projection seed (draco_plan_set_projection_seed)
- *                and no vector is read from memory
+ *                a seed that changes with every decode (see
+ *                draco_plan_set_projection_seed) and no vector is read from memory
  *   sum_dev      [d] fp32 out
  *   mask_host    as above: the located set V
  * A node whose message holds NaN or Inf is flagged outright (it is one of the
@@ -226,16 +226,24 @@ int draco_decode_cyclic(draco_plan* plan, const float* messages_dev, int64_t ld_
                         const float* f_dev, float* sum_dev, uint64_t* mask_host,
                         void* stream);
 
-/* Seed of the generated projection vector used when f_dev is NULL (default 0).
- * Entry i is a counter-based function of (seed, i): splitmix64's finaliser on
- * seed + (i+1)*0x9E3779B97F4A7C15 gives two 24-bit uniforms u1 (top bits) and
- * u2 (bits 16..39), and f_i = fp32(1 + sqrt(-2 ln u1) cos(2 pi u2)).  A fresh
- * seed per decode keeps an adversary from preparing a message orthogonal to f.
- * The seed travels as a kernel argument: a captured HIP graph replays the seed
- * it was captured with (pass f_dev, refreshed by the caller, to vary f there).
+/* The generated projection vector (f_dev == NULL).  Entry i is a counter-based
+ * function of (seed, i): splitmix64's finaliser on seed + (i+1)*0x9E3779B97F4A7C15
+ * gives two 24-bit uniforms u1 (top bits) and u2 (bits 16..39), and
+ * f_i = fp32(1 + sqrt(-2 ln u1) cos(2 pi u2)).
+ * phi needs an f the adversaries cannot know in advance (Lemma 3), so every
+ * decode of a plan uses another seed: a plan starts from a base seed taken from
+ * the system's entropy source when it is created; the k-th decode (k = 0, 1, ...)
+ * after the base was set uses seed_0 = base and, for k > 0, seed_k = splitmix64's
+ * finaliser on base + k*0x9E3779B97F4A7C15.  draco_plan_set_projection_seed sets
+ * the base (and restarts k at 0), which makes a run reproducible;
+ * draco_plan_last_projection_seed reports the seed the most recent such decode
+ * used (DRACO_EINVAL before the first).  The seed travels as a kernel argument:
+ * a captured HIP graph replays the seed it was captured with (pass f_dev,
+ * refreshed by the caller, to vary f there).
  * draco_projection_vector writes the entries for a seed (draco_message_len()/2
  * of them) to host memory (inspection, tests). */
 int draco_plan_set_projection_seed(draco_plan* plan, uint64_t seed);
+int draco_plan_last_projection_seed(const draco_plan* plan, uint64_t* seed);
 int draco_projection_vector(const draco_plan* plan, uint64_t seed, float* f_host);
 
 /* Speculative single-pass decode (cyclic code, s <= 16; on by default).  While
@@ -297,6 +305,46 @@ int draco_cyclic_locate_tol(const draco_plan* plan, const double* gamma_host, do
 int draco_cyclic_recombination_vector(const draco_plan* plan, const uint64_t* mask_host,
                                       double* b_host);
 
+/* ---- the three calls without a plan ------------------------------------ */
+
+/* encode(assign, grads_per_sample) -> messages.  assign_host is the P x P 0/1
+ * allocation matrix A (row j = node j, as draco_plan_assign writes it); it must
+ * be A^Rep or A^Cyc of Sec. 3 for `code` (every row holds r = 2s+1 ones, which
+ * fixes s), otherwise DRACO_EINVAL.  samples_dev is [B][ld_g] with B a multiple
+ * of P (B = P: one unit gradient per row), as for draco_encode_samples; the
+ * cyclic code uses the packed wire.  The library keeps one plan per
+ * (code, P, s, d, device) behind these calls and prepares it on first use (that
+ * call allocates; later ones do not).  Calls with the same parameters take
+ * turns.  Asynchronous on `stream`. */
+int draco_encode_oneshot(const uint8_t* assign_host, int code, int P, int64_t d,
+                         const float* samples_dev, int64_t B, int64_t ld_g,
+                         float* messages_dev, int64_t ld_m, void* stream);
+
+/* decode_repetition(messages, P, s) -> (sum, adversary_mask) and
+ * decode_cyclic(messages, P, s) -> (sum, adversary_mask): draco_decode_repetition
+ * / draco_decode_cyclic on the cached plan for (P, s, d).  The cyclic form draws
+ * f inside the library (f_dev = NULL: a fresh seed per call).  Return values,
+ * outputs and waiting as for the plan forms. */
+int draco_decode_repetition_oneshot(const float* messages_dev, int64_t ld_m, int P, int s,
+                                    int64_t d, float* sum_dev, uint64_t* mask_host, void* stream);
+int draco_decode_cyclic_oneshot(const float* messages_dev, int64_t ld_m, int P, int s,
+                                int64_t d, float* sum_dev, uint64_t* mask_host, void* stream);
+
+/* Destroy every cached plan (waits for the device).  Not to be called while a
+ * plan-free call is running. */
+void draco_cache_clear(void);
+
+/* ---- parameter server: the model update -------------------------------- */
+
+/* Mini-batch SGD's update with the decoded sum (Sec. 2, "Distributed Training":
+ * w_k = w_{k-1} - (gamma/|S_k|) * sum of the batch's gradients):
+ * params[i] <- params[i] - scale * sum[i] for i < d, in fp32 with one fused
+ * multiply-add per parameter (scale = learning rate / B).  One read of the sum,
+ * one read-modify-write of the parameters.  Both pointers 16-byte aligned.
+ * Asynchronous on `stream`. */
+int draco_apply_update(float* params_dev, const float* sum_dev, int64_t d, float scale,
+                       void* stream);
+
 /* ---- misc -------------------------------------------------------------- */
 
 /* Static, NUL-terminated description of a status value. */
@@ -305,28 +353,6 @@ const char* draco_strerror(int status);
 /* Text describing the last HIP runtime failure behind a DRACO_EHIP return on the
  * calling thread (the failing call and HIP's error string); "" if none. */
 const char* draco_last_hip_error(void);
-
-/* Plain device-to-device copy of a [rows][ld] fp32 slab (row_len floats used
- * per row; row_len and ld multiples of 4, pointers 16-byte aligned; rows <=
- * 65535) with 16-byte non-temporal accesses, one 4 KiB piece of one row per
- * workgroup, pieces of a row varying fastest: a calibration kernel, the fastest
- * slab copy found on this GPU.  Timing it gives the copy bandwidth the GPU
- * sustains (the ceiling of the encoders, which read and write equal amounts);
- * profiling it gives the scale of the hardware byte counters for a known
- * 2*4*rows*row_len bytes.  Asynchronous on `stream`. */
-int draco_copy_probe(const float* src_dev, float* dst_dev, int rows, int64_t row_len, int64_t ld,
-                     void* stream);
-
-/* Kernel timing with HIP events recorded on the stream each kernel is launched
- * on.  draco_plan_set_timing(plan, n) gives every kernel kind n event pairs
- * (n = 0 switches timing off); from then on each launch of a kind uses the next
- * free pair (launches beyond n are not timed) and nothing waits.
- * draco_plan_kernel_time waits for the recorded kernels of one kind, returns
- * their summed duration in milliseconds and their number, and frees the pairs
- * for reuse.  kind: 0 encode, 1 repetition vote, 2 cyclic projection (with its
- * small reduction), 3 cyclic recombination. */
-int draco_plan_set_timing(draco_plan* plan, int max_records);
-int draco_plan_kernel_time(draco_plan* plan, int kind, double* total_ms, int* launches);
 
 #ifdef __cplusplus
 }

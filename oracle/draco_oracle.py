@@ -533,3 +533,13 @@ def decode_cyclic_unpacked(R: np.ndarray, f: np.ndarray, s: int, b_mode: str = "
     rounding; its largest magnitude is returned as `residual` for tests to bound."""
     u_hat, mask, status = decode_cyclic_complex(wire_to_complex(R), f, s, b_mode)
     return u_hat.real.copy(), mask, status, float(np.max(np.abs(u_hat.imag))) if u_hat.size else 0.0
+
+
+# --------------------------------------------------------------------------
+# Parameter server: the model update (Sec. 2, "Distributed Training").
+# --------------------------------------------------------------------------
+def sgd_update(w: np.ndarray, grad_sum: np.ndarray, gamma: float, batch: int) -> np.ndarray:
+    """Mini-batch SGD's step with the recovered gradient sum:
+    w_k = w_{k-1} - (gamma / |S_k|) * sum_{i in S_k} g_i, in fp64."""
+    w = np.asarray(w, dtype=np.float64)
+    return w - (float(gamma) / float(batch)) * np.asarray(grad_sum, dtype=np.float64)

@@ -21,10 +21,10 @@ SOURCES = [os.path.join(_HERE, "csrc", n) for n in (
     # slowest first: the per-s encoder units dominate the build time
     "cyc_encode_s10.hip", "cyc_encode_s9.hip", "cyc_encode_s8.hip", "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
     "cyc_encode_s2.hip", "cyc_encode_s1.hip", "cyc_encode_s0.hip", "rep.hip", "cyc_encode.hip", "cyc_decode.hip",
-    "locate.hip", "api.hip", "host_math.cpp")]
+    "locate.hip", "update.hip", "api.hip", "host_math.cpp")]
 HEADERS = [os.path.join(_HERE, "csrc", n) for n in (
     "kernels.hpp", "device_util.hpp", "cyc_encode_kernels.hpp", "cyc_encode_s.inc", "host_math.hpp")] + [
-    os.path.join(_ROOT, "include", "draco.h")]
+    os.path.join(_ROOT, "include", "draco.h"), os.path.join(_ROOT, "include", "draco_bench.h")]
 BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
@@ -32,7 +32,7 @@ WIRE_PACKED, WIRE_UNPACKED = 0, 1
 TAU, TAU_WIDE = 32.0 / 16777216.0, 1.0 / 68719476736.0
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
 EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
-KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE = 0, 1, 2, 3
+KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE, KIND_LOCATE = 0, 1, 2, 3, 4
 MAX_NODES = 256
 
 EXPORTS = [
@@ -42,11 +42,14 @@ EXPORTS = [
     "draco_decode_cyclic_async", "draco_decode_cyclic_hostphi", "draco_encode_wide", "draco_encode_samples",
     "draco_decode_cyclic_wide", "draco_decode_cyclic_wide_async",
     "draco_cyclic_locate", "draco_cyclic_recombination_vector", "draco_strerror",
-    "draco_plan_set_timing", "draco_plan_kernel_time", "draco_last_hip_error",
-    "draco_copy_probe", "draco_plan_set_speculation",
+    "draco_last_hip_error", "draco_plan_set_speculation",
     "draco_plan_set_projection_seed", "draco_projection_vector", "draco_plan_set_wire",
     "draco_cyclic_locate_tol", "draco_decode_repetition_static",
+    "draco_plan_last_projection_seed", "draco_encode_oneshot", "draco_decode_repetition_oneshot",
+    "draco_decode_cyclic_oneshot", "draco_cache_clear", "draco_apply_update",
 ]
+# the measuring instruments of include/draco_bench.h
+BENCH_EXPORTS = ["draco_copy_probe", "draco_plan_set_timing", "draco_plan_kernel_time", "draco_plan_kernel_times"]
 
 
 def build(verbose: bool = False) -> str:
@@ -159,6 +162,20 @@ def lib() -> ctypes.CDLL:
     L.draco_plan_set_timing.restype = i32
     L.draco_plan_kernel_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     L.draco_plan_kernel_time.restype = i32
+    L.draco_plan_kernel_times.argtypes = [vp, i32, vp, i32, ctypes.POINTER(i32)]
+    L.draco_plan_kernel_times.restype = i32
+    L.draco_plan_last_projection_seed.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
+    L.draco_plan_last_projection_seed.restype = i32
+    L.draco_encode_oneshot.argtypes = [vp, i32, i32, i64, vp, i64, i64, vp, i64, vp]
+    L.draco_encode_oneshot.restype = i32
+    L.draco_decode_repetition_oneshot.argtypes = [vp, i64, i32, i32, i64, vp, vp, vp]
+    L.draco_decode_repetition_oneshot.restype = i32
+    L.draco_decode_cyclic_oneshot.argtypes = [vp, i64, i32, i32, i64, vp, vp, vp]
+    L.draco_decode_cyclic_oneshot.restype = i32
+    L.draco_cache_clear.argtypes = []
+    L.draco_cache_clear.restype = None
+    L.draco_apply_update.argtypes = [vp, vp, i64, ctypes.c_float, vp]
+    L.draco_apply_update.restype = i32
     _lib = L
     return L
 
@@ -342,6 +359,11 @@ class Plan:
         _check(lib().draco_projection_vector(self._h, seed, f.ctypes.data))
         return f
 
+    def last_projection_seed(self) -> int:
+        seed = ctypes.c_uint64()
+        _check(lib().draco_plan_last_projection_seed(self._h, ctypes.byref(seed)))
+        return seed.value
+
     def set_speculation(self, enabled: bool) -> None:
         _check(lib().draco_plan_set_speculation(self._h, 1 if enabled else 0))
 
@@ -353,6 +375,13 @@ class Plan:
         ms, n = ctypes.c_double(), ctypes.c_int()
         _check(lib().draco_plan_kernel_time(self._h, kind, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
+
+    def kernel_times(self, kind: int, capacity: int = 4096) -> np.ndarray:
+        """Durations in ms of the timed launches of one kind since the last query, in launch order."""
+        out = np.zeros(capacity, dtype=np.float64)
+        n = ctypes.c_int()
+        _check(lib().draco_plan_kernel_times(self._h, kind, out.ctypes.data, capacity, ctypes.byref(n)))
+        return out[:min(n.value, capacity)].copy()
 
 
 def draco_copy_probe(src, dst, rows: int, row_len: int, ld: int, stream=None) -> None:
@@ -383,40 +412,34 @@ def draco_decode_cyclic(plan: Plan, messages, f, out_sum, stream=None):
 
 
 # ---------------------------------------------------------------------------
-# One-shot forms with the argument lists the method's description uses --
-# encode(assign, grads) -> messages; decode(messages, P, s) -> (sum, mask) --
-# on torch tensors.  They keep one plan per (code, P, s, d, device) and
-# allocate the outputs; every step of the work is the library's.
+# The three calls without a plan, on torch tensors: encode(assign, grads) -> messages;
+# decode(messages, P, s) -> (sum, mask).  The library keeps the plans; this side only
+# allocates the outputs and marshals.
 # ---------------------------------------------------------------------------
-_PLANS: dict = {}
-
-
-def cached_plan(code: int, P: int, s: int, d: int, device) -> Plan:
-    import torch
-    dev = torch.device(device)
-    key = (code, P, s, d, dev.index if dev.index is not None else torch.cuda.current_device())
-    plan = _PLANS.get(key)
-    if plan is None:
-        with torch.cuda.device(key[4]):
-            plan = Plan(code, P, s, d)
-            plan.prepare()
-        _PLANS[key] = plan
-    return plan
-
-
 def _row_stride(n: int) -> int:
     return (n + 3) // 4 * 4
 
 
-def encode(code: int, s: int, grads):
-    """grads [P][>= d] fp32 on the GPU (d = grads.shape[1]) -> messages [P][message_len]."""
+def draco_apply_update(params, out_sum, d: int, scale: float, stream=None) -> None:
+    """params[:d] -= scale * out_sum[:d] on the device (the parameter server's SGD step)."""
+    _check(lib().draco_apply_update(params.data_ptr(), out_sum.data_ptr(), d, scale, _stream_ptr(stream)))
+
+
+def encode(assign: np.ndarray, code: int, grads, d: int | None = None):
+    """assign [P][P] 0/1 (the code's allocation matrix), grads [B][>= d] fp32 on the GPU with B a
+    multiple of P -> messages [P][message_len]."""
     import torch
-    P, d = grads.shape
-    plan = cached_plan(code, P, s, d, grads.device)
+    A = np.ascontiguousarray(assign, dtype=np.uint8)
+    P = A.shape[0]
+    d = grads.shape[1] if d is None else d
+    mlen = d if code == CODE_REPETITION else 2 * ((d + 1) // 2)
     with torch.cuda.device(grads.device):
-        out = torch.empty((P, _row_stride(plan.message_len)), dtype=torch.float32, device=grads.device)
-        plan.encode(grads, out)
-    return out[:, :plan.message_len]
+        out = torch.empty((P, _row_stride(mlen)), dtype=torch.float32, device=grads.device)
+        st = lib().draco_encode_oneshot(A.ctypes.data, code, P, d, grads.data_ptr(), grads.shape[0], grads.stride(0),
+                                        out.data_ptr(), out.stride(0), _stream_ptr(None))
+    if st != OK:
+        raise DracoError(st)
+    return out[:, :mlen]
 
 
 def decode_repetition(messages, P: int, s: int):
@@ -424,22 +447,24 @@ def decode_repetition(messages, P: int, s: int):
     import torch
     assert messages.shape[0] == P
     d = messages.shape[1]
-    plan = cached_plan(CODE_REPETITION, P, s, d, messages.device)
+    words = np.zeros(mask_words(P), dtype=np.uint64)
     with torch.cuda.device(messages.device):
         out = torch.empty(_row_stride(d), dtype=torch.float32, device=messages.device)
-        mask, status = plan.decode_repetition(messages, out)
-    return out[:d], mask, status
+        status = lib().draco_decode_repetition_oneshot(messages.data_ptr(), messages.stride(0), P, s, d, out.data_ptr(),
+                                                       words.ctypes.data, _stream_ptr(None))
+    _check(status)
+    return out[:d], mask_to_bool(words, P), status
 
 
-def decode_cyclic(messages, P: int, s: int, d: int, f=None, seed: int = 0):
+def decode_cyclic(messages, P: int, s: int, d: int):
     """messages [P][2*ceil(d/2)] -> (sum [d], mask bool[P], status); the projection vector is
-    `f` if given, else generated inside the library from `seed`."""
+    drawn inside the library, afresh for every call."""
     import torch
     assert messages.shape[0] == P
-    plan = cached_plan(CODE_CYCLIC, P, s, d, messages.device)
+    words = np.zeros(mask_words(P), dtype=np.uint64)
     with torch.cuda.device(messages.device):
         out = torch.empty(_row_stride(d), dtype=torch.float32, device=messages.device)
-        if f is None:
-            plan.set_projection_seed(seed)
-        mask, status = plan.decode_cyclic(messages, f, out)
-    return out[:d], mask, status
+        status = lib().draco_decode_cyclic_oneshot(messages.data_ptr(), messages.stride(0), P, s, d, out.data_ptr(),
+                                                   words.ctypes.data, _stream_ptr(None))
+    _check(status)
+    return out[:d], mask_to_bool(words, P), status

@@ -2,6 +2,7 @@
 // with its device tables and scratch, and the sequencing of kernels and host
 // algebra for each entry point.
 #include "../../include/draco.h"
+#include "../../include/draco_bench.h"
 
 #include <hip/hip_runtime.h>
 
@@ -9,7 +10,11 @@
 #include <complex>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
+#include <random>
+#include <tuple>
 #include <vector>
 
 #include "host_math.hpp"
@@ -20,7 +25,7 @@ using namespace draco;
 
 namespace {
 
-enum Kind { kEncode = 0, kVote = 1, kProject = 2, kRecombine = 3, kKinds = 4 };
+enum Kind { kEncode = 0, kVote = 1, kProject = 2, kRecombine = 3, kLocateKind = 4, kKinds = 5 };
 
 // Ring of HIP event pairs bracketing the kernels of one kind.
 struct Timer {
@@ -45,7 +50,9 @@ struct draco_plan {
     double2* b0_dev = nullptr;       // P: recombination vector when no node is flagged
     int32_t* spec_dev = nullptr;     // 2 words: speculate next / speculated now (see cyc_decode.hip)
     bool speculation = true;
-    uint64_t f_seed = 0;             // seed of the generated projection vector (f_dev == NULL)
+    uint64_t f_seed = 0;             // base seed of the generated projection vector (f_dev == NULL)
+    uint64_t f_calls = 0;            // decodes that generated f since the base seed was set
+    uint64_t f_last = 0;             // seed the last such decode used
     int wire = DRACO_WIRE_PACKED;    // cyclic code: packed (ceil(d/2) complex) or unpacked (d complex)
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
@@ -74,6 +81,21 @@ bool unpacked(const draco_plan* p) { return p->wire == DRACO_WIRE_UNPACKED; }
 int64_t message_len(const draco_plan* p) {
     if (p->code == DRACO_CODE_REPETITION) return p->d;
     return unpacked(p) ? 2 * p->d : 2 * ((p->d + 1) / 2);
+}
+
+// Seed of the generated projection vector for the next decode: the base seed itself for the
+// first decode after it was set, then splitmix64's finaliser on base + k * golden ratio for
+// the k-th one, so that no two decodes project on the same f.
+uint64_t next_projection_seed(draco_plan* p) {
+    uint64_t z = p->f_seed + p->f_calls * 0x9E3779B97F4A7C15ull;
+    if (p->f_calls != 0) {
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+    }
+    ++p->f_calls;
+    p->f_last = z;
+    return z;
 }
 
 // Cyclic code: how many floats of a message the decode kernels treat as packed pairs
@@ -184,7 +206,13 @@ int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d) {
     p->P = P;
     p->s = s;
     p->d = d;
-    if (code == DRACO_CODE_CYCLIC) p->cyc.build(P, s);
+    if (code == DRACO_CODE_CYCLIC) {
+        p->cyc.build(P, s);
+        // phi draws f afresh for every decode (Lemma 3 needs f unknown to the adversaries):
+        // the base seed comes from the system's entropy source unless the caller sets one
+        std::random_device rd;
+        p->f_seed = ((uint64_t)rd() << 32) ^ (uint64_t)rd();
+    }
     *out = p;
     return DRACO_OK;
 }
@@ -411,13 +439,17 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P;
     int32_t* spec = p->speculation ? p->spec_dev : nullptr;
+    const uint64_t seed = f_dev == nullptr ? next_projection_seed(p) : 0;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
                                    sum_dev, unpacked(p), spec, P, paired_len(p), st));
     }
-    HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev, p->b_dev, p->idx_dev,
-                              p->idx_dev + P, spec, st));
+    {
+        Timed timed(p, kLocateKind, st);
+        HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev,
+                                  p->b_dev, p->idx_dev, p->idx_dev + P, spec, st));
+    }
     {
         Timed timed(p, kRecombine, st);
         HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev,
@@ -434,9 +466,10 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     const float* lo = wide ? lo_dev : nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int P = p->P, s = p->s;
+    const uint64_t seed = f_dev == nullptr ? next_projection_seed(p) : 0;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, p->f_seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
                                    sum_dev, unpacked(p), nullptr, P, paired_len(p), st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
@@ -581,6 +614,13 @@ int draco_plan_set_wire(draco_plan* p, int wire) {
 int draco_plan_set_projection_seed(draco_plan* p, uint64_t seed) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC) return DRACO_EINVAL;
     p->f_seed = seed;
+    p->f_calls = 0;
+    return DRACO_OK;
+}
+
+int draco_plan_last_projection_seed(const draco_plan* p, uint64_t* seed) {
+    if (p == nullptr || seed == nullptr || p->code != DRACO_CODE_CYCLIC || p->f_calls == 0) return DRACO_EINVAL;
+    *seed = p->f_last;
     return DRACO_OK;
 }
 
@@ -645,6 +685,127 @@ int draco_plan_kernel_time(draco_plan* p, int kind, double* total_ms, int* launc
     *launches = t.used;
     t.used = 0;
     return DRACO_OK;
+}
+
+int draco_plan_kernel_times(draco_plan* p, int kind, double* ms_host, int capacity, int* launches) {
+    if (p == nullptr || kind < 0 || kind >= kKinds || launches == nullptr || capacity < 0) return DRACO_EINVAL;
+    if (capacity > 0 && ms_host == nullptr) return DRACO_EINVAL;
+    Timer& t = p->timers[kind];
+    for (int i = 0; i < t.used; ++i) {
+        HIP_TRY(hipEventSynchronize(t.stop[i]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+        if (i < capacity) ms_host[i] = (double)ms;
+    }
+    *launches = t.used;
+    t.used = 0;
+    return DRACO_OK;
+}
+
+int draco_apply_update(float* params_dev, const float* sum_dev, int64_t d, float scale, void* stream) {
+    if (params_dev == nullptr || sum_dev == nullptr || d < 1 || d > DRACO_MAX_DIM) return DRACO_EINVAL;
+    if (!aligned16(params_dev) || !aligned16(sum_dev)) return DRACO_EALIGN;
+    HIP_TRY(launch_apply_update(params_dev, sum_dev, scale, d, static_cast<hipStream_t>(stream)));
+    return DRACO_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+// Plan-free forms: (code, P, s, d) in, a cached plan per parameter set and device inside.
+// ---------------------------------------------------------------------------
+namespace {
+
+struct CachedPlan {
+    draco_plan* plan = nullptr;
+    std::mutex busy;  // a plan's scratch serves one call at a time
+};
+using CacheKey = std::tuple<int, int, int, int64_t, int>;  // code, P, s, d, device
+
+std::mutex g_cache_mutex;
+// never destroyed: plans hold device memory, and the HIP runtime may be gone by the time
+// static destructors run; draco_cache_clear() is the way to release them
+std::map<CacheKey, CachedPlan*>* g_cache = nullptr;
+
+int cached_plan(int code, int P, int s, int64_t d, CachedPlan** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (g_cache == nullptr) g_cache = new (std::nothrow) std::map<CacheKey, CachedPlan*>();
+    if (g_cache == nullptr) return DRACO_ENOMEM;
+    const CacheKey key(code, P, s, d, dev);
+    auto it = g_cache->find(key);
+    if (it == g_cache->end()) {
+        draco_plan* plan = nullptr;
+        int rc = draco_plan_create(&plan, code, P, s, d);
+        if (rc != DRACO_OK) return rc;
+        rc = prepare(plan);
+        if (rc != DRACO_OK) {
+            draco_plan_destroy(plan);
+            return rc;
+        }
+        CachedPlan* c = new (std::nothrow) CachedPlan();
+        if (c == nullptr) {
+            draco_plan_destroy(plan);
+            return DRACO_ENOMEM;
+        }
+        c->plan = plan;
+        it = g_cache->emplace(key, c).first;
+    }
+    *out = it->second;
+    return DRACO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int draco_encode_oneshot(const uint8_t* assign_host, int code, int P, int64_t d, const float* samples_dev, int64_t B,
+                         int64_t ld_g, float* messages_dev, int64_t ld_m, void* stream) {
+    if (assign_host == nullptr || P < 1 || P > DRACO_MAX_NODES) return DRACO_EINVAL;
+    // the assignment matrix names the code: every node holds r = 2s+1 gradients
+    int r = 0;
+    for (int k = 0; k < P; ++k) r += assign_host[k] != 0;
+    if (r < 1 || (r & 1) == 0) return DRACO_EINVAL;
+    const int s = (r - 1) / 2;
+    CachedPlan* c = nullptr;
+    int rc = cached_plan(code, P, s, d, &c);
+    if (rc != DRACO_OK) return rc;
+    std::vector<uint8_t> A((size_t)P * P);
+    rc = draco_plan_assign(c->plan, A.data());
+    if (rc != DRACO_OK) return rc;
+    for (size_t i = 0; i < A.size(); ++i)
+        if ((assign_host[i] != 0) != (A[i] != 0)) return DRACO_EINVAL;  // not this code's allocation matrix
+    std::lock_guard<std::mutex> lock(c->busy);
+    return draco_encode_samples(c->plan, samples_dev, B, ld_g, messages_dev, ld_m, stream);
+}
+
+int draco_decode_repetition_oneshot(const float* messages_dev, int64_t ld_m, int P, int s, int64_t d, float* sum_dev,
+                                    uint64_t* mask_host, void* stream) {
+    CachedPlan* c = nullptr;
+    const int rc = cached_plan(DRACO_CODE_REPETITION, P, s, d, &c);
+    if (rc != DRACO_OK) return rc;
+    std::lock_guard<std::mutex> lock(c->busy);
+    return draco_decode_repetition(c->plan, messages_dev, ld_m, sum_dev, mask_host, stream);
+}
+
+int draco_decode_cyclic_oneshot(const float* messages_dev, int64_t ld_m, int P, int s, int64_t d, float* sum_dev,
+                                uint64_t* mask_host, void* stream) {
+    CachedPlan* c = nullptr;
+    const int rc = cached_plan(DRACO_CODE_CYCLIC, P, s, d, &c);
+    if (rc != DRACO_OK) return rc;
+    std::lock_guard<std::mutex> lock(c->busy);
+    return draco_decode_cyclic(c->plan, messages_dev, ld_m, nullptr, sum_dev, mask_host, stream);
+}
+
+void draco_cache_clear(void) {
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (g_cache == nullptr) return;
+    for (auto& kv : *g_cache) {
+        draco_plan_destroy(kv.second->plan);
+        delete kv.second;
+    }
+    g_cache->clear();
 }
 
 }  // extern "C"

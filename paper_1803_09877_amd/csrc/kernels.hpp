@@ -79,6 +79,9 @@ hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, c
                                 const int32_t* idx, const int32_t* nu, const int32_t* spec_state, int P,
                                 float* u, bool realout, int64_t d, hipStream_t stream);
 
+// params[i] <- params[i] - scale * sum[i], i < d (the model update of mini-batch SGD).
+hipError_t launch_apply_update(float* params, const float* sum, float scale, int64_t d, hipStream_t stream);
+
 // dst[j][0..row_len) <- src[j][0..row_len) for j < rows, row_len a multiple of 4 floats
 // (bandwidth / counter calibration).
 hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row_len, int64_t ld,

@@ -110,23 +110,24 @@ __global__ __launch_bounds__(kBlock) void encode_rep_generic_kernel(const float*
     else encode_rep_generic_body<false>(G, ldg, Z, ldm, groups, rows, copies, d);
 }
 
-// Streaming majority vote (Algorithm 2) on the bit patterns of one coordinate.
+// Majority candidate among R bit patterns of one coordinate (the streaming vote of
+// Algorithm 2): one candidate and its lead over everything else seen so far, updated with
+// selects only.  A copy that agrees raises the lead, one that differs lowers it, and when
+// the lead is used up the next copy takes over as candidate.  If some pattern is held by
+// more than half of the copies it is the result.
+__device__ __forceinline__ void vote_step(uint32_t copy, uint32_t& candidate, int& lead) {
+    const bool vacant = lead == 0;
+    const int delta = (copy == candidate) ? 1 : -1;
+    candidate = vacant ? copy : candidate;
+    lead = vacant ? 1 : lead + delta;
+}
 template <int R>
 __device__ __forceinline__ uint32_t vote(const uint32_t (&v)[R]) {
-    uint32_t ma = v[0];
-    int counter = 0;
+    uint32_t candidate = v[0];
+    int lead = 1;
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-        if (counter == 0) {
-            ma = v[i];
-            counter = 1;
-        } else if (v[i] == ma) {
-            ++counter;
-        } else {
-            --counter;
-        }
-    }
-    return ma;
+    for (int i = 1; i < R; ++i) vote_step(v[i], candidate, lead);
+    return candidate;
 }
 
 // Node flags of one wavefront (wavefront-uniform values, kept in scalar registers).
@@ -261,8 +262,8 @@ __global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restr
     publish_flags(wflags, flags);
 }
 
-// Any r: the copies of a group stream through Algorithm 2's two words of state per
-// coordinate (candidate, counter), eight rows in flight, so every message byte is read
+// Any r: the copies of a group stream through the vote's two words of state per
+// coordinate (candidate, lead), eight rows in flight, so every message byte is read
 // once.  Only where some lane of the wavefront saw a copy differ from the first one is the
 // group read again, to flag the nodes that differ from the winner.
 template <bool FULL>
@@ -278,21 +279,11 @@ __device__ __forceinline__ void decode_rep_stream_body(const float* __restrict__
         if (active) t = ldx<FULL>(p, n);
         return make_uint4(__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w));
     };
-    auto step = [](uint32_t v, uint32_t& ma, int& counter) {
-        if (counter == 0) {
-            ma = v;
-            counter = 1;
-        } else if (v == ma) {
-            ++counter;
-        } else {
-            --counter;
-        }
-    };
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int g = 0; g < groups; ++g) {
         const float* src = Rm + (int64_t)g * r * ldm + c0;
-        uint4 ma = make_uint4(0u, 0u, 0u, 0u), first = ma;
-        int cx = 0, cy = 0, cz = 0, cw = 0;
+        uint4 ma = make_uint4(0u, 0u, 0u, 0u), first = ma;   // ma: the four coordinates' candidates
+        int cx = 0, cy = 0, cz = 0, cw = 0;                   // their leads (0: no candidate yet)
         uint32_t differ = 0;
         for (int i0 = 0; i0 < r; i0 += UN) {
             uint4 x[UN];
@@ -304,10 +295,10 @@ __device__ __forceinline__ void decode_rep_stream_body(const float* __restrict__
                 if (i0 + i < r) {
                     if (i0 + i == 0) first = x[i];
                     differ |= (x[i].x ^ first.x) | (x[i].y ^ first.y) | (x[i].z ^ first.z) | (x[i].w ^ first.w);
-                    step(x[i].x, ma.x, cx);
-                    step(x[i].y, ma.y, cy);
-                    step(x[i].z, ma.z, cz);
-                    step(x[i].w, ma.w, cw);
+                    vote_step(x[i].x, ma.x, cx);
+                    vote_step(x[i].y, ma.y, cy);
+                    vote_step(x[i].z, ma.z, cz);
+                    vote_step(x[i].w, ma.w, cw);
                 }
             }
         }

@@ -385,8 +385,8 @@ def test_cyc_generated_projection_vector(P, s, d, attacks, sigma, seed):
         fo = o.projection_vector((d + 1) // 2, seed)
         uo, mo, so = o.decode_cyclic(R_host, fo, s, d)
         assert so == o.OK and np.array_equal(mo, c.expected_mask())
-        c.plan.set_projection_seed(seed)
         for form in ("device", "host"):
+            c.plan.set_projection_seed(seed)           # the first decode after this call uses exactly `seed`
             c.u.fill_(float("nan"))
             fn = c.plan.decode_cyclic if form == "device" else c.plan.decode_cyclic_hostphi
             mask, status = fn(c.R, None, c.u)
@@ -819,25 +819,125 @@ def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d)
 
 # ------------------------------------------------------------ arguments -----
 def test_one_shot_forms():
-    """encode(code, s, grads) -> messages and decode(messages, P, s) -> (sum, mask) with cached plans."""
+    """The three calls without a plan: encode(assign, grads) -> messages and
+    decode(messages, P, s) -> (sum, mask), the plans cached inside the library."""
     dev = torch.device("cuda:0")
     for code, P, s, d in ((B.CODE_REPETITION, 15, 2, 4099), (B.CODE_CYCLIC, 15, 2, 4099), (B.CODE_CYCLIC, 15, 2, 4100)):
         G = synth.make_gradients(P, d, 1.0, 4242, device=dev)
-        Gv = G[:, :d]
-        Z = B.encode(code, s, Gv)
-        R = Z.clone() if Z.is_contiguous() else Z.contiguous()
-        R = torch.nn.functional.pad(R, (0, (-R.shape[1]) % 4))          # rows 16-byte aligned
+        A = o.assign_repetition(P, s) if code == B.CODE_REPETITION else o.assign_cyclic(P, s)
+        Z = B.encode(A, code, G, d)
+        Zo = o.encode_repetition(G[:, :d].cpu().numpy(), s) if code == B.CODE_REPETITION else \
+            o.encode_cyclic(G[:, :d].cpu().numpy(), s)
+        for j in range(P):
+            assert_message_close(Z[j].cpu().numpy(), Zo[j], 2 * (2 * s + 1), j)
+        R = torch.nn.functional.pad(Z.contiguous(), (0, (-Z.shape[1]) % 4))          # rows 16-byte aligned
         mlen = Z.shape[1]
         R[3, :mlen] = -100.0 * R[3, :mlen]
-        ref = Gv.double().sum(0).cpu().numpy()
+        ref = G[:, :d].double().sum(0).cpu().numpy()
         for _ in range(2):                                                 # second call reuses the plan
             if code == B.CODE_REPETITION:
                 u, mask, status = B.decode_repetition(R[:, :mlen], P, s)
             else:
-                u, mask, status = B.decode_cyclic(R[:, :mlen], P, s, d, seed=5)
+                u, mask, status = B.decode_cyclic(R[:, :mlen], P, s, d)
             assert status == B.OK and list(np.flatnonzero(mask)) == [3]
             assert u.shape == (d,) and rel_l2(u.cpu().numpy(), ref) <= 1e-5
-    assert len(B._PLANS) >= 3
+        # a matrix that is not the code's allocation is refused
+        bad = A.copy()
+        bad[0, 0], bad[0, (2 * s + 1) % P] = 0, 1
+        with pytest.raises(B.DracoError) as e:
+            B.encode(bad, code, G, d)
+        assert e.value.status == B.EINVAL
+    # B > P through the same call: 4 per-sample rows per unit gradient
+    P, s, d, m = 9, 1, 1030, 4
+    S = synth.make_gradients(P * m, d, 1.0, 77, device=dev)
+    Z = B.encode(o.assign_cyclic(P, s), B.CODE_CYCLIC, S, d)
+    units = S[:, :d].double().reshape(P, m, d).sum(1).cpu().numpy()
+    Zo = o.encode_cyclic(units, s)
+    for j in range(P):
+        assert_message_close(Z[j].cpu().numpy(), Zo[j], 2, j)
+    B.lib().draco_cache_clear()
+
+
+def test_every_generated_decode_draws_another_projection_vector():
+    """f_dev = NULL: a plan's decodes use seed_0 = base, then other seeds; the seed a decode
+    used is reported, and the oracle decoding with ITS generator on that seed agrees."""
+    w = wl("cyc", 15, 2, 10_007, ("offset", "noise"), "any", 1.0)
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        R_host = c.R[:, :c.mlen].cpu().numpy()
+        c.plan.set_projection_seed(41)
+        seeds = []
+        for k in range(3):
+            c.u.fill_(float("nan"))
+            mask, status = c.plan.decode_cyclic(c.R, None, c.u)
+            torch.cuda.synchronize()
+            seeds.append(c.plan.last_projection_seed())
+            uo, mo, so = o.decode_cyclic(R_host, o.projection_vector(c.mlen // 2, seeds[-1]), w.s, w.d)
+            assert status == so == B.OK and np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
+            assert_sum_close(c.u[:w.d].cpu().numpy(), uo, TOL_SUM["cyc"], k)
+        assert seeds[0] == 41 and len(set(seeds)) == 3
+        c.plan.set_projection_seed(41)                     # the same base replays the same sequence
+        c.plan.decode_cyclic(c.R, None, c.u)
+        assert c.plan.last_projection_seed() == 41
+        c.plan.decode_cyclic_hostphi(c.R, None, c.u)
+        assert c.plan.last_projection_seed() == seeds[1]
+        other = B.Plan(B.CODE_CYCLIC, 15, 2, 10_007)      # two plans start from different bases
+        other2 = B.Plan(B.CODE_CYCLIC, 15, 2, 10_007)
+        u2 = torch.zeros_like(c.u)
+        other.decode_cyclic(c.R, None, u2)
+        other2.decode_cyclic(c.R, None, u2)
+        assert other.last_projection_seed() != other2.last_projection_seed()
+        other.close()
+        other2.close()
+    finally:
+        c.close()
+
+
+# ------------------------------------------------ the parameter server's update -----
+@pytest.mark.parametrize("d", [1, 3, 4, 1023, 1024, 1025, 1_000_003])
+def test_apply_update_against_the_oracle(d):
+    """params <- params - (lr/B) * sum: one fused multiply-add per parameter in fp32 against
+    the oracle's fp64 step; padding beyond d untouched."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(d)
+    n = synth.padded_len(d) + 8
+    w0 = torch.randn(n, generator=g, device=dev)
+    u = torch.randn(n, generator=g, device=dev) * 30
+    lr, Bsz = 0.1, 180
+    w = w0.clone()
+    B.draco_apply_update(w, u, d, lr / Bsz)
+    torch.cuda.synchronize()
+    want = o.sgd_update(w0[:d].cpu().numpy(), u[:d].cpu().numpy(), np.float32(lr / Bsz), 1)
+    got = w[:d].cpu().numpy().astype(np.float64)
+    # one rounding of the fused result: half an ulp of the result
+    assert np.all(np.abs(got - want) <= 2.0 ** -24 * (1 + 1e-6) * np.abs(want) + 1e-30)
+    assert torch.equal(w[d:], w0[d:])
+    B.draco_apply_update(w, u, d, 0.0)
+    assert torch.equal(w[:d].cpu(), torch.from_numpy(got.astype(np.float32)))
+
+
+def test_decode_then_update_is_the_clean_sgd_step():
+    """Sec. 2's update fed by D^Rep: with two liars the model after the step is the one
+    plain mini-batch SGD reaches on the honest gradients."""
+    w = wl("rep", 15, 2, 50_003, ("signflip", "noise"), "distinct_groups")
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        mask, status = c.decode()
+        assert status == B.OK and np.array_equal(mask, c.expected_mask())
+        params = torch.randn(c.u.numel(), device=c.device)
+        p0 = params.clone()
+        lr = 0.05
+        B.draco_apply_update(params, c.u, w.d, lr / w.P)
+        torch.cuda.synchronize()
+        want = o.sgd_update(p0[:w.d].cpu().numpy(), c.G[:, :w.d].double().sum(0).cpu().numpy(), lr, w.P)
+        assert max_abs_err(params[:w.d].cpu().numpy(), want) <= 1e-6 * float(np.max(np.abs(want)))
+    finally:
+        c.close()
 
 
 def test_alignment_and_argument_errors():

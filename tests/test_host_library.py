@@ -17,12 +17,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "draco.h")).read()
-    declared = set(re.findall(r"\b(draco_[a-z_]+)\s*\(", header))
-    assert declared == set(B.EXPORTS)
     L = B.lib()
-    for name in declared:
-        assert hasattr(L, name), name
+    for header_name, exports in (("draco.h", B.EXPORTS), ("draco_bench.h", B.BENCH_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", header_name)).read()
+        declared = set(re.findall(r"\b(draco_[a-z_]+)\s*\(", header))
+        assert declared == set(exports), header_name
+        for name in declared:
+            assert hasattr(L, name), name
 
 
 @pytest.mark.parametrize("code,P,s,d", [
