@@ -153,6 +153,12 @@ int draco_encode_samples(draco_plan* plan, const float* samples_dev, int64_t B, 
 int draco_encode_wide(draco_plan* plan, const float* grads_dev, int64_t ld_g,
                       float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m, void* stream);
 
+/* draco_encode_samples on the wide wire (B a multiple of P; B = P is
+ * draco_encode_wide).  DRACO_EINVAL for the repetition code or the unpacked wire. */
+int draco_encode_samples_wide(draco_plan* plan, const float* samples_dev, int64_t B, int64_t ld_g,
+                              float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m,
+                              void* stream);
+
 /* One node, as a real compute node would run it: node_grads_dev holds ONLY
  * that node's r = 2s+1 assigned gradients, [r][ld_g], in assignment order
  * (repetition: ascending k within the group; cyclic: k = node, node+1, ...,

@@ -46,7 +46,7 @@ EXPORTS = [
     "draco_plan_set_projection_seed", "draco_projection_vector", "draco_plan_set_wire",
     "draco_cyclic_locate_tol", "draco_decode_repetition_static",
     "draco_plan_last_projection_seed", "draco_encode_oneshot", "draco_decode_repetition_oneshot",
-    "draco_decode_cyclic_oneshot", "draco_cache_clear", "draco_apply_update",
+    "draco_decode_cyclic_oneshot", "draco_cache_clear", "draco_apply_update", "draco_encode_samples_wide",
 ]
 # the measuring instruments of include/draco_bench.h
 BENCH_EXPORTS = ["draco_copy_probe", "draco_plan_set_timing", "draco_plan_kernel_time", "draco_plan_kernel_times"]
@@ -132,6 +132,8 @@ def lib() -> ctypes.CDLL:
     L.draco_decode_cyclic_async.restype = i32
     L.draco_encode_samples.argtypes = [vp, vp, i64, i64, vp, i64, vp]
     L.draco_encode_samples.restype = i32
+    L.draco_encode_samples_wide.argtypes = [vp, vp, i64, i64, vp, vp, i64, vp]
+    L.draco_encode_samples_wide.restype = i32
     L.draco_encode_wide.argtypes = [vp, vp, i64, vp, vp, i64, vp]
     L.draco_encode_wide.restype = i32
     L.draco_decode_cyclic_wide.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
@@ -328,6 +330,11 @@ class Plan:
         """samples: [B][ld] with B a multiple of P (B/P per-sample rows per unit gradient)."""
         _check(lib().draco_encode_samples(self._h, samples.data_ptr(), samples.shape[0], samples.stride(0),
                                           messages.data_ptr(), messages.stride(0), _stream_ptr(stream)))
+
+    def encode_samples_wide(self, samples, hi, lo, stream=None) -> None:
+        assert hi.stride(0) == lo.stride(0)
+        _check(lib().draco_encode_samples_wide(self._h, samples.data_ptr(), samples.shape[0], samples.stride(0),
+                                               hi.data_ptr(), lo.data_ptr(), hi.stride(0), _stream_ptr(stream)))
 
     def encode_wide(self, grads, hi, lo, stream=None) -> None:
         assert hi.stride(0) == lo.stride(0)

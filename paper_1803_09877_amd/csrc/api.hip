@@ -322,16 +322,23 @@ int draco_encode_wide(draco_plan* p, const float* grads_dev, int64_t ld_g, float
     return encode_impl(p, grads_dev, ld_g, messages_hi_dev, messages_lo_dev, true, ld_m, stream);
 }
 
-int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g, float* messages_dev,
-                         int64_t ld_m, void* stream) {
+namespace {
+
+int encode_samples_impl(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g, float* messages_dev,
+                        float* lo_dev, bool wide, int64_t ld_m, void* stream) {
     if (p == nullptr || B < p->P || B % p->P != 0 || B / p->P > (1 << 20)) return DRACO_EINVAL;
     if (unpacked(p) && B != p->P) return DRACO_EINVAL;
+    if (wide && (p->code != DRACO_CODE_CYCLIC || unpacked(p))) return DRACO_EINVAL;
     const int m = (int)(B / p->P);
-    if (m == 1) return encode_impl(p, samples_dev, ld_g, messages_dev, nullptr, false, ld_m, stream);
+    if (m == 1) return encode_impl(p, samples_dev, ld_g, messages_dev, lo_dev, wide, ld_m, stream);
     int rc = check_slab(samples_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
     rc = check_slab(messages_dev, ld_m, message_len(p));
     if (rc != DRACO_OK) return rc;
+    if (wide) {
+        rc = check_slab(lo_dev, ld_m, message_len(p));
+        if (rc != DRACO_OK) return rc;
+    }
     rc = prepare(p);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -339,8 +346,21 @@ int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_samples(samples_dev, ld_g, m, messages_dev, ld_m, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
+        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, wide ? lo_dev : nullptr, ld_m, p->coef_dev,
+                                          p->P, p->s, p->d, st));
     return DRACO_OK;
+}
+
+}  // namespace
+
+int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g, float* messages_dev,
+                         int64_t ld_m, void* stream) {
+    return encode_samples_impl(p, samples_dev, B, ld_g, messages_dev, nullptr, false, ld_m, stream);
+}
+
+int draco_encode_samples_wide(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g,
+                              float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m, void* stream) {
+    return encode_samples_impl(p, samples_dev, B, ld_g, messages_hi_dev, messages_lo_dev, true, ld_m, stream);
 }
 
 int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,

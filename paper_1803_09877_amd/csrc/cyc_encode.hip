@@ -200,20 +200,20 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, const double2* coef,
-                                     int P, int s, int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int64_t ldm,
+                                     const double2* coef, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
     const int r = 2 * s + 1;
 #define DRACO_CASE(S) \
-    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, ldm, coef, P, d);
+    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   (float*)nullptr, coef + (int64_t)j * r, j, P, r, P, m, d);
+                                   Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, m, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();

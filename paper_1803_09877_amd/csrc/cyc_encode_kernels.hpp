@@ -215,9 +215,9 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_kernel(const float* __
 // k*m+m-1 of the sample slab): the same sliding window, but a window entry is the fp64
 // sum of m rows, formed as the rows arrive; the first 2s unit sums are parked in LDS in
 // fp64 for the wrap-around.  Units are fetched one round ahead.
-template <int S, bool FULL>
+template <int S, bool FULL, bool WIDE>
 __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ G, int64_t ldg, int m,
-                                                      float* __restrict__ Z, int64_t ldm,
+                                                      float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
                                                       const double2* __restrict__ coef, int P, int64_t d,
                                                       double4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
@@ -280,8 +280,13 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
                     cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
                     cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
                 }
-                stx<FULL>(Z + (int64_t)n * ldm + c0, make_float4((float)are0, (float)aim0, (float)are1, (float)aim1),
-                          nout);
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if constexpr (WIDE) {
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
             }
         }
     };
@@ -303,14 +308,14 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
     }
 }
 
-template <int S>
+template <int S, bool WIDE>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* __restrict__ G, int64_t ldg, int m,
-                                                                  float* __restrict__ Z, int64_t ldm,
-                                                                  const double2* __restrict__ coef, int P,
-                                                                  int64_t d) {
+                                                                  float* __restrict__ Z, float* __restrict__ Zlo,
+                                                                  int64_t ldm, const double2* __restrict__ coef,
+                                                                  int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
-    if (block_is_full(d)) encode_cyc_multi_body<S, true>(G, ldg, m, Z, ldm, coef, P, d, head_sums);
-    else encode_cyc_multi_body<S, false>(G, ldg, m, Z, ldm, coef, P, d, head_sums);
+    if (block_is_full(d)) encode_cyc_multi_body<S, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    else encode_cyc_multi_body<S, false, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 
 
@@ -326,6 +331,6 @@ hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stre
 // Same for the B > P form (m per-sample rows per unit gradient).
 template <int S>
 hipError_t launch_encode_cyc_multi_s(dim3 grid, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
-                                     int64_t ldm, const double2* coef, int P, int64_t d);
+                                     float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
 
 }  // namespace draco

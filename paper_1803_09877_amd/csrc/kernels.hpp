@@ -38,7 +38,7 @@ hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint6
 // B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,
                                      int s, int64_t d, hipStream_t stream);
-hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm,
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int64_t ldm,
                                      const double2* coef, int P, int s, int64_t d, hipStream_t stream);
 
 // ---- cyclic code ----

@@ -13,7 +13,7 @@ from . import synth
 class Case:
     """Slabs of one workload resident in HBM.
 
-    G  [P][ld_g]  per-sample (unit) gradients
+    G  [B][ld_g]  per-sample gradients, B = m*P rows (m = 1: one unit gradient per row)
     Z  [P][ld_m]  messages as the encoder wrote them
     R  [P][ld_m]  messages as received: Z with the adversaries' edits
     u  [d_pad]    decoded sum
@@ -35,7 +35,7 @@ class Case:
         self.mlen = self.plan.message_len
         self.ld_g = synth.padded_len(w.d)
         self.ld_m = synth.padded_len(self.mlen)
-        self.G = synth.make_gradients(w.P, w.d, w.sigma, w.seed, device=self.device, ld=self.ld_g)
+        self.G = synth.make_gradients(w.P * w.m, w.d, w.sigma, w.seed, device=self.device, ld=self.ld_g)
         self.Z = torch.zeros((w.P, self.ld_m), dtype=torch.float32, device=self.device)
         self.R = None
         self.Zlo = torch.zeros_like(self.Z) if wide else None
@@ -48,7 +48,12 @@ class Case:
         self.plan.prepare()
 
     def encode(self, stream=None) -> None:
-        if self.wide:
+        if self.w.m > 1:
+            if self.wide:
+                self.plan.encode_samples_wide(self.G, self.Z, self.Zlo, stream)
+            else:
+                self.plan.encode_samples(self.G, self.Z, stream)
+        elif self.wide:
             self.plan.encode_wide(self.G, self.Z, self.Zlo, stream)
         else:
             self.plan.encode(self.G, self.Z, stream)

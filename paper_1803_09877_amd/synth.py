@@ -108,6 +108,7 @@ class Workload:
     placement: str       # how the adversarial nodes are drawn
     decode: bool = True
     seed: int = field(default=0)
+    m: int = 1           # per-sample gradients per unit gradient: the slab holds B = m*P rows
 
     @property
     def r(self) -> int:
@@ -141,7 +142,9 @@ def _wl(i, **kw) -> Workload:
     return Workload(seed=SEED_BASE + i, **kw)
 
 
-# The five configurations the benchmark contract names, in its order.
+# The five configurations the benchmark contract names, in its order, then one shaped like
+# the paper's own timing runs (Sec. 4, end-to-end tables: 45 compute nodes, batch B = 180,
+# s = 5) at the largest gradient length of the five.
 WORKLOADS = [
     _wl(0, name="rep_P15_s1_d10k", code="rep", P=15, s=1, d=10_000, sigma=1.0,
         attacks=("noise",), placement="any"),
@@ -153,6 +156,8 @@ WORKLOADS = [
         attacks=(), placement="any", decode=False),
     _wl(4, name="cyc_P45_s3_d25.6M", code="cyc", P=45, s=3, d=25_600_000, sigma=1e-2,
         attacks=("noise", "signflip", "noise"), placement="adjacent_pair"),
+    _wl(5, name="cyc_P45_s5_B180_d25.6M", code="cyc", P=45, s=5, d=25_600_000, sigma=1e-2,
+        attacks=("signflip", "constant", "signflip", "constant", "signflip"), placement="any", m=4),
 ]
 
 
@@ -160,4 +165,4 @@ def scaled(w: Workload, d: int, name: str | None = None) -> Workload:
     """Same recipe at another gradient length (oracle-sized parity cases)."""
     return Workload(name=name or f"{w.name}@d={d}", code=w.code, P=w.P, s=w.s, d=d,
                     sigma=w.sigma, attacks=w.attacks, placement=w.placement,
-                    decode=w.decode, seed=w.seed)
+                    decode=w.decode, seed=w.seed, m=w.m)

@@ -35,8 +35,106 @@ def windows(d, code):
     return [(0, 4096), (mid, mid + (3001 if code == "rep" else 3002)), (max(0, (d - 2500) // 2 * 2), d)]
 
 
+CHUNK = 1 << 20          # coordinates per oracle call in the whole-slab checks (even: complex pairs stay whole)
+
+
+class RowErrors:
+    """Accumulates, per row, the squared error and squared reference over chunks, and checks each
+    chunk element by element against a bound relative to the chunk's largest reference entry."""
+
+    def __init__(self, rows):
+        self.num = np.zeros(rows)
+        self.den = np.zeros(rows)
+
+    def add(self, got, ref, elem_rel, what):
+        got = np.asarray(got, dtype=np.float64)
+        ref = np.asarray(ref, dtype=np.float64)
+        diff = got - ref
+        self.num += (diff * diff).sum(axis=-1)
+        self.den += (ref * ref).sum(axis=-1)
+        bound = elem_rel * np.max(np.abs(ref), axis=-1, initial=0.0)
+        worst = np.max(np.abs(diff), axis=-1, initial=0.0)
+        assert np.all(worst <= bound), (what, float(np.max(worst - bound)))
+
+    def rel_l2(self):
+        return np.sqrt(self.num / np.maximum(self.den, 1e-300))
+
+
+def whole_slab_check(c, wide=False):
+    """Oracle over EVERY coordinate, chunk by chunk: encoder rows, locator (the projection is
+    accumulated over the whole received slab), and the decoded sum."""
+    w = c.w
+    P, s, d = w.P, w.s, w.d
+    mask_gpu, status = c.last_decode if w.decode else (None, 0)
+    enc = RowErrors(P)
+    msg_ulps = (2 * w.r if w.code == "rep" else 2) * 2.0 ** -24
+    gamma = np.zeros(P, dtype=np.complex128)
+    f = c.f.cpu().numpy() if w.code == "cyc" else None
+    tau = o.TAU_H_WIDE if wide else o.TAU_H
+    dec = RowErrors(1)
+    mask_or = np.zeros(P, dtype=bool)
+
+    def received(a, b):
+        R = c.R[:, a:b].cpu().numpy()
+        return R.astype(np.float64) + c.Rlo[:, a:b].cpu().numpy() if wide else R
+
+    for a in range(0, d, CHUNK):
+        b = min(d, a + CHUNK)
+        G = c.G[:, a:b].cpu().numpy()
+        if w.code == "rep":
+            Zo = o.encode_repetition(G, s)
+            enc.add(c.Z[:, a:b].cpu().numpy(), Zo, msg_ulps, ("encode", a))
+        else:
+            Zo = o.encode_cyclic(G, s)
+            mb = a + Zo.shape[1]
+            if wide:       # hi + lo carries the fp64 message to 48 bits; the two sides' fp64 W and sums differ by ~1e-14
+                Zw = c.Z[:, a:mb].double().cpu().numpy() + c.Zlo[:, a:mb].double().cpu().numpy()
+                enc.add(Zw, Zo, 2.0 ** -43, ("encode", a))
+            else:
+                enc.add(c.Z[:, a:mb].cpu().numpy(), Zo, msg_ulps, ("encode", a))
+        if not w.decode:
+            continue
+        if w.code == "rep":
+            uo, mo, so = o.decode_repetition(received(a, b), s)
+            assert so == 0
+            mask_or |= mo
+            dec.add(c.u[a:b].cpu().numpy()[None], uo[None], 1e-5, ("vote", a))
+        else:
+            mb = min(c.mlen, (b + 1) // 2 * 2)
+            gamma += o.project(o.wire_to_complex(received(a, mb)), f[a // 2:mb // 2])
+    assert np.all(enc.rel_l2() <= (1e-12 if wide else 1e-6)), enc.rel_l2().max()
+    if not w.decode:
+        return
+    if w.code == "rep":
+        assert np.array_equal(mask_or, mask_gpu)
+        assert dec.rel_l2()[0] <= 1e-5
+        return
+    mo, _, so = o.phi_from_projection(gamma, s, tau)
+    assert so == 0 == status and np.array_equal(mo, mask_gpu)
+    bo = o.solve_b(P, s, [j for j in range(P) if not mo[j]], "min_norm")
+    honest = [j for j in range(P) if not mo[j]]
+    for a in range(0, d, CHUNK):
+        b = min(d, a + CHUNK)
+        mb = min(c.mlen, (b + 1) // 2 * 2)
+        Rc = o.wire_to_complex(received(a, mb))
+        uh = np.zeros(Rc.shape[1], dtype=np.complex128)
+        for j in honest:
+            uh += bo[j] * Rc[j]
+        dec.add(c.u[a:b].cpu().numpy()[None], o.unpack_complex(uh, b - a)[None], 1e-6 if wide else 1e-4, ("recombine", a))
+    assert dec.rel_l2()[0] <= (1e-6 if wide else 1e-4), dec.rel_l2()
+
+
+def true_sum_error(c):
+    """Definition 2: the decoded sum against the adversary-free gradient sum (fp64 on the GPU)."""
+    ref = c.G[:, :c.w.d].double().sum(0)
+    return float((c.u[:c.w.d].double() - ref).norm() / ref.norm())
+
+
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
 def test_full_size_workload(idx):
+    """Benchmark configurations 1-4 on the one-word wire: three windows as a fast pre-check, then
+    the oracle over every coordinate of Z and u (masks bit-exact, sums within tolerance of the
+    oracle decoding the same received messages, element-wise bounds on every chunk)."""
     w = synth.WORKLOADS[idx]
     print(f"full-size {w.name}: P={w.P} s={w.s} d={w.d} seed={w.seed}", flush=True)
     c = Case(w)
@@ -61,74 +159,68 @@ def test_full_size_workload(idx):
                 if j % r:
                     assert torch.equal(Zi[j], Zi[j - j % r]), j
         assert torch.isfinite(c.Z[:, :c.mlen]).all()
-        if not w.decode:
-            return
-        # ---- decoder -----------------------------------------------------------
-        c.receive()
-        c.u.fill_(float("nan"))
-        mask, status = c.decode()
-        torch.cuda.synchronize()
-        assert status == 0
-        assert np.array_equal(mask, c.expected_mask())
-        assert torch.isfinite(c.u[:w.d]).all()
-        if c.u.numel() > w.d:
-            assert torch.isnan(c.u[w.d:]).all()
-        if w.code == "rep":
-            for a, b in windows(w.d, w.code):
-                R = c.R[:, a:b].cpu().numpy()
-                uo, mo, so = o.decode_repetition(R, w.s)
-                assert so == 0 and np.array_equal(mo, mask)       # these attacks touch every coordinate
-                assert rel_l2(c.u[a:b].cpu().numpy(), uo) <= 1e-5
-        else:
-            h = (w.d + 1) // 2
-            f = c.f.cpu().numpy()
-            gamma = np.zeros(w.P, dtype=np.complex128)
-            step = 1 << 20
-            for a in range(0, h, step):                           # oracle's projection over the whole slab
-                b = min(h, a + step)
-                Rc = o.wire_to_complex(c.R[:, 2 * a:2 * b].cpu().numpy())
-                gamma += o.project(Rc, f[a:b])
-            mo, _, so = o.phi_from_projection(gamma, w.s)
-            assert so == 0 and np.array_equal(mo, mask)
-            bo = o.solve_b(w.P, w.s, [j for j in range(w.P) if not mo[j]], "min_norm")
-            for a, b in windows(w.d, w.code):
-                mb = min(c.mlen, (b + 1) // 2 * 2)
-                Rc = o.wire_to_complex(c.R[:, a:mb].cpu().numpy())
-                uh = np.zeros(Rc.shape[1], dtype=np.complex128)
-                for j in range(w.P):
-                    if not mo[j]:
-                        uh += bo[j] * Rc[j]
-                uo = o.unpack_complex(uh, b - a)
-                assert rel_l2(c.u[a:b].cpu().numpy(), uo) <= 1e-4
-            # Definition 2 end to end (measured, fp32 wire): report, and bound loosely
-            ref = c.G[:, :w.d].double().sum(0)
-            err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
+        c.last_decode = None
+        if w.decode:
+            c.receive()
+            c.u.fill_(float("nan"))
+            mask, status = c.decode()
+            torch.cuda.synchronize()
+            c.last_decode = (mask, status)
+            assert status == 0
+            assert np.array_equal(mask, c.expected_mask())
+            assert torch.isfinite(c.u[:w.d]).all()
+            if c.u.numel() > w.d:
+                assert torch.isnan(c.u[w.d:]).all()
+        whole_slab_check(c)
+        if w.decode:
+            err = true_sum_error(c)
             print(f"   end-to-end rel-L2 vs true sum: {err:.3e}", flush=True)
-            assert err <= (1e-5 if w.P == 15 else 1e-3)
+            if w.code == "rep":
+                assert err <= 1e-5                        # Definition 2, Theorem 2
+            elif w.P == 15:
+                assert err <= 1e-4                        # Definition 2 within the cyclic bar
+            # P = 45 on one fp32 word: see test_one_word_wire_at_p45_misses_the_bar_end_to_end
+    finally:
+        c.close()
+
+
+@pytest.mark.xfail(strict=True, reason="one fp32 word per message float cannot carry the cyclic code at P = 45 "
+                   "to 1e-4 end to end: |W| reaches 2.6e4 and the rounding of z is amplified to ~3e-4; "
+                   "the two-word wire is the path that meets the bar there")
+def test_one_word_wire_at_p45_misses_the_bar_end_to_end():
+    """Recorded, not hidden: the one-word wire's end-to-end error at (45, 3, 25.6 M) is out of
+    tolerance (it is in tolerance stage by stage against the oracle on the same messages)."""
+    w = synth.WORKLOADS[4]
+    c = Case(w)
+    try:
+        c.encode()
+        c.receive()
+        mask, status = c.decode()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        err = true_sum_error(c)
+        print(f"   one-word wire, end-to-end rel-L2 vs true sum: {err:.3e}", flush=True)
+        assert err <= 1e-4
     finally:
         c.close()
 
 
 def test_full_size_cyclic_wide_wire_end_to_end():
-    """Config 4 (P=45, s=3, d=25.6M) on the two-word wire: mask exact and the
-    decoded sum within 1e-6 of the TRUE gradient sum (the one-word wire's floor
-    is 3e-4 here)."""
+    """Configuration 4 (P=45, s=3, d=25.6M) on the two-word wire, the path the benchmark's
+    headline runs: mask exact, every coordinate of hi+lo and of u against the oracle, and the
+    decoded sum within 1e-6 of the TRUE gradient sum (the one-word wire's floor is 3e-4)."""
     w = synth.WORKLOADS[4]
     print(f"full-size wide {w.name}", flush=True)
     c = Case(w, wide=True)
     try:
         c.encode()
         c.receive()
+        c.u.fill_(float("nan"))
         mask, status = c.decode()
         torch.cuda.synchronize()
         assert status == 0 and np.array_equal(mask, c.expected_mask())
-        for a, b in windows(w.d, w.code):
-            Zo = o.encode_cyclic(c.G[:, a:b].cpu().numpy(), w.s)
-            Zw = (c.Z[:, a:a + Zo.shape[1]].double() + c.Zlo[:, a:a + Zo.shape[1]].double()).cpu().numpy()
-            for j in range(w.P):
-                assert rel_l2(Zw[j], Zo[j]) <= 1e-12
-        ref = c.G[:, :w.d].double().sum(0)
-        err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
+        c.last_decode = (mask, status)
+        whole_slab_check(c, wide=True)
+        err = true_sum_error(c)
         print(f"   end-to-end rel-L2 vs true sum (wide wire): {err:.3e}", flush=True)
         assert err <= 1e-6
         # the messages as sent: the projection's own rounding over 12.8 M terms must stay below
@@ -137,8 +229,34 @@ def test_full_size_cyclic_wide_wire_end_to_end():
             mask, status = c.plan.decode_cyclic_wide(c.Z, c.Zlo, c.f, c.u)
             torch.cuda.synchronize()
             assert status == 0 and not mask.any()
-            err = float((c.u[:w.d].double() - ref).norm() / ref.norm())
-            assert err <= 1e-6
+            assert true_sum_error(c) <= 1e-6
+    finally:
+        c.close()
+
+
+def test_full_size_paper_shaped_workload():
+    """P = 45, s = 5, B = 180 (the paper's timing setup) at d = 25.6 M on the two-word wire: the
+    per-sample rows are summed inside the encoder; mask exact, Definition 2 end to end."""
+    w = synth.WORKLOADS[5]
+    print(f"full-size paper-shaped {w.name}", flush=True)
+    c = Case(w, wide=True)
+    try:
+        c.encode()
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == 0 and np.array_equal(mask, c.expected_mask())
+        d, m = w.d, w.m
+        for a, b in windows(d, "cyc"):
+            units = c.G[:, a:b].double().reshape(w.P, m, b - a).sum(1).cpu().numpy()
+            Zo = o.encode_cyclic(units, w.s)
+            Zw = (c.Z[:, a:a + Zo.shape[1]].double() + c.Zlo[:, a:a + Zo.shape[1]].double()).cpu().numpy()
+            for j in range(w.P):
+                assert rel_l2(Zw[j], Zo[j]) <= 1e-12, (a, j)
+        err = true_sum_error(c)
+        print(f"   end-to-end rel-L2 vs true sum: {err:.3e}", flush=True)
+        assert err <= 1e-6
     finally:
         c.close()
 
