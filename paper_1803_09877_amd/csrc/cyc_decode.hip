@@ -187,7 +187,7 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
                                                    bool realout, int64_t d) {
     constexpr int UN = 8;
     const int nu = *nu_ptr;  // honest nodes; written by the locator (device) or copied in by the host path
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadRecombine>();
     if (!FULL && c0 >= d) return;
     const int64_t mlen = 2 * ((d + 1) / 2);
     const int nin = FULL ? 4 : clamp4(mlen - c0);
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
                                                                const int32_t* __restrict__ spec_state, int P,
                                                                float* __restrict__ u, int realout, int64_t d) {
     if (spec_state != nullptr && spec_state[1] != 0 && *nu == P) return;
-    if (block_is_full(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    if (block_is_full<kSpreadRecombine>(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
     else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
 }
 
@@ -290,7 +290,7 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
 hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
                                 const int32_t* nu, const int32_t* spec_state, int P, float* u, bool realout,
                                 int64_t d, hipStream_t stream) {
-    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadRecombine>(d)), block(kBlock);
     if (Rlo == nullptr) {
         allow_large_lds<cyc_recombine_kernel<false>>();
         hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,

@@ -13,7 +13,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
                                                                  float* __restrict__ z, float* __restrict__ zlo,
                                                                  const double2* __restrict__ cn, int node, int P,
                                                                  int r, int wrap_rows, int m, int64_t d) {
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (c0 >= mlen) return;
     const int nin = clamp4(d - c0);
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const floa
                                                                       float* __restrict__ z,
                                                                       const double2* __restrict__ cn, int node,
                                                                       int P, int r, int wrap_rows, int64_t d) {
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
     if (c0 >= d) return;
     const int nin = clamp4(d - c0);
     double re[4] = {0.0, 0.0, 0.0, 0.0}, im[4] = {0.0, 0.0, 0.0, 0.0};
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const floa
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm, const double2* coef, int P,
                              int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
-    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
 #define DRACO_CASE(S) \
@@ -183,7 +183,7 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
 
 hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef, int P,
                                   int s, int64_t d, hipStream_t stream) {
-    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeCyc>(d)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
 #define DRACO_CASE(S) \
@@ -203,7 +203,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
 hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int64_t ldm,
                                      const double2* coef, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
-    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
@@ -221,7 +221,7 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
 
 hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node, int P,
                                        int s, int64_t d, hipStream_t stream) {
-    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeCyc>(d)), block(kBlock);
     const int r = 2 * s + 1;
     hipLaunchKernelGGL(encode_cyc_real_node_kernel, grid, block, 0, stream, Gn, ldg, z, coef + (int64_t)node * r, node,
                        P, r, 0, d);
@@ -231,7 +231,7 @@ hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, c
 hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef, int node,
                                   int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
-    const dim3 grid(grid_for((mlen + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, coef + (int64_t)node * r, node,
                        P, r, 0, 1, d);

@@ -19,7 +19,7 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
                                                 const double2* __restrict__ coef, int P, int64_t d,
                                                 float4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (!FULL && c0 >= mlen) return;
     const int nin = FULL ? 4 : clamp4(d - c0);      // gradient floats that exist (the pad of an odd d reads as 0)
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
                                                             int64_t ldm, const double2* __restrict__ coef, int P,
                                                             int64_t d) {
     extern __shared__ float4 head[];  // [2S][kBlock]
-    if (block_is_full(d)) encode_cyc_body<S, NB, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_body<S, NB, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
     else encode_cyc_body<S, NB, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
 }
 
@@ -117,7 +117,7 @@ __device__ __forceinline__ void encode_cyc_real_body(const float* __restrict__ G
                                                      float4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     // the wavefront covers 256 consecutive real coordinates; mine are cA, cA+1, cA+128, cA+129
-    const int64_t cA = (int64_t)blockIdx.x * (kBlock * 4) + (threadIdx.x >> 6) * 256 + (threadIdx.x & 63) * 2;
+    const int64_t cA = lane_column<kSpreadEncodeCyc>() - (threadIdx.x & 63) * 2;
     const int64_t cB = cA + 128;
     if (!FULL && cA >= d) return;
     const int nA = FULL ? 2 : (d - cA >= 2 ? 2 : (int)(d - cA));
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_kernel(const float* __
                                                                  const double2* __restrict__ coef, int P,
                                                                  int64_t d) {
     extern __shared__ float4 head[];  // [2S][kBlock]
-    if (block_is_full(d)) encode_cyc_real_body<S, NB, true>(G, ldg, Z, ldm, coef, P, d, head);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_real_body<S, NB, true>(G, ldg, Z, ldm, coef, P, d, head);
     else encode_cyc_real_body<S, NB, false>(G, ldg, Z, ldm, coef, P, d, head);
 }
 
@@ -222,7 +222,7 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
                                                       double4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     constexpr int UN = 4;
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (!FULL && c0 >= mlen) return;
     const int nin = FULL ? 4 : clamp4(d - c0);
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* _
                                                                   int64_t ldm, const double2* __restrict__ coef,
                                                                   int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
-    if (block_is_full(d)) encode_cyc_multi_body<S, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_multi_body<S, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
     else encode_cyc_multi_body<S, false, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 

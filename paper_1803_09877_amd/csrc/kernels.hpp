@@ -17,6 +17,14 @@ constexpr int kMaxNodes = 256;        // DRACO_MAX_NODES
 constexpr int kMaskWords = 4;         // 64-bit words of node flags (kMaxNodes / 64)
 constexpr int kLocateMaxS = 16;       // largest s the on-device locator handles
 
+// Which kernel families spread a workgroup's wavefronts over a 128 KiB window of each row
+// (device_util.hpp, "workgroup footprint"); chosen per family by measurement.
+constexpr bool kSpreadEncodeCyc = true;
+constexpr bool kSpreadEncodeRep = true;
+constexpr bool kSpreadVote = true;
+constexpr bool kSpreadRecombine = true;
+constexpr bool kSpreadUpdate = true;
+
 // Complex numbers in device tables: (re, im) as double2.
 
 // ---- repetition code ----

@@ -21,7 +21,7 @@ namespace draco {
 template <int R, int GU, bool FULL>
 __device__ __forceinline__ void encode_rep_body(const float* __restrict__ G, int64_t ldg, float* __restrict__ Z,
                                                 int64_t ldm, int groups, int64_t d) {
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeRep>();
     if (!FULL && c0 >= d) return;
     const int n = FULL ? 4 : clamp4(d - c0);
     {
@@ -58,7 +58,7 @@ template <int R, int GU>
 __global__ __launch_bounds__(kBlock) void encode_rep_kernel(const float* __restrict__ G, int64_t ldg,
                                                             float* __restrict__ Z, int64_t ldm,
                                                             int groups, int64_t d) {
-    if (block_is_full(d)) encode_rep_body<R, GU, true>(G, ldg, Z, ldm, groups, d);
+    if (block_is_full<kSpreadEncodeRep>(d)) encode_rep_body<R, GU, true>(G, ldg, Z, ldm, groups, d);
     else encode_rep_body<R, GU, false>(G, ldg, Z, ldm, groups, d);
 }
 
@@ -70,7 +70,7 @@ __device__ __forceinline__ void encode_rep_generic_body(const float* __restrict_
                                                         float* __restrict__ Z, int64_t ldm, int groups, int rows,
                                                         int copies, int64_t d) {
     constexpr int UN = 8;
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadEncodeRep>();
     if (!FULL && c0 >= d) return;
     const int n = FULL ? 4 : clamp4(d - c0);
     {
@@ -106,7 +106,7 @@ __device__ __forceinline__ void encode_rep_generic_body(const float* __restrict_
 __global__ __launch_bounds__(kBlock) void encode_rep_generic_kernel(const float* __restrict__ G, int64_t ldg,
                                                                     float* __restrict__ Z, int64_t ldm,
                                                                     int groups, int rows, int copies, int64_t d) {
-    if (block_is_full(d)) encode_rep_generic_body<true>(G, ldg, Z, ldm, groups, rows, copies, d);
+    if (block_is_full<kSpreadEncodeRep>(d)) encode_rep_generic_body<true>(G, ldg, Z, ldm, groups, rows, copies, d);
     else encode_rep_generic_body<false>(G, ldg, Z, ldm, groups, rows, copies, d);
 }
 
@@ -219,7 +219,7 @@ __device__ __forceinline__ uint4 vote_group(const uint4 (&x)[R], int first_node,
 template <int R, int GU, bool FULL>
 __device__ __forceinline__ void decode_rep_body(const float* __restrict__ Rm, int64_t ldm, float* __restrict__ u,
                                                 WaveFlags& wflags, int groups, int64_t d) {
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadVote>();
     const bool active = FULL || c0 < d;
     const int n = FULL ? 4 : (active ? clamp4(d - c0) : 0);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kBlock) void decode_rep_kernel(const float* __restr
                                                             float* __restrict__ u, uint64_t* __restrict__ flags,
                                                             int groups, int64_t d) {
     WaveFlags wflags;
-    if (block_is_full(d)) decode_rep_body<R, GU, true>(Rm, ldm, u, wflags, groups, d);
+    if (block_is_full<kSpreadVote>(d)) decode_rep_body<R, GU, true>(Rm, ldm, u, wflags, groups, d);
     else decode_rep_body<R, GU, false>(Rm, ldm, u, wflags, groups, d);
     publish_flags(wflags, flags);
 }
@@ -271,7 +271,7 @@ __device__ __forceinline__ void decode_rep_stream_body(const float* __restrict__
                                                        float* __restrict__ u, WaveFlags& wflags, int groups,
                                                        int r, int64_t d) {
     constexpr int UN = 8;
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadVote>();
     const bool active = FULL || c0 < d;
     const int n = FULL ? 4 : (active ? clamp4(d - c0) : 0);
     auto fetch = [&](const float* p) -> uint4 {
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kBlock) void decode_rep_generic_kernel(const float*
                                                                     float* __restrict__ u, uint64_t* __restrict__ flags,
                                                                     int groups, int r, int64_t d) {
     WaveFlags wflags;
-    if (block_is_full(d)) decode_rep_stream_body<true>(Rm, ldm, u, wflags, groups, r, d);
+    if (block_is_full<kSpreadVote>(d)) decode_rep_stream_body<true>(Rm, ldm, u, wflags, groups, r, d);
     else decode_rep_stream_body<false>(Rm, ldm, u, wflags, groups, r, d);
     publish_flags(wflags, flags);
 }
@@ -368,7 +368,7 @@ __global__ void decode_rep_finish_kernel(uint64_t* __restrict__ flags, uint64_t*
 hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm, int P, int s, int64_t d,
                              hipStream_t stream) {
     const int r = 2 * s + 1, groups = P / r;
-    const unsigned tiles = grid_for((d + 3) / 4);
+    const unsigned tiles = grid_cols<kSpreadEncodeRep>(d);
     const dim3 block(kBlock);
     bool generic = false;
 #define DRACO_LAUNCH(R, GU, BPC)                                                                             \
@@ -390,7 +390,7 @@ hipError_t launch_encode_rep(const float* G, int64_t ldg, float* Z, int64_t ldm,
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P, int s, int64_t d,
                                      hipStream_t stream) {
     const int r = 2 * s + 1, groups = P / r;
-    const dim3 grid(grid_for((d + 3) / 4), (unsigned)groups), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeRep>(d), (unsigned)groups), block(kBlock);
     allow_large_lds<encode_rep_generic_kernel>();
     hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, throttle_lds(2, 0, 0), stream, G, ldg, Z, ldm, groups,
                        r * m, r, d);
@@ -398,7 +398,7 @@ hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* 
 }
 
 hipError_t launch_encode_rep_node(const float* Gn, int64_t ldg, float* z, int s, int64_t d, hipStream_t stream) {
-    const dim3 grid(grid_for((d + 3) / 4)), block(kBlock);
+    const dim3 grid(grid_cols<kSpreadEncodeRep>(d)), block(kBlock);
     hipLaunchKernelGGL(encode_rep_generic_kernel, grid, block, 0, stream, Gn, ldg, z, (int64_t)0, 1, 2 * s + 1, 1, d);
     return hipGetLastError();
 }
@@ -407,7 +407,7 @@ hipError_t launch_decode_rep_vote(const float* R, int64_t ldm, float* u, uint64_
                                   hipStream_t stream) {
     const int r = 2 * s + 1, groups = P / r;
     const dim3 block(kBlock);
-    const dim3 grid(grid_for((d + 3) / 4));
+    const dim3 grid(grid_cols<kSpreadVote>(d));
     bool generic = false;
 #define DRACO_LAUNCH(R_, GU, BPC)                                                                               \
     {                                                                                                           \

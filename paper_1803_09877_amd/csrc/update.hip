@@ -11,7 +11,7 @@ namespace draco {
 template <bool FULL>
 __device__ __forceinline__ void apply_update_body(float* __restrict__ w, const float* __restrict__ u, float scale,
                                                   int64_t d) {
-    const int64_t c0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int64_t c0 = lane_column<kSpreadUpdate>();
     if (!FULL && c0 >= d) return;
     const int n = FULL ? 4 : clamp4(d - c0);
     const float4 g = ldx<FULL>(u + c0, n);
@@ -30,12 +30,12 @@ __device__ __forceinline__ void apply_update_body(float* __restrict__ w, const f
 
 __global__ __launch_bounds__(kBlock) void apply_update_kernel(float* __restrict__ w, const float* __restrict__ u,
                                                               float scale, int64_t d) {
-    if (block_is_full(d)) apply_update_body<true>(w, u, scale, d);
+    if (block_is_full<kSpreadUpdate>(d)) apply_update_body<true>(w, u, scale, d);
     else apply_update_body<false>(w, u, scale, d);
 }
 
 hipError_t launch_apply_update(float* params, const float* sum, float scale, int64_t d, hipStream_t stream) {
-    hipLaunchKernelGGL(apply_update_kernel, dim3(grid_for((d + 3) / 4)), dim3(kBlock), 0, stream, params, sum, scale,
+    hipLaunchKernelGGL(apply_update_kernel, dim3(grid_cols<kSpreadUpdate>(d)), dim3(kBlock), 0, stream, params, sum, scale,
                        d);
     return hipGetLastError();
 }
