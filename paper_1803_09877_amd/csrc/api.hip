@@ -48,6 +48,7 @@ struct draco_plan {
     double2* gamma_dev = nullptr;    // P
     double2* b_dev = nullptr;        // P
     double2* b0_dev = nullptr;       // P: recombination vector when no node is flagged
+    double2* root_dev = nullptr;     // P: exp(2 pi i k / P)
     int32_t* spec_dev = nullptr;     // 2 words: speculate next / speculated now (see cyc_decode.hip)
     bool speculation = true;
     uint64_t f_seed = 0;             // base seed of the generated projection vector (f_dev == NULL)
@@ -147,6 +148,13 @@ int prepare(draco_plan* p) {
                 t0[2 * j + 1] = (double)b0[j].imag();
             }
             HIP_TRY(hipMemcpy(p->b0_dev, t0.data(), P * sizeof(double2), hipMemcpyHostToDevice));
+            for (int k = 0; k < P; ++k) {
+                const cplx_t w = root_of_unity(P, k);
+                t0[2 * k] = (double)w.real();
+                t0[2 * k + 1] = (double)w.imag();
+            }
+            HIP_TRY(hipMalloc(&p->root_dev, P * sizeof(double2)));
+            HIP_TRY(hipMemcpy(p->root_dev, t0.data(), P * sizeof(double2), hipMemcpyHostToDevice));
             const int32_t init[2] = {1, 0};  // optimistic: the first decode speculates
             HIP_TRY(hipMemcpy(p->spec_dev, init, sizeof(init), hipMemcpyHostToDevice));
         }
@@ -231,6 +239,7 @@ void draco_plan_destroy(draco_plan* p) {
         (void)hipFree(p->gamma_dev);
         (void)hipFree(p->b_dev);
         (void)hipFree(p->b0_dev);
+        (void)hipFree(p->root_dev);
         (void)hipFree(p->spec_dev);
         (void)hipFree(p->idx_dev);
         (void)hipFree(p->flags_dev);
@@ -467,7 +476,7 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     }
     {
         Timed timed(p, kLocateKind, st);
-        HIP_TRY(launch_cyc_locate(p->gamma_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev,
+        HIP_TRY(launch_cyc_locate(p->gamma_dev, p->root_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev,
                                   p->b_dev, p->idx_dev, p->idx_dev + P, spec, st));
     }
     {

@@ -76,10 +76,10 @@ hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, con
                               hipStream_t stream);
 // phi steps 2-4 and the recombination vector on the device (one wavefront, fp64; s <= kLocateMaxS):
 // gamma[P] -> mask words, status, and the honest nodes' (idx, b) compacted in ascending order with
-// their count in *nu_out.  tau: relative zero threshold for syndromes.
+// their count in *nu_out.  roots[k] = exp(2 pi i k / P), k < P.  tau: relative zero threshold for syndromes.
 // With no located node the coefficients are copied from b0 (bit-identical to the speculative pass);
 // spec_state[0] <- 1 if this decode was clean (the next call speculates), else 0.
-hipError_t launch_cyc_locate(const double2* gamma, int P, int s, double tau, const double2* b0,
+hipError_t launch_cyc_locate(const double2* gamma, const double2* roots, int P, int s, double tau, const double2* b0,
                              uint64_t* mask_out, int32_t* status_out, double2* b_out, int32_t* idx_out,
                              int32_t* nu_out, int32_t* spec_state, hipStream_t stream);
 // u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
