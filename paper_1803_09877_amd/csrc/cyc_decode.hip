@@ -177,15 +177,17 @@ __global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double
     if (threadIdx.x == 0) gamma[j] = sm[0];
 }
 
+constexpr int kRecombineRows = 6;      // message rows a lane has in flight (one word per float)
+constexpr int kRecombineRowsWide = 3;  // the same on the two-word wire (two loads per row)
+
 // u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
 // ascending node order, fp64 accumulation, one rounding to fp32.
-template <bool FULL, bool WIDE>
+template <bool FULL, bool WIDE, int UN>
 __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
                                                    int64_t ldm,
                                                    const double2* __restrict__ b, const int32_t* __restrict__ idx,
                                                    const int32_t* __restrict__ nu_ptr, float* __restrict__ u,
                                                    bool realout, int64_t d) {
-    constexpr int UN = 8;
     const int nu = *nu_ptr;  // honest nodes; written by the locator (device) or copied in by the host path
     const int64_t c0 = lane_column<kSpreadRecombine>();
     if (!FULL && c0 >= d) return;
@@ -227,7 +229,7 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
 
 // If the projection pass speculated (spec_state[1]) and every node turned out honest
 // (*nu == P), the output already holds the answer: nothing to do.
-template <bool WIDE>
+template <bool WIDE, int UN>
 __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm,
                                                                const float* __restrict__ Rlo, int64_t ldm,
                                                                const double2* __restrict__ b,
@@ -236,8 +238,8 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
                                                                const int32_t* __restrict__ spec_state, int P,
                                                                float* __restrict__ u, int realout, int64_t d) {
     if (spec_state != nullptr && spec_state[1] != 0 && *nu == P) return;
-    if (block_is_full<kSpreadRecombine>(d)) cyc_recombine_body<true, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
-    else cyc_recombine_body<false, WIDE>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    if (block_is_full<kSpreadRecombine>(d)) cyc_recombine_body<true, WIDE, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    else cyc_recombine_body<false, WIDE, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
 }
 
 // Plain copy of a [rows][row_len] slab (row stride ld): the fastest copy of a row-major
@@ -292,12 +294,12 @@ hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, c
                                 int64_t d, hipStream_t stream) {
     const dim3 grid(grid_cols<kSpreadRecombine>(d)), block(kBlock);
     if (Rlo == nullptr) {
-        allow_large_lds<cyc_recombine_kernel<false>>();
-        hipLaunchKernelGGL(cyc_recombine_kernel<false>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+        allow_large_lds<cyc_recombine_kernel<false, kRecombineRows>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<false, kRecombineRows>), grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
                            nu, spec_state, P, u, realout ? 1 : 0, d);
     } else {
-        allow_large_lds<cyc_recombine_kernel<true>>();
-        hipLaunchKernelGGL(cyc_recombine_kernel<true>, grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+        allow_large_lds<cyc_recombine_kernel<true, kRecombineRowsWide>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<true, kRecombineRowsWide>), grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
                            nu, spec_state, P, u, realout ? 1 : 0, d);
     }
     return hipGetLastError();

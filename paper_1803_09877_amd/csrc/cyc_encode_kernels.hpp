@@ -308,6 +308,101 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
     }
 }
 
+// The same when m is a multiple of D: the B = m P sample rows are consumed in one linear
+// walk with the next D rows always in flight (a ring of D raw rows whose slot is the row
+// index mod D, static because m is a multiple of D), so the loads of the next unit overlap
+// the sums of this one.  Same additions in the same order as above: identical bits.
+template <int S, int D, bool FULL, bool WIDE>
+__device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restrict__ G, int64_t ldg, int m,
+                                                           float* __restrict__ Z, float* __restrict__ Zlo,
+                                                           int64_t ldm, const double2* __restrict__ coef, int P,
+                                                           int64_t d, double4* head /* LDS [2S][kBlock] */) {
+    constexpr int R = 2 * S + 1;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (!FULL && c0 >= mlen) return;
+    const int nin = FULL ? 4 : clamp4(d - c0);
+    const int nout = FULL ? 4 : clamp4(mlen - c0);
+    const int64_t rows = (int64_t)P * m;
+
+    float4 ring[D];
+    int64_t next = 0;  // next sample row to fetch
+    const float* src = G + c0;
+#pragma unroll
+    for (int t = 0; t < D; ++t) {
+        ring[t] = ldx<FULL>(src + next * ldg, nin);
+        ++next;
+    }
+    auto unit_sum = [&]() -> double4 {  // the next unit gradient: its m rows, ascending, in fp64
+        double4 acc = make_double4(0.0, 0.0, 0.0, 0.0);
+        for (int t0 = 0; t0 < m; t0 += D) {
+#pragma unroll
+            for (int t = 0; t < D; ++t) {
+                const float4 x = ring[t];
+                if (next < rows) ring[t] = ldx<FULL>(src + next * ldg, nin);
+                ++next;
+                acc.x += (double)x.x;
+                acc.y += (double)x.y;
+                acc.z += (double)x.z;
+                acc.w += (double)x.w;
+            }
+        }
+        return acc;
+    };
+    double wre[R][2], wim[R][2];
+    auto put = [&](int slot, const double4& v) {
+        wre[slot][0] = v.x;
+        wim[slot][0] = v.y;
+        wre[slot][1] = v.z;
+        wim[slot][1] = v.w;
+    };
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        const double4 v = unit_sum();
+        head[k * kBlock + threadIdx.x] = v;
+        put(k, v);
+    }
+    for (int n0 = 0; n0 < P; n0 += R) {
+#pragma unroll
+        for (int uu = 0; uu < R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                const int kk = n + 2 * S;
+                const double4 v = kk < P ? unit_sum() : head[(kk - P) * kBlock + threadIdx.x];
+                put((uu + 2 * S) % R, v);
+                const double2* cn = coef + (int64_t)n * R;
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    const double cr = cn[t].x, ci = cn[t].y;
+                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
+                }
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if constexpr (WIDE) {
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
+            }
+        }
+    }
+}
+
+template <int S, int D, bool WIDE>
+__global__ __launch_bounds__(kBlock) void encode_cyc_multi_ring_kernel(const float* __restrict__ G, int64_t ldg, int m,
+                                                                       float* __restrict__ Z, float* __restrict__ Zlo,
+                                                                       int64_t ldm, const double2* __restrict__ coef,
+                                                                       int P, int64_t d) {
+    extern __shared__ double4 head_sums[];  // [2S][kBlock]
+    if (block_is_full<kSpreadEncodeCyc>(d))
+        encode_cyc_multi_ring_body<S, D, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    else
+        encode_cyc_multi_ring_body<S, D, false, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+}
+
 template <int S, bool WIDE>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                   float* __restrict__ Z, float* __restrict__ Zlo,
