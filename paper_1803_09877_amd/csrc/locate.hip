@@ -216,6 +216,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     const int ldq = 2 * kLocateMaxS;
     const double isq = 1.0 / sqrt((double)P);
     int status = 0;
+    int fitted = 0;  // columns of the syndrome fit left in (Q, Rr) by the locator: the located nodes, in ranking order
 
     // A message with NaN or Inf entries is no vector of R^d: its node is flagged outright and
     // its projection taken as 0, which leaves an ordinary error at a known node.
@@ -408,6 +409,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             }
             const int take = found ? found : s;
             if (!found) status = 2;
+            fitted = found;
             if (lane < take) sm.mask[sm.order[lane]] = 1;
             __syncthreads();
             int mine = 0;
@@ -437,25 +439,37 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     const int a = nv <= s ? nv : s;
     if (nv > s) status = 2;
     if (a > 0) {
-        for (int v = 0; v < a; ++v) {
-            const int node = sm.vlist[v];
-            if (lane < 2 * s) sm.Q[v * ldq + lane] = cscale(sm.root[mulmod(n + lane, node, P)], isq);
-            if (lane == 0) sm.rhs[v] = cscale(cconj(sm.root[mulmod(n - 1, node, P)]), -isq);
-            __syncthreads();
-            mgs_append(sm, 2 * s, v, lane);
+        // The columns needed here, (1/sqrt P) w^{(n+row) v} for the flagged nodes v, are the complex
+        // conjugates of the columns the locator fitted the syndromes with.  When the flagged nodes
+        // are exactly the located ones, that factorisation is reused (conjugate Q and R; the order
+        // of the columns does not change the minimum-norm solution); else it is built afresh.
+        const bool reuse = fitted == nv && fitted > 0;
+        if (!reuse) {
+            for (int v = 0; v < a; ++v) {
+                const int node = sm.vlist[v];
+                if (lane < 2 * s) sm.Q[v * ldq + lane] = cscale(sm.root[mulmod(n + lane, node, P)], isq);
+                __syncthreads();
+                mgs_append(sm, 2 * s, v, lane);
+            }
         }
         if (lane == 0) {  // R^H y = rhs, forward substitution
             for (int i = 0; i < a; ++i) {
-                double2 acc = sm.rhs[i];
-                for (int k = 0; k < i; ++k) acc = csub(acc, cmul(cconj(sm.Rr[i * ldq + k]), sm.y[k]));
-                const double rii = sm.Rr[i * ldq + i].x;
-                sm.y[i] = cscale(acc, 1.0 / rii);
+                const int node = reuse ? sm.order[i] : sm.vlist[i];
+                double2 acc = cscale(cconj(sm.root[mulmod(n - 1, node, P)]), -isq);
+                for (int k = 0; k < i; ++k) {
+                    const double2 rki = sm.Rr[i * ldq + k];   // R[k][i] of the factorisation in LDS
+                    acc = csub(acc, cmul(reuse ? rki : cconj(rki), sm.y[k]));
+                }
+                sm.y[i] = cscale(acc, 1.0 / sm.Rr[i * ldq + i].x);
             }
         }
         __syncthreads();
         if (lane < 2 * s) {
             double2 acc = make_double2(0.0, 0.0);
-            for (int v = 0; v < a; ++v) acc = cadd(acc, cmul(sm.Q[v * ldq + lane], sm.y[v]));
+            for (int v = 0; v < a; ++v) {
+                const double2 qv = sm.Q[v * ldq + lane];
+                acc = cadd(acc, cmul(reuse ? cconj(qv) : qv, sm.y[v]));
+            }
             sm.Bv[lane] = acc;
         }
         __syncthreads();
