@@ -4,8 +4,9 @@
 // is bound by HBM bandwidth: one lane owns 4 consecutive floats (one 16-byte load per
 // row), a wavefront therefore reads 1 KiB of each row per step, and the loop over the
 // rows runs inside the lane so each input byte is read from HBM exactly once.
-// Workgroups are 256 lanes (4 wavefronts).  There is no reuse between workgroups, so the
-// blockIdx -> tile map is the identity.
+// Workgroups are 256 lanes (4 wavefronts).  There is no reuse between workgroups; which
+// part of a row a workgroup takes is chosen for the memory system alone (see "workgroup
+// footprint" below).
 #pragma once
 
 #include "kernels.hpp"
