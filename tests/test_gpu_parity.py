@@ -640,6 +640,23 @@ def test_cyc_determinism():
         c.close()
 
 
+# ------------------------------------------- workgroup footprint boundaries ----
+@pytest.mark.parametrize("d", [255, 256, 257, 1023, 1025, 8191, 8192, 8193, 8449, 16385, 24577, 32767, 32768, 32769,
+                               32768 + 8192 + 3, 65535, 65536, 65537, 3 * 32768 - 1, 3 * 32768 + 2049])
+def test_lengths_around_the_footprint_windows(d):
+    """A workgroup's wavefronts sit 32 KiB apart inside 128 KiB windows of a row (and a lane of the
+    narrow-window cyclic encoder owns four pieces 8 KiB apart), so a row that ends near a piece, a
+    wavefront stride or a window boundary leaves workgroups with some wavefronts inside the row and
+    some outside: lengths one below, on and one above each boundary, for both codes, both packed
+    cyclic encoders (rounds of rows; four pieces per lane) and all three wires."""
+    run_and_check(wl("rep", 9, 1, d, ("noise",), "any"), check_true_sum=1e-6)
+    run_and_check(wl("rep", 25, 2, d, ("signflip",), "any"), check_true_sum=1e-6)
+    run_and_check(wl("cyc", 9, 1, d, ("noise",), "any"), check_true_sum=1e-5)
+    run_and_check(wl("cyc", 33, 2, d, ("noise", "signflip"), "any", 1e-2))      # four pieces per lane
+    run_wide(wl("cyc", 33, 3, d, ("noise", "offset", "signflip"), "any", 1e-2))
+    run_unpacked(wl("cyc", 9, 2, d, ("noise",), "any"))
+
+
 # ------------------------------------------------------ one-node encoder ----
 @pytest.mark.parametrize("code,P,s,d", [("rep", 15, 2, 3001), ("cyc", 15, 2, 3001), ("cyc", 45, 3, 2048), ("cyc", 5, 2, 7), ("cyc", 20, 8, 2051), ("cyc", 21, 10, 1030), ("cyc", 45, 16, 1030)])
 def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
@@ -787,6 +804,8 @@ def test_random_shapes_and_attacks_on_the_other_wires():
     ("rep", 15, 2, 4, 3001), ("rep", 45, 2, 4, 20_003), ("rep", 9, 1, 16, 999), ("rep", 34, 8, 3, 777),
     ("cyc", 15, 2, 4, 3001), ("cyc", 45, 3, 4, 20_002), ("cyc", 45, 3, 16, 5_001), ("cyc", 15, 7, 2, 2_050),
     ("cyc", 20, 8, 3, 1_001), ("cyc", 6, 0, 5, 4_099), ("cyc", 45, 5, 4, 8_000), ("cyc", 21, 10, 2, 1_030), ("cyc", 25, 12, 2, 515),
+    # rows that end next to a piece, a wavefront stride and a window of the workgroup footprint
+    ("cyc", 45, 3, 4, 32_769), ("cyc", 9, 1, 4, 8_193), ("rep", 9, 1, 4, 32_767), ("cyc", 9, 1, 8, 65_537), ("cyc", 9, 2, 16, 257),
 ])
 def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d):
     """B = m*P per-sample gradients (the paper runs B = 180 and 720 on P = 45): unit gradient k
