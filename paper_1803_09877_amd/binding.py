@@ -19,11 +19,13 @@ _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libdraco.so")
 SOURCES = [os.path.join(_HERE, "csrc", n) for n in (
     # slowest first: the per-s encoder units dominate the build time
-    "cyc_encode_s10.hip", "cyc_encode_s9.hip", "cyc_encode_s8.hip", "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
+    "cyc_encode_s16.hip", "cyc_encode_s15.hip", "cyc_encode_s14.hip", "cyc_encode_s13.hip", "cyc_encode_s12.hip",
+    "cyc_encode_s11.hip", "cyc_encode_s10.hip", "cyc_encode_s9.hip", "cyc_encode_s8.hip", "cyc_encode_s7.hip", "cyc_encode_s6.hip", "cyc_encode_s5.hip", "cyc_encode_s4.hip", "cyc_encode_s3.hip",
     "cyc_encode_s2.hip", "cyc_encode_s1.hip", "cyc_encode_s0.hip", "rep.hip", "cyc_encode.hip", "cyc_decode.hip",
     "locate.hip", "update.hip", "api.hip", "host_math.cpp")]
 HEADERS = [os.path.join(_HERE, "csrc", n) for n in (
-    "kernels.hpp", "device_util.hpp", "cyc_encode_kernels.hpp", "cyc_encode_s.inc", "host_math.hpp")] + [
+    "kernels.hpp", "device_util.hpp", "cyc_encode_kernels.hpp", "cyc_encode_s.inc", "cyc_encode_narrow.hpp",
+    "cyc_encode_narrow_s.inc", "host_math.hpp", "projection_rng.hpp")] + [
     os.path.join(_ROOT, "include", "draco.h"), os.path.join(_ROOT, "include", "draco_bench.h")]
 BUILD_DIR = os.path.join(_HERE, "_build")
 

@@ -1,8 +1,28 @@
 // Cyclic code (Sec. 3, "Cyclic Code"): dispatch of the encoder E^Cyc, z_j = G W_{.,j},
 // over the window width, and the one-node / any-width kernel.
 #include "cyc_encode_kernels.hpp"
+#include "cyc_encode_narrow.hpp"
 
 namespace draco {
+
+namespace {
+
+// Windows of 23 to 33 gradients (11 <= s <= 16): the one-complex-per-lane kernel.
+hipError_t launch_narrow(int s, bool real, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z, float* Zlo,
+                         int64_t ldm, const double2* coef, int P, int64_t d) {
+    switch (s) {
+        case 11: return launch_encode_cyc_narrow_s<11>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 12: return launch_encode_cyc_narrow_s<12>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 13: return launch_encode_cyc_narrow_s<13>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 14: return launch_encode_cyc_narrow_s<14>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 15: return launch_encode_cyc_narrow_s<15>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 16: return launch_encode_cyc_narrow_s<16>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        default: return hipErrorInvalidValue;
+    }
+}
+constexpr int kMaxNarrowS = 16;
+
+}  // namespace
 
 // One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
 // wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
@@ -47,8 +67,8 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 
 
 
-// All nodes for any window width r = 2s+1 (used when r exceeds the register-window
-// kernels): the window lives in LDS as a ring of r raw rows per lane (each lane reads back
+// All nodes for any window width r = 2s+1 (used beyond s = 16, where no register-window
+// kernel is instantiated): the window lives in LDS as a ring of r raw rows per lane (each lane reads back
 // only what it wrote: no barrier), rows are fetched Q ahead into registers, and the last
 // 2s nodes re-read rows 0..2s-1 from memory (2s/P more reads than the register kernels).
 // Same operation order as the one-node kernel: results are bit-identical to it.
@@ -154,6 +174,7 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, 1, Z, Zlo, ldm, coef, P, d);
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, ldm, coef, P, d);
     switch (s) {
@@ -186,6 +207,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(d)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, true, stream, G, ldg, 1, Z, nullptr, ldm, coef, P, d);
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_real_s<S>(one_per_cu, grid, stream, G, ldg, Z, ldm, coef, P, d);
     switch (s) {
@@ -205,6 +227,7 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
     switch (s) {

@@ -36,6 +36,12 @@ __device__ __forceinline__ float2 ld2(const float* p) {
     const vfloat2 v = __builtin_nontemporal_load(reinterpret_cast<const vfloat2*>(p));
     return make_float2(v.x, v.y);
 }
+__device__ __forceinline__ void st2(float* p, float2 v) {
+    vfloat2 w;
+    w.x = v.x;
+    w.y = v.y;
+    __builtin_nontemporal_store(w, reinterpret_cast<vfloat2*>(p));
+}
 // Guarded load of up to 2 floats; missing ones read as 0.
 __device__ __forceinline__ float2 ld2_partial(const float* p, int n) {
     float2 v = make_float2(0.f, 0.f);

@@ -11,7 +11,7 @@ namespace draco {
 
 constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts of 64)
 constexpr int kMaxS = 7;              // repetition kernels are specialised for r = 2s+1 <= 15; larger r takes the generic path
-constexpr int kMaxCycS = 10;          // cyclic encoder: register windows up to r = 21, an LDS ring beyond
+constexpr int kMaxCycS = 10;          // cyclic encoder: two complex per lane up to r = 21, one per lane up to r = 33, an LDS ring beyond
 constexpr int kProjectLoads = 8;      // float4 loads per lane per message row in the projection kernel
 constexpr int kMaxNodes = 256;        // DRACO_MAX_NODES
 constexpr int kMaskWords = 4;         // 64-bit words of node flags (kMaxNodes / 64)
