@@ -2,6 +2,8 @@
 // per-window-width translation units (one per s, so they compile in parallel).
 #pragma once
 
+#include <type_traits>
+
 #include "device_util.hpp"
 
 namespace draco {
@@ -495,6 +497,104 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
             }
         }
     }
+}
+
+// m = 4 (the paper's B = 180 on P = 45): two units, eight rows, in flight.  Row i sits in ring
+// slot i mod 8 = 4 (k mod 2) + t for row t of unit k, so the half a unit reads is fixed by the
+// parity of k; the node loop is unrolled over 2R nodes to make that parity static.
+template <int S, bool FULL, bool WIDE>
+__device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restrict__ G, int64_t ldg,
+                                                           float* __restrict__ Z, float* __restrict__ Zlo,
+                                                           int64_t ldm, const double2* __restrict__ coef, int P,
+                                                           int64_t d, double4* head /* LDS [2S][kBlock] */) {
+    constexpr int R = 2 * S + 1;
+    const int64_t c0 = lane_column<kSpreadEncodeCyc>();
+    const int64_t mlen = 2 * ((d + 1) / 2);
+    if (!FULL && c0 >= mlen) return;
+    const int nin = FULL ? 4 : clamp4(d - c0);
+    const int nout = FULL ? 4 : clamp4(mlen - c0);
+    const int64_t rows = (int64_t)P * 4;
+
+    float4 ring[8];
+    int64_t next = 0;  // next sample row to fetch
+    const float* src = G + c0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        if (next < rows) ring[t] = ldx<FULL>(src + next * ldg, nin);
+        ++next;
+    }
+    auto unit_sum = [&](auto parity) -> double4 {  // the next unit gradient: its 4 rows, ascending, in fp64
+        constexpr int H = 4 * decltype(parity)::value;
+        double4 acc = make_double4(0.0, 0.0, 0.0, 0.0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float4 x = ring[H + t];
+            if (next < rows) ring[H + t] = ldx<FULL>(src + next * ldg, nin);
+            ++next;
+            acc.x += (double)x.x;
+            acc.y += (double)x.y;
+            acc.z += (double)x.z;
+            acc.w += (double)x.w;
+        }
+        return acc;
+    };
+    double wre[R][2], wim[R][2];
+    auto put = [&](int slot, const double4& v) {
+        wre[slot][0] = v.x;
+        wim[slot][0] = v.y;
+        wre[slot][1] = v.z;
+        wim[slot][1] = v.w;
+    };
+#pragma unroll
+    for (int k = 0; k < 2 * S; ++k) {
+        double4 v;
+        if (k % 2 == 0) v = unit_sum(std::integral_constant<int, 0>());
+        else v = unit_sum(std::integral_constant<int, 1>());
+        head[k * kBlock + threadIdx.x] = v;
+        put(k, v);
+    }
+    for (int n0 = 0; n0 < P; n0 += 2 * R) {
+#pragma unroll
+        for (int uu = 0; uu < 2 * R; ++uu) {
+            const int n = n0 + uu;
+            if (n < P) {
+                const int kk = n + 2 * S;   // same parity as uu: n0 and 2S are even
+                double4 v;
+                if (kk >= P) v = head[(kk - P) * kBlock + threadIdx.x];
+                else if (uu % 2 == 0) v = unit_sum(std::integral_constant<int, 0>());
+                else v = unit_sum(std::integral_constant<int, 1>());
+                put((uu + 2 * S) % R, v);
+                const double2* cn = coef + (int64_t)n * R;
+                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+#pragma unroll
+                for (int t = 0; t < R; ++t) {
+                    const int slot = (uu + t) % R;
+                    const double cr = cn[t].x, ci = cn[t].y;
+                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
+                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
+                }
+                const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
+                if constexpr (WIDE) {
+                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                }
+            }
+        }
+    }
+}
+
+template <int S, bool WIDE>
+__global__ __launch_bounds__(kBlock) void encode_cyc_multi_four_kernel(const float* __restrict__ G, int64_t ldg,
+                                                                       float* __restrict__ Z, float* __restrict__ Zlo,
+                                                                       int64_t ldm, const double2* __restrict__ coef,
+                                                                       int P, int64_t d) {
+    extern __shared__ double4 head_sums[];  // [2S][kBlock]
+    if (block_is_full<kSpreadEncodeCyc>(d))
+        encode_cyc_multi_four_body<S, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
+    else
+        encode_cyc_multi_four_body<S, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 
 template <int S, int D, bool WIDE>
