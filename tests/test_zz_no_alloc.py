@@ -82,3 +82,53 @@ def test_static_decoder_rejects_what_does_not_fit():
                                             status.data_ptr(), st) == B.EALIGN
     assert L.draco_decode_repetition_static(3, 1, 8, R.data_ptr(), 8, None, mask.data_ptr(), status.data_ptr(),
                                             st) == B.EINVAL
+
+
+def test_static_decoder_inside_a_captured_graph():
+    """What the entry point is for: captured into a HIP graph (after one call outside capture,
+    which looks up the device array), replayed several times with the messages edited and
+    unrelated eager work in between; every replay against the eager plan-based decoder."""
+    w = synth.Workload(name="rep_static_graph", code="rep", P=45, s=2, d=200_003, sigma=1e-2,
+                       attacks=("signflip", "noise"), placement="distinct_groups", seed=synth.SEED_BASE + 905)
+    c = Case(w)
+    try:
+        dev = c.device
+        c.encode()
+        c.receive()
+        u = torch.zeros_like(c.u)
+        mask = torch.zeros(4, dtype=torch.int64, device=dev)
+        status = torch.full((1,), -7, dtype=torch.int32, device=dev)
+        B.draco_decode_repetition_static(w.P, w.s, w.d, c.R, u, mask, status)       # outside capture first
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                B.draco_decode_repetition_static(w.P, w.s, w.d, c.R, u, mask, status, stream=side)
+        torch.cuda.synchronize()
+        ref_u = torch.zeros_like(c.u)
+        ref_mask = torch.zeros(4, dtype=torch.int64, device=dev)
+        ref_status = torch.zeros(1, dtype=torch.int32, device=dev)
+        filler = torch.zeros(1 << 20, device=dev)
+        for it in range(4):
+            c.R.copy_(c.Z)
+            groups = w.P // w.r
+            liars = [(((j // w.r + it) % groups) * w.r + (j + it) % w.r, a) for j, a in c.adversaries]
+            synth.apply_attacks(c.R, c.mlen, liars, w.seed + it)
+            expect = np.zeros(w.P, dtype=bool)
+            expect[[j for j, _ in liars]] = True
+            c.plan.decode_repetition_async(c.R, ref_u, ref_mask, ref_status)
+            filler.add_(1.0)                                                         # eager work between replays
+            torch.cuda.synchronize()
+            u.fill_(float("nan"))
+            mask.fill_(-1)
+            status.fill_(-7)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert int(status.item()) == int(ref_status.item()) == B.OK, it
+            assert int(mask[0].item()) == int(ref_mask[0].item()), it
+            assert np.array_equal(B.mask_to_bool(mask.cpu().numpy().view(np.uint64), w.P), expect), it
+            assert torch.equal(u[:w.d].view(torch.int32), ref_u[:w.d].view(torch.int32)), it
+    finally:
+        c.close()
