@@ -52,6 +52,8 @@ TAU_H = 32.0 * 2.0 ** -24   # syndromes with max|h_m| <= TAU_H * rho count as ze
 # The same threshold for messages carried to 48 bits (two fp32 words): their clean syndromes
 # sit near 1e-14 * rho, the rounding of the fp64 projection itself.
 TAU_H_WIDE = 2.0 ** -36
+# And for a two-word wire whose second word is a bfloat16 (32 bits of the message): 32 of its ulps.
+TAU_H_BF16 = 32.0 * 2.0 ** -33
 
 
 # --------------------------------------------------------------------------
@@ -286,6 +288,33 @@ def complex_to_wire(Zc: np.ndarray) -> np.ndarray:
     out[..., 0::2] = Zc.real
     out[..., 1::2] = Zc.imag
     return out
+
+
+def round_to_bfloat16(x: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bfloat16 (1 sign, 8 exponent, 7 fraction bits: the
+    upper half of the fp32 word), ties to the even neighbour; returned as fp32.  NaN stays
+    NaN.  The number format is the published one; Sec. 3 leaves a message's format open."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    keep = bits >> 16
+    rest = bits & 0xFFFF
+    up = (rest > 0x8000) | ((rest == 0x8000) & ((keep & 1) == 1))
+    out = ((keep + up.astype(np.uint64)) << 16).astype(np.uint32).view(np.float32)
+    return np.where(np.isnan(x), x, out).astype(np.float32)
+
+
+def two_word_wire(Z: np.ndarray, second: str = "f32"):
+    """An fp64 message slab as two words per value: hi = fp32(z) and lo = the rounding
+    residual z - hi, itself rounded to fp32 ("f32") or to bfloat16 ("bf16").  Both fp32 arrays."""
+    Z = np.asarray(Z, dtype=np.float64)
+    hi = Z.astype(np.float32)
+    with np.errstate(invalid="ignore"):
+        lo = (Z - hi.astype(np.float64)).astype(np.float32)
+    if second == "bf16":
+        lo = round_to_bfloat16(lo)
+    elif second != "f32":
+        raise ValueError(second)
+    return hi, lo
 
 
 # --------------------------------------------------------------------------

@@ -542,3 +542,112 @@ def test_wide_threshold_sits_between_the_floors():
         gamma = o.project(o.wire_to_complex(R), f)
         floor = np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma))
         assert lo_b <= floor <= hi_b, floor
+
+
+# ------------------------------------- two-word wire with a bfloat16 second word --
+def test_round_to_bfloat16_hand_values_and_ties():
+    """Values whose nearest bfloat16 can be read off: 8 significant bits, ties to even."""
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                  -(1.0 + 3 * 2.0 ** -8), 0.0, -0.0, 3.0e38, 1e-30, np.inf, -np.inf], dtype=np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7,
+                     -(1.0 + 2.0 ** -6), 0.0, -0.0, 3.0e38, 1e-30, np.inf, -np.inf], dtype=np.float32)
+    got = o.round_to_bfloat16(x)
+    assert np.array_equal(got[:8].view(np.uint32), want[:8].view(np.uint32))
+    assert (got.view(np.uint32) & 0xFFFF == 0).all()                 # the lower half of every word is clear
+    assert np.array_equal(got[10:], want[10:])
+    assert abs(float(got[8]) - 3.0e38) <= 2.0 ** -9 * 3.0e38 and abs(float(got[9]) - 1e-30) <= 2.0 ** -9 * 1e-30
+    assert np.isnan(o.round_to_bfloat16(np.array([np.nan], dtype=np.float32))).all()
+
+
+def test_round_to_bfloat16_against_a_library_conversion():
+    """torch's CPU conversion to bfloat16 rounds to nearest even as well: bit for bit on random
+    fp32 words of every exponent, and rounding twice changes nothing."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 2 ** 32, size=200_000, dtype=np.uint64).astype(np.uint32)
+    x = bits.view(np.float32)
+    x = x[np.isfinite(x)]
+    got = o.round_to_bfloat16(x)
+    lib = torch.from_numpy(x.copy()).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got.view(np.uint32), lib.view(np.uint32))
+    assert np.array_equal(o.round_to_bfloat16(got).view(np.uint32), got.view(np.uint32))
+
+
+def test_two_word_wire_carries_48_and_32_bits():
+    """hi + lo is within 2^-48 |z| (fp32 second word) and 2^-33 |z| (bfloat16) of z, element by
+    element, and the first word alone within 2^-24 |z|."""
+    rng = np.random.default_rng(11)
+    z = rng.standard_normal(100_000) * 10.0 ** rng.uniform(-6, 6, 100_000)
+    for second, bits in (("f32", 48), ("bf16", 33)):
+        hi, lo = o.two_word_wire(z, second)
+        assert hi.dtype == lo.dtype == np.float32
+        err = np.abs(hi.astype(np.float64) + lo.astype(np.float64) - z)
+        assert (err <= 2.0 ** -bits * np.abs(z)).all(), second
+        assert (np.abs(hi.astype(np.float64) - z) <= 2.0 ** -24 * np.abs(z)).all()
+    assert err.max() > 0                                              # the bfloat16 word does round
+    with pytest.raises(ValueError):
+        o.two_word_wire(z, "fp8")
+
+
+def test_bfloat16_second_word_end_to_end_at_p45():
+    """(P, s) = (45, 3): W's entries reach 1e4-1e5 and the decoder cancels them, so what the wire
+    rounds away comes back amplified.  One fp32 word leaves the decoded sum around 3e-4 from the
+    true one -- outside Definition 2's 1e-4 reading -- the bfloat16 second word 2^9 closer."""
+    P, s, d = 45, 3, 20_000
+    G = _grads(P, d, 21, 1e-2)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    Z = o.encode_cyclic(G, s)
+    f = _f(d // 2, 3)
+    errs = {}
+    for name, second in (("bf16", "bf16"), ("f32", "f32")):
+        hi, lo = o.two_word_wire(Z, second)
+        R = hi.astype(np.float64) + lo.astype(np.float64)
+        tau = o.TAU_H_BF16 if second == "bf16" else o.TAU_H_WIDE
+        u, mask, st = o.decode_cyclic(R, f, s, d, tau_h=tau)
+        assert st == o.OK and not mask.any()
+        errs[name] = np.linalg.norm(u - ref) / np.linalg.norm(ref)
+    u1, mask1, st1 = o.decode_cyclic(Z.astype(np.float32), f, s, d)
+    assert st1 == o.OK and not mask1.any()
+    errs["one"] = np.linalg.norm(u1 - ref) / np.linalg.norm(ref)
+    assert errs["f32"] < 1e-9 < errs["bf16"] < 3e-6 < 1e-4 < errs["one"] < 1e-3, errs
+    assert 100 < errs["one"] / errs["bf16"] < 2000, errs             # 2^9 more bits, give or take
+
+
+@pytest.mark.parametrize("P,s", [(5, 1), (7, 2), (9, 4)])
+def test_bfloat16_threshold_every_adversary_subset(P, s):
+    """Messages carried to 32 bits: lies of 5e-7 of the message size (the middle of the 2^9 between
+    the two thresholds; with 8 coordinates a lie's syndromes scatter over two orders), every
+    adversary set of size <= s: located with TAU_H_BF16, passed as rounding by the one-word TAU_H."""
+    d = 16
+    G = _grads(P, d, 9 * P + s)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    hi, lo = o.two_word_wire(o.encode_cyclic(G, s), "bf16")
+    Zw = hi.astype(np.float64) + lo.astype(np.float64)
+    f = _f(d // 2, P + 1)
+    rng = np.random.default_rng(P + s)
+    scale = np.median(np.abs(Zw))
+    for a in range(0, s + 1):
+        for V in itertools.combinations(range(P), a):
+            R = Zw.copy()
+            for j in V:
+                R[j] += rng.standard_normal(d) * 5e-7 * scale
+            u, mask, st = o.decode_cyclic(R, f, s, d, tau_h=o.TAU_H_BF16)
+            assert st == o.OK and sorted(np.flatnonzero(mask)) == sorted(V)
+            assert np.linalg.norm(u - ref) <= 1e-7 * np.linalg.norm(ref)
+            _, loose, st2 = o.decode_cyclic(R, f, s, d)
+            assert st2 == o.OK and not loose.any()
+
+
+def test_bfloat16_threshold_sits_between_the_floors():
+    """Clean syndromes of the 32-bit wire are some 2^-33 of the median projection: TAU_H_BF16 is
+    an order above them at the benchmark's shape and far below the one-word wire's floor."""
+    P, s, d = 45, 3, 40_000
+    G = _grads(P, d, 4, 1e-2)
+    Z = o.encode_cyclic(G, s)
+    hi, lo = o.two_word_wire(Z, "bf16")
+    f = _f(d // 2, 8)
+    floors = []
+    for R in (hi.astype(np.float64) + lo.astype(np.float64), hi.astype(np.float64)):
+        gamma = o.project(o.wire_to_complex(R), f)
+        floors.append(np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma)))
+    assert floors[0] <= o.TAU_H_BF16 / 8 and 8 * o.TAU_H_BF16 <= floors[1], floors
