@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the DRACO encode/decode hot path on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--wire auto|one|wide|unpacked]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--wire auto|one|wide16|wide|unpacked]
 
 A step is one pass of the whole hot path over one batch of synthetic gradient
 slabs already resident in HBM: the encoder of all P nodes (G -> Z), then the
@@ -9,16 +9,16 @@ parameter-server decoder on the received messages R (Z with the workload's
 adversarial rows), through the synchronous C-ABI entry points (sum left on the
 device, mask and status on the host).  The headline workload is the largest
 one, the cyclic code at P = 45, s = 3, d = 25.6 M with full encode and decode,
-on the wire that meets the 1e-4 bar END TO END there (two fp32 words per lane:
-one word leaves 3e-4).  The metric is the benchmark contract's "decoded gradient
+on the narrowest wire that meets the 1e-4 bar END TO END there (an fp32 word plus a
+bfloat16 word per float, 6 bytes: that leaves 4e-7; one fp32 word leaves 3e-4).  The metric is the benchmark contract's "decoded gradient
 GB/s consumed": P*d*4 bytes per step divided by the step time.
 
 One JSON line is printed.  Beside the headline it carries
   * `roofline`: the dominant kernel's algorithmic bytes over its HIP-event duration
     (events recorded by the library on the launch stream) against 8 TB/s;
   * `cpu_baseline`: the CPU oracle timed on a bounded sample on this machine's cores;
-  * `configs`: one record per benchmark configuration (and the one-word-wire and
-    paper-shaped rows) with per-kernel avg / median / min, encode-only and decode-only
+  * `configs`: one record per benchmark configuration (and the headline's shape on two fp32
+    words and on one, and the paper-shaped row) with per-kernel avg / median / min, encode-only and decode-only
     "consumed" GB/s, the end-to-end error against the true gradient sum, and the oracle's
     seconds.
 """
@@ -38,18 +38,24 @@ KIND_NAMES = ["encode", "vote", "project", "recombine", "locate"]
 # kernel-name fragments of each kind in the rocprofv3 summaries under profiles/
 KIND_KERNEL = {"encode": "encode_", "vote": "decode_rep", "project": "cyc_project_kernel", "recombine": "cyc_recombine"}
 TOL_END_TO_END = {"rep": 1e-5, "cyc": 1e-4}
+# two-word wires: format of the second word, and fp32 words per message float
+WIRE_SECOND = {"wide": "f32", "wide16": "bf16"}
+WIRE_WORDS = {"one": 1.0, "wide": 2.0, "wide16": 1.5, "unpacked": 1.0}
+WIRE_TEXT = {"one": "one fp32 word", "wide": "two fp32 words (hi+lo)", "wide16": "fp32 word + bfloat16 word (hi+lo)",
+             "unpacked": "unpacked complex, one word"}
 
 
 def algorithmic_bytes(w, mlen, n_honest, words):
     """Bytes each kernel must move per launch (every input read once, every output written
-    once); `words` = fp32 words per message float (2 on the wide wire); the encoder reads
+    once); `words` = fp32 words per message float (2 on the wide wire, 1.5 with a bfloat16
+    second word); the encoder reads
     B = m*P per-sample rows."""
     P, d, h = w.P, w.d, mlen // 2   # h: complex entries per message = entries of f
     return {
-        "encode": (w.m * P * d + words * P * mlen) * 4,
+        "encode": int((w.m * P * d + words * P * mlen) * 4),
         "vote": (P * d + d) * 4,
-        "project": (words * P * mlen + h) * 4,
-        "recombine": (words * n_honest * mlen + d) * 4,
+        "project": int((words * P * mlen + h) * 4),
+        "recombine": int((words * n_honest * mlen + d) * 4),
     }
 
 
@@ -113,8 +119,12 @@ def oracle_time(w, wire, budget_s, d_cap):
         else:
             Z = o.encode_cyclic(G, ws.s)
         t_enc += time.perf_counter() - t0
-        # the wire: one fp32 word, or (wide) the fp64 message itself -- 48 bits of it travel
-        R = torch.from_numpy(Z.astype(np.float32) if wire != "wide" else Z.copy())
+        # the wire: one fp32 word, or the oracle's two-word wire (48 or 32 bits of the fp64 message)
+        if wire in WIRE_SECOND:
+            hi, lo = o.two_word_wire(Z, WIRE_SECOND[wire])
+            R = torch.from_numpy(hi.astype(np.float64) + lo.astype(np.float64))
+        else:
+            R = torch.from_numpy(Z.astype(np.float32))
         synth.apply_attacks(R, Z.shape[1], ws.adversaries(), ws.seed)
         if ws.decode:
             t1 = time.perf_counter()
@@ -123,7 +133,7 @@ def oracle_time(w, wire, budget_s, d_cap):
             elif unpacked:
                 _, mask, st, _ = o.decode_cyclic_unpacked(R.numpy(), f, ws.s)
             else:
-                _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s, tau_h=o.TAU_H_WIDE if wire == "wide" else o.TAU_H)
+                _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s, tau_h={"wide": o.TAU_H_WIDE, "wide16": o.TAU_H_BF16}.get(wire, o.TAU_H))
             t_dec += time.perf_counter() - t1
             assert st == 0 and sorted(np.flatnonzero(mask)) == sorted(j for j, _ in ws.adversaries())
         reps += 1
@@ -145,13 +155,13 @@ def oracle_time(w, wire, budget_s, d_cap):
 
 
 def pick_wire(w, wire):
-    """auto: the two-word wire where one fp32 word cannot meet 1e-4 end to end (the entries of W
-    reach 1e4 and more from P = 32 on), one word elsewhere."""
+    """auto: the narrowest wire that meets 1e-4 end to end -- one fp32 word, or, where the entries
+    of W reach 1e4 and more (from P = 32 on) and one word cannot, fp32 + bfloat16."""
     if w.code == "rep":
         return "one"
     if wire != "auto":
         return wire
-    return "wide" if w.P >= 32 else "one"
+    return "wide16" if w.P >= 32 else "one"
 
 
 def stats(ms):
@@ -168,14 +178,14 @@ def measure(w, wire, steps, warmup, headline):
     from paper_1803_09877_amd import binding as B
     from paper_1803_09877_amd.runner import Case
 
-    wide, unpacked = wire == "wide", wire == "unpacked"
-    words = 2 if wide else 1
-    c = Case(w, "cuda:0", wide=wide, unpacked=unpacked)
-    name = w.name + {"one": "+one_word_wire", "wide": "+wide_wire", "unpacked": "+unpacked_wire"}[wire] \
+    wide, unpacked = wire in WIRE_SECOND, wire == "unpacked"
+    words = WIRE_WORDS[wire]
+    c = Case(w, "cuda:0", wide=WIRE_SECOND.get(wire, False), unpacked=unpacked)
+    name = w.name + {"one": "+one_word_wire", "wide": "+wide_wire", "wide16": "+wide16_wire",
+                     "unpacked": "+unpacked_wire"}[wire] \
         if (w.code == "cyc" and wire != pick_wire(w, "auto")) else w.name
     rec = {"workload": name, "code": w.code, "P": w.P, "s": w.s, "d": w.d, "B": w.P * w.m,
-           "wire": {"one": "one fp32 word", "wide": "two fp32 words (hi+lo)", "unpacked": "unpacked complex, one word"}[wire]
-           if w.code == "cyc" else "fp32", "wire_words": words,
+           "wire": WIRE_TEXT[wire] if w.code == "cyc" else "fp32", "wire_words": words,
            "adversaries": [[int(j), a] for j, a in c.adversaries],
            "step": "encode(all nodes) + decode" if w.decode else "encode(all nodes)"}
     c.encode()
@@ -287,7 +297,7 @@ def main():
     ap.add_argument("--config", type=int, default=4,
                     help="headline workload: index into the benchmark's configurations (default 4: cyclic, P=45, "
                          "s=3, d=25.6M, encode+decode); 5 = the paper-shaped row (P=45, s=5, B=180)")
-    ap.add_argument("--wire", choices=["auto", "one", "wide", "unpacked"], default="auto",
+    ap.add_argument("--wire", choices=["auto", "one", "wide", "wide16", "unpacked"], default="auto",
                     help="cyclic message format (auto: two words where one cannot meet 1e-4 end to end)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration records")
@@ -341,9 +351,9 @@ def main():
         out["cpu_baseline"] = oracle_time(w, wire, 10.0, 8_000_000 if w.code == "cyc" else 16_000_000)
 
     if not args.no_configs:
-        # every benchmark configuration on its default wire, then the one-word wire where it is
-        # not the default (reported: out of tolerance end to end), then the paper-shaped row
-        plan = [(i, "auto") for i in range(5)] + [(4, "one"), (5, "auto")]
+        # every benchmark configuration on its default wire, then the headline's shape on two fp32
+        # words and on one (reported: out of tolerance end to end), then the paper-shaped row
+        plan = [(i, "auto") for i in range(5)] + [(4, "wide"), (4, "one"), (5, "auto")]
         recs = []
         for i, wr in plan:
             wi = synth.WORKLOADS[i]

@@ -94,6 +94,26 @@ int draco_plan_create(draco_plan** out, int code, int P, int s, int64_t d);
  * the wide wire and draco_encode_samples with B > P return DRACO_EINVAL. */
 int draco_plan_set_wire(draco_plan* plan, int wire);
 
+/* Cyclic code, two-word wire (draco_encode_wide and the other *_wide entry
+ * points): the format in which the second word of a message travels.  Sec. 3
+ * defines the code over the complex numbers and leaves the number format of a
+ * message open; this picks it.
+ * DRACO_SECOND_WORD_F32 (default): lo = fp32(z - hi); hi + lo carries 48 bits
+ * of the fp64 message z, at 8 bytes per value.
+ * DRACO_SECOND_WORD_BF16: lo = bfloat16(z - hi), rounded to nearest even;
+ * hi + lo carries 32 bits of z at 6 bytes per value -- the decoded sum stays
+ * within about 1e-6 of the true one at P = 45 (one fp32 word: 3e-4), and
+ * every pass over the messages moves a quarter fewer bytes.  messages_lo_dev
+ * then points at [P][ld_m] 16-bit values: SAME ld_m and column index as the
+ * first word, counted in elements, so its rows are half as long in bytes.
+ * May be changed at any time; encoder and decoder must agree.  DRACO_EINVAL
+ * for the repetition code, the unpacked wire, or an unknown value. */
+enum {
+    DRACO_SECOND_WORD_F32 = 0,
+    DRACO_SECOND_WORD_BF16 = 1
+};
+int draco_plan_set_second_word(draco_plan* plan, int format);
+
 /* Allocate the plan's device-side tables and scratch on the current device
  * (a few MB: per-node coefficients, per-wave partial projections, flag
  * words).  Called implicitly by the first encode/decode if omitted; after it
@@ -149,14 +169,15 @@ int draco_encode_samples(draco_plan* plan, const float* samples_dev, int64_t B, 
  * one fp32 word then leaves a relative error near 3e-4 in the decoded sum,
  * the wide wire leaves about 1e-9, at twice the message bytes.  Same layout
  * and conditions as draco_encode for each of the two slabs (one ld_m).
- * DRACO_EINVAL for the repetition code. */
+ * draco_plan_set_second_word selects a 16-bit second word instead; the
+ * pointer is untyped for that reason.  DRACO_EINVAL for the repetition code. */
 int draco_encode_wide(draco_plan* plan, const float* grads_dev, int64_t ld_g,
-                      float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m, void* stream);
+                      float* messages_hi_dev, void* messages_lo_dev, int64_t ld_m, void* stream);
 
 /* draco_encode_samples on the wide wire (B a multiple of P; B = P is
  * draco_encode_wide).  DRACO_EINVAL for the repetition code or the unpacked wire. */
 int draco_encode_samples_wide(draco_plan* plan, const float* samples_dev, int64_t B, int64_t ld_g,
-                              float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m,
+                              float* messages_hi_dev, void* messages_lo_dev, int64_t ld_m,
                               void* stream);
 
 /* One node, as a real compute node would run it: node_grads_dev holds ONLY
@@ -281,12 +302,13 @@ int draco_decode_cyclic_hostphi(draco_plan* plan, const float* messages_dev, int
  * draco_decode_cyclic / draco_decode_cyclic_async, except that the locator
  * counts a syndrome as zero below DRACO_TAU_WIDE (instead of DRACO_TAU) times
  * the median projection: the wide wire's clean syndromes sit near 1e-14, so
- * much smaller lies can be told from rounding. */
+ * much smaller lies can be told from rounding.  With a bfloat16 second word
+ * (draco_plan_set_second_word) the threshold is DRACO_TAU_BF16. */
 int draco_decode_cyclic_wide(draco_plan* plan, const float* messages_hi_dev,
-                             const float* messages_lo_dev, int64_t ld_m, const float* f_dev,
+                             const void* messages_lo_dev, int64_t ld_m, const float* f_dev,
                              float* sum_dev, uint64_t* mask_host, void* stream);
 int draco_decode_cyclic_wide_async(draco_plan* plan, const float* messages_hi_dev,
-                                   const float* messages_lo_dev, int64_t ld_m, const float* f_dev,
+                                   const void* messages_lo_dev, int64_t ld_m, const float* f_dev,
                                    float* sum_dev, uint64_t* mask_dev, int32_t* status_dev,
                                    void* stream);
 
@@ -299,9 +321,11 @@ int draco_decode_cyclic_wide_async(draco_plan* plan, const float* messages_hi_de
 int draco_cyclic_locate(const draco_plan* plan, const double* gamma_host,
                         uint64_t* mask_host, double* t_host);
 /* Same with the relative zero threshold of the syndromes given (0 < tau < 1):
- * DRACO_TAU is what the one-word decoders use, DRACO_TAU_WIDE the wide ones. */
+ * DRACO_TAU is what the one-word decoders use, DRACO_TAU_WIDE the wide ones,
+ * DRACO_TAU_BF16 the wide ones with a bfloat16 second word. */
 #define DRACO_TAU (32.0 / 16777216.0)        /* 32 ulps of an fp32 wire */
 #define DRACO_TAU_WIDE (1.0 / 68719476736.0) /* 2^-36 */
+#define DRACO_TAU_BF16 (32.0 / 8589934592.0) /* 32 ulps of the 32-bit fp32 + bfloat16 wire */
 int draco_cyclic_locate_tol(const draco_plan* plan, const double* gamma_host, double tau,
                             uint64_t* mask_host, double* t_host);
 

@@ -31,7 +31,8 @@ BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
 WIRE_PACKED, WIRE_UNPACKED = 0, 1
-TAU, TAU_WIDE = 32.0 / 16777216.0, 1.0 / 68719476736.0
+TAU, TAU_WIDE, TAU_BF16 = 32.0 / 16777216.0, 1.0 / 68719476736.0, 32.0 / 8589934592.0
+SECOND_WORD_F32, SECOND_WORD_BF16 = 0, 1
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
 EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
 KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE, KIND_LOCATE = 0, 1, 2, 3, 4
@@ -49,6 +50,7 @@ EXPORTS = [
     "draco_cyclic_locate_tol", "draco_decode_repetition_static",
     "draco_plan_last_projection_seed", "draco_encode_oneshot", "draco_decode_repetition_oneshot",
     "draco_decode_cyclic_oneshot", "draco_cache_clear", "draco_apply_update", "draco_encode_samples_wide",
+    "draco_plan_set_second_word",
 ]
 # the measuring instruments of include/draco_bench.h
 BENCH_EXPORTS = ["draco_copy_probe", "draco_plan_set_timing", "draco_plan_kernel_time", "draco_plan_kernel_times"]
@@ -154,6 +156,8 @@ def lib() -> ctypes.CDLL:
     L.draco_cyclic_locate_tol.restype = i32
     L.draco_plan_set_wire.argtypes = [vp, i32]
     L.draco_plan_set_wire.restype = i32
+    L.draco_plan_set_second_word.argtypes = [vp, i32]
+    L.draco_plan_set_second_word.restype = i32
     L.draco_plan_set_projection_seed.argtypes = [vp, ctypes.c_uint64]
     L.draco_plan_set_projection_seed.restype = i32
     L.draco_projection_vector.argtypes = [vp, ctypes.c_uint64, vp]
@@ -236,6 +240,7 @@ class Plan:
             self._h = None
             raise DracoError(status)
         self.code, self.P, self.s, self.d = code, P, s, d
+        self._second_word = SECOND_WORD_F32
 
     def close(self) -> None:
         if getattr(self, "_h", None):
@@ -334,17 +339,17 @@ class Plan:
                                           messages.data_ptr(), messages.stride(0), _stream_ptr(stream)))
 
     def encode_samples_wide(self, samples, hi, lo, stream=None) -> None:
-        assert hi.stride(0) == lo.stride(0)
+        self._check_lo(hi, lo)
         _check(lib().draco_encode_samples_wide(self._h, samples.data_ptr(), samples.shape[0], samples.stride(0),
                                                hi.data_ptr(), lo.data_ptr(), hi.stride(0), _stream_ptr(stream)))
 
     def encode_wide(self, grads, hi, lo, stream=None) -> None:
-        assert hi.stride(0) == lo.stride(0)
+        self._check_lo(hi, lo)
         _check(lib().draco_encode_wide(self._h, grads.data_ptr(), grads.stride(0), hi.data_ptr(), lo.data_ptr(),
                                        hi.stride(0), _stream_ptr(stream)))
 
     def decode_cyclic_wide(self, hi, lo, f, out_sum, stream=None):
-        assert hi.stride(0) == lo.stride(0)
+        self._check_lo(hi, lo)
         words = np.zeros(mask_words(self.P), dtype=np.uint64)
         status = lib().draco_decode_cyclic_wide(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), _ptr_or_null(f),
                                                 out_sum.data_ptr(), words.ctypes.data, _stream_ptr(stream))
@@ -352,13 +357,23 @@ class Plan:
         return mask_to_bool(words, self.P), status
 
     def decode_cyclic_wide_async(self, hi, lo, f, out_sum, mask_dev, status_dev, stream=None) -> None:
-        assert hi.stride(0) == lo.stride(0)
+        self._check_lo(hi, lo)
         _check(lib().draco_decode_cyclic_wide_async(self._h, hi.data_ptr(), lo.data_ptr(), hi.stride(0), _ptr_or_null(f),
                                                     out_sum.data_ptr(), mask_dev.data_ptr(), status_dev.data_ptr(),
                                                     _stream_ptr(stream)))
 
     def set_wire(self, wire: int) -> None:
         _check(lib().draco_plan_set_wire(self._h, wire))
+
+    def set_second_word(self, fmt: int) -> None:
+        """Two-word wire: SECOND_WORD_F32 (float32 slab) or SECOND_WORD_BF16 (bfloat16 slab, same shape)."""
+        _check(lib().draco_plan_set_second_word(self._h, fmt))
+        self._second_word = fmt
+
+    def _check_lo(self, hi, lo) -> None:
+        """The second slab has the first one's row stride in elements and the plan's element type."""
+        want = "torch.bfloat16" if self._second_word == SECOND_WORD_BF16 else "torch.float32"
+        assert hi.stride(0) == lo.stride(0) and str(lo.dtype) == want, (lo.dtype, want)
 
     def set_projection_seed(self, seed: int) -> None:
         _check(lib().draco_plan_set_projection_seed(self._h, seed))

@@ -55,6 +55,7 @@ struct draco_plan {
     uint64_t f_calls = 0;            // decodes that generated f since the base seed was set
     uint64_t f_last = 0;             // seed the last such decode used
     int wire = DRACO_WIRE_PACKED;    // cyclic code: packed (ceil(d/2) complex) or unpacked (d complex)
+    int second_word = DRACO_SECOND_WORD_F32;   // two-word wire: format of the second word
     int32_t* idx_dev = nullptr;      // P, then one more word: the number of honest nodes
     uint64_t* flags_dev = nullptr;   // kMaskWords, zero between calls
     // pinned host staging
@@ -78,6 +79,15 @@ int check_slab(const void* p, int64_t ld, int64_t row_len) {
 }
 
 bool unpacked(const draco_plan* p) { return p->wire == DRACO_WIRE_UNPACKED; }
+
+// Second-word format as the launchers name it, and the locator's zero threshold for a wire.
+int lo_format(const draco_plan* p) {
+    return p->second_word == DRACO_SECOND_WORD_BF16 ? kSecondWordBf16 : kSecondWordF32;
+}
+double tau_of(const draco_plan* p, bool wide) {
+    if (!wide) return kTauH;
+    return p->second_word == DRACO_SECOND_WORD_BF16 ? kTauHBf16 : kTauHWide;
+}
 
 int64_t message_len(const draco_plan* p) {
     if (p->code == DRACO_CODE_REPETITION) return p->d;
@@ -314,8 +324,8 @@ int encode_impl(draco_plan* p, const float* grads_dev, int64_t ld_g, float* hi_d
     else if (unpacked(p))
         HIP_TRY(launch_encode_cyc_real(grads_dev, ld_g, hi_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, ld_m, p->coef_dev, p->P, p->s,
-                                  p->d, st));
+        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->coef_dev,
+                                  p->P, p->s, p->d, st));
     return DRACO_OK;
 }
 
@@ -327,8 +337,8 @@ int draco_encode(draco_plan* p, const float* grads_dev, int64_t ld_g, float* mes
 }
 
 int draco_encode_wide(draco_plan* p, const float* grads_dev, int64_t ld_g, float* messages_hi_dev,
-                      float* messages_lo_dev, int64_t ld_m, void* stream) {
-    return encode_impl(p, grads_dev, ld_g, messages_hi_dev, messages_lo_dev, true, ld_m, stream);
+                      void* messages_lo_dev, int64_t ld_m, void* stream) {
+    return encode_impl(p, grads_dev, ld_g, messages_hi_dev, static_cast<float*>(messages_lo_dev), true, ld_m, stream);
 }
 
 namespace {
@@ -355,7 +365,7 @@ int encode_samples_impl(draco_plan* p, const float* samples_dev, int64_t B, int6
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_samples(samples_dev, ld_g, m, messages_dev, ld_m, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, wide ? lo_dev : nullptr, ld_m, p->coef_dev,
+        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->coef_dev,
                                           p->P, p->s, p->d, st));
     return DRACO_OK;
 }
@@ -368,8 +378,8 @@ int draco_encode_samples(draco_plan* p, const float* samples_dev, int64_t B, int
 }
 
 int draco_encode_samples_wide(draco_plan* p, const float* samples_dev, int64_t B, int64_t ld_g,
-                              float* messages_hi_dev, float* messages_lo_dev, int64_t ld_m, void* stream) {
-    return encode_samples_impl(p, samples_dev, B, ld_g, messages_hi_dev, messages_lo_dev, true, ld_m, stream);
+                              float* messages_hi_dev, void* messages_lo_dev, int64_t ld_m, void* stream) {
+    return encode_samples_impl(p, samples_dev, B, ld_g, messages_hi_dev, static_cast<float*>(messages_lo_dev), true, ld_m, stream);
 }
 
 int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
@@ -388,7 +398,7 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     else if (unpacked(p))
         HIP_TRY(launch_encode_cyc_real_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, p->coef_dev, node, p->P, p->s, p->d,
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, kSecondWordF32, p->coef_dev, node, p->P, p->s, p->d,
                                        st));
     return DRACO_OK;
 }
@@ -471,17 +481,17 @@ int decode_cyclic_async_impl(draco_plan* p, const float* hi_dev, const float* lo
     const uint64_t seed = f_dev == nullptr ? next_projection_seed(p) : 0;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, lo_format(p), ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
                                    sum_dev, unpacked(p), spec, P, paired_len(p), st));
     }
     {
         Timed timed(p, kLocateKind, st);
-        HIP_TRY(launch_cyc_locate(p->gamma_dev, p->root_dev, P, p->s, wide ? kTauHWide : kTauH, p->b0_dev, mask_dev, status_dev,
+        HIP_TRY(launch_cyc_locate(p->gamma_dev, p->root_dev, P, p->s, tau_of(p, wide), p->b0_dev, mask_dev, status_dev,
                                   p->b_dev, p->idx_dev, p->idx_dev + P, spec, st));
     }
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev,
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, lo_format(p), ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, spec, P, sum_dev,
                                      unpacked(p), paired_len(p), st));
     }
     return DRACO_OK;
@@ -498,7 +508,7 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     const uint64_t seed = f_dev == nullptr ? next_projection_seed(p) : 0;
     {
         Timed timed(p, kProject, st);
-        HIP_TRY(launch_cyc_project(hi_dev, lo, ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
+        HIP_TRY(launch_cyc_project(hi_dev, lo, lo_format(p), ld_m, f_dev, seed, p->partial_dev, p->gamma_dev, p->b0_dev,
                                    sum_dev, unpacked(p), nullptr, P, paired_len(p), st));
     }
     HIP_TRY(hipMemcpyAsync(p->gamma_pin, p->gamma_dev, P * sizeof(double2), hipMemcpyDeviceToHost, st));
@@ -507,7 +517,7 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     std::vector<std::complex<double>> gamma(P), t;
     for (int j = 0; j < P; ++j) gamma[j] = std::complex<double>(p->gamma_pin[2 * j], p->gamma_pin[2 * j + 1]);
     std::vector<uint8_t> mask;
-    const bool located = cyclic_locate(P, s, wide ? kTauHWide : kTauH, gamma.data(), mask, t);
+    const bool located = cyclic_locate(P, s, tau_of(p, wide), gamma.data(), mask, t);
     words_from_mask(mask, mask_host, P);
     std::vector<cplx_t> b;
     if (!cyclic_recombination_vector(P, s, mask, b)) return DRACO_LOCATE_FAILED;
@@ -524,7 +534,7 @@ int decode_cyclic_hostphi_impl(draco_plan* p, const float* hi_dev, const float* 
     HIP_TRY(hipMemcpyAsync(p->idx_dev, p->idx_pin, (P + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     {
         Timed timed(p, kRecombine, st);
-        HIP_TRY(launch_cyc_recombine(hi_dev, lo, ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, nullptr, P, sum_dev,
+        HIP_TRY(launch_cyc_recombine(hi_dev, lo, lo_format(p), ld_m, p->b_dev, p->idx_dev, p->idx_dev + P, nullptr, P, sum_dev,
                                      unpacked(p), paired_len(p), st));
     }
     HIP_TRY(hipStreamSynchronize(st));
@@ -568,15 +578,15 @@ int draco_decode_cyclic_hostphi(draco_plan* p, const float* messages_dev, int64_
     return decode_cyclic_hostphi_impl(p, messages_dev, nullptr, false, ld_m, f_dev, sum_dev, mask_host, stream);
 }
 
-int draco_decode_cyclic_wide(draco_plan* p, const float* messages_hi_dev, const float* messages_lo_dev, int64_t ld_m,
+int draco_decode_cyclic_wide(draco_plan* p, const float* messages_hi_dev, const void* messages_lo_dev, int64_t ld_m,
                              const float* f_dev, float* sum_dev, uint64_t* mask_host, void* stream) {
-    return decode_cyclic_impl(p, messages_hi_dev, messages_lo_dev, true, ld_m, f_dev, sum_dev, mask_host, stream);
+    return decode_cyclic_impl(p, messages_hi_dev, static_cast<const float*>(messages_lo_dev), true, ld_m, f_dev, sum_dev, mask_host, stream);
 }
 
-int draco_decode_cyclic_wide_async(draco_plan* p, const float* messages_hi_dev, const float* messages_lo_dev,
+int draco_decode_cyclic_wide_async(draco_plan* p, const float* messages_hi_dev, const void* messages_lo_dev,
                                    int64_t ld_m, const float* f_dev, float* sum_dev, uint64_t* mask_dev,
                                    int32_t* status_dev, void* stream) {
-    return decode_cyclic_async_impl(p, messages_hi_dev, messages_lo_dev, true, ld_m, f_dev, sum_dev, mask_dev,
+    return decode_cyclic_async_impl(p, messages_hi_dev, static_cast<const float*>(messages_lo_dev), true, ld_m, f_dev, sum_dev, mask_dev,
                                     status_dev, stream);
 }
 
@@ -637,6 +647,13 @@ int draco_plan_set_wire(draco_plan* p, int wire) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC || p->prepared) return DRACO_EINVAL;
     if (wire != DRACO_WIRE_PACKED && wire != DRACO_WIRE_UNPACKED) return DRACO_EINVAL;
     p->wire = wire;
+    return DRACO_OK;
+}
+
+int draco_plan_set_second_word(draco_plan* p, int format) {
+    if (p == nullptr || p->code != DRACO_CODE_CYCLIC || unpacked(p)) return DRACO_EINVAL;
+    if (format != DRACO_SECOND_WORD_F32 && format != DRACO_SECOND_WORD_BF16) return DRACO_EINVAL;
+    p->second_word = format;
     return DRACO_OK;
 }
 

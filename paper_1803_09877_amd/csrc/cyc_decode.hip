@@ -16,7 +16,7 @@ namespace draco {
 // the output.  If the locator then finds no adversary -- the usual case in training -- u0 IS
 // the decoded sum (same coefficients, same order, same instruction sequence as the
 // recombination kernel) and the second pass over the messages is skipped.
-template <bool WIDE, bool SPEC>
+template <int LO, bool SPEC>
 __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
                                                  int64_t ldm, const float* __restrict__ f, uint64_t f_seed,
                                                  double2* __restrict__ partial, const double2* __restrict__ b0,
@@ -58,15 +58,15 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
             for (int k = 0; k < K; ++k) x[k] = ld4_partial(row + (int64_t)k * kBlock * 4, nflt[k]);
         }
         double xr0[K], xi0[K], xr1[K], xi1[K];  // the wire values in fp64 (hi + lo is exact)
-        if constexpr (WIDE) {
-            const float* rowl = Rlo + (int64_t)j * ldm + q0 * 4;
+        if constexpr (LO != kLoNone) {
+            const int64_t rowl = (int64_t)j * ldm + q0 * 4;
             float4 xl[K];
             if (tile_full) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) xl[k] = ld4(rowl + (int64_t)k * kBlock * 4);
+                for (int k = 0; k < K; ++k) xl[k] = ld_lo<true, LO>(Rlo, rowl + (int64_t)k * kBlock * 4, 4);
             } else {
 #pragma unroll
-                for (int k = 0; k < K; ++k) xl[k] = ld4_partial(rowl + (int64_t)k * kBlock * 4, nflt[k]);
+                for (int k = 0; k < K; ++k) xl[k] = ld_lo<false, LO>(Rlo, rowl + (int64_t)k * kBlock * 4, nflt[k]);
             }
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -138,7 +138,7 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
 // spec_state[0]: speculate in this call (set by the previous call's locator: 1 if that decode was
 // clean); spec_state[1]: whether this call speculated (read by the recombination kernel).
 // spec_state == nullptr: never speculate.
-template <bool WIDE>
+template <int LO>
 __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __restrict__ Rm,
                                                              const float* __restrict__ Rlo, int64_t ldm,
                                                              const float* __restrict__ f, uint64_t f_seed,
@@ -149,8 +149,8 @@ __global__ __launch_bounds__(kBlock) void cyc_project_kernel(const float* __rest
     __shared__ double2 wsum[kBlock / 64][kMaxNodes];
     const bool spec = spec_state != nullptr && spec_state[0] != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0 && spec_state != nullptr) spec_state[1] = spec ? 1 : 0;
-    if (spec) cyc_project_body<WIDE, true>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, realout != 0, P, d, wsum);
-    else cyc_project_body<WIDE, false>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, false, P, d, wsum);
+    if (spec) cyc_project_body<LO, true>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, realout != 0, P, d, wsum);
+    else cyc_project_body<LO, false>(Rm, Rlo, ldm, f, f_seed, partial, b0, u, false, P, d, wsum);
 }
 
 // gamma[j] = sum over tiles of partial[tile][j], in a fixed order.
@@ -179,10 +179,11 @@ __global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double
 
 constexpr int kRecombineRows = 6;      // message rows a lane has in flight (one word per float)
 constexpr int kRecombineRowsWide = 3;  // the same on the two-word wire (two loads per row)
+constexpr int kRecombineRowsBf16 = 3;  // and with a bfloat16 second word (a 16- and an 8-byte load per row)
 
 // u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
 // ascending node order, fp64 accumulation, one rounding to fp32.
-template <bool FULL, bool WIDE, int UN>
+template <bool FULL, int LO, int UN>
 __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm, const float* __restrict__ Rlo,
                                                    int64_t ldm,
                                                    const double2* __restrict__ b, const int32_t* __restrict__ idx,
@@ -196,19 +197,19 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
     const int nout = FULL ? 4 : clamp4(d - c0);
     double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
     for (int q0 = 0; q0 < nu; q0 += UN) {
-        float4 x[UN], xl[WIDE ? UN : 1];
+        float4 x[UN], xl[LO != kLoNone ? UN : 1];
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
             if (q0 + i < nu) {
                 x[i] = ldx<FULL>(Rm + (int64_t)idx[q0 + i] * ldm + c0, nin);
-                if constexpr (WIDE) xl[i] = ldx<FULL>(Rlo + (int64_t)idx[q0 + i] * ldm + c0, nin);
+                if constexpr (LO != kLoNone) xl[i] = ld_lo<FULL, LO>(Rlo, (int64_t)idx[q0 + i] * ldm + c0, nin);
             }
         }
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
             if (q0 + i < nu) {
                 const double br = b[q0 + i].x, bi = b[q0 + i].y;
-                if constexpr (WIDE) {
+                if constexpr (LO != kLoNone) {
                     cmac(br, bi, (double)x[i].x + (double)xl[i].x, (double)x[i].y + (double)xl[i].y, are0, aim0);
                     cmac(br, bi, (double)x[i].z + (double)xl[i].z, (double)x[i].w + (double)xl[i].w, are1, aim1);
                 } else {
@@ -229,7 +230,7 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
 
 // If the projection pass speculated (spec_state[1]) and every node turned out honest
 // (*nu == P), the output already holds the answer: nothing to do.
-template <bool WIDE, int UN>
+template <int LO, int UN>
 __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __restrict__ Rm,
                                                                const float* __restrict__ Rlo, int64_t ldm,
                                                                const double2* __restrict__ b,
@@ -238,8 +239,8 @@ __global__ __launch_bounds__(kBlock) void cyc_recombine_kernel(const float* __re
                                                                const int32_t* __restrict__ spec_state, int P,
                                                                float* __restrict__ u, int realout, int64_t d) {
     if (spec_state != nullptr && spec_state[1] != 0 && *nu == P) return;
-    if (block_is_full<kSpreadRecombine>(d)) cyc_recombine_body<true, WIDE, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
-    else cyc_recombine_body<false, WIDE, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    if (block_is_full<kSpreadRecombine>(d)) cyc_recombine_body<true, LO, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
+    else cyc_recombine_body<false, LO, UN>(Rm, Rlo, ldm, b, idx, nu, u, realout != 0, d);
 }
 
 // Plain copy of a [rows][row_len] slab (row stride ld): the fastest copy of a row-major
@@ -266,15 +267,18 @@ int64_t project_tiles(int64_t d) {
     return (nvec + per - 1) / per;
 }
 
-hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f, uint64_t f_seed,
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int lo, int64_t ldm, const float* f, uint64_t f_seed,
                               double2* partial, double2* gamma, const double2* b0, float* u, bool realout,
                               int32_t* spec_state, int P, int64_t d, hipStream_t stream) {
     const int64_t tiles = project_tiles(d);
     if (Rlo == nullptr)
-        hipLaunchKernelGGL(cyc_project_kernel<false>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+        hipLaunchKernelGGL(cyc_project_kernel<kLoNone>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
+    else if (lo == kLoBf16)
+        hipLaunchKernelGGL(cyc_project_kernel<kLoBf16>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
                            f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
     else
-        hipLaunchKernelGGL(cyc_project_kernel<true>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+        hipLaunchKernelGGL(cyc_project_kernel<kLoF32>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
                            f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -289,18 +293,25 @@ hipError_t launch_copy_probe(const float* src, float* dst, int rows, int64_t row
     return hipGetLastError();
 }
 
-hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b, const int32_t* idx,
+hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int lo, int64_t ldm, const double2* b, const int32_t* idx,
                                 const int32_t* nu, const int32_t* spec_state, int P, float* u, bool realout,
                                 int64_t d, hipStream_t stream) {
     const dim3 grid(grid_cols<kSpreadRecombine>(d)), block(kBlock);
+    const size_t lds = throttle_lds(2, 0, 0);
     if (Rlo == nullptr) {
-        allow_large_lds<cyc_recombine_kernel<false, kRecombineRows>>();
-        hipLaunchKernelGGL((cyc_recombine_kernel<false, kRecombineRows>), grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
+        allow_large_lds<cyc_recombine_kernel<kLoNone, kRecombineRows>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<kLoNone, kRecombineRows>), grid, block, lds, stream, R, Rlo, ldm, b, idx,
                            nu, spec_state, P, u, realout ? 1 : 0, d);
+    } else if (lo == kLoBf16) {
+        // the 8-byte loads of the 16-bit slab want more wavefronts per CU: four workgroups run
+        // at 0.82 of the HBM peak at (P, s, d) = (45, 3, 25.6 M), two at 0.69-0.76
+        allow_large_lds<cyc_recombine_kernel<kLoBf16, kRecombineRowsBf16>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<kLoBf16, kRecombineRowsBf16>), grid, block, throttle_lds(4, 0, 0), stream,
+                           R, Rlo, ldm, b, idx, nu, spec_state, P, u, realout ? 1 : 0, d);
     } else {
-        allow_large_lds<cyc_recombine_kernel<true, kRecombineRowsWide>>();
-        hipLaunchKernelGGL((cyc_recombine_kernel<true, kRecombineRowsWide>), grid, block, throttle_lds(2, 0, 0), stream, R, Rlo, ldm, b, idx,
-                           nu, spec_state, P, u, realout ? 1 : 0, d);
+        allow_large_lds<cyc_recombine_kernel<kLoF32, kRecombineRowsWide>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<kLoF32, kRecombineRowsWide>), grid, block, lds, stream, R, Rlo, ldm, b,
+                           idx, nu, spec_state, P, u, realout ? 1 : 0, d);
     }
     return hipGetLastError();
 }

@@ -9,14 +9,14 @@ namespace {
 
 // Windows of 23 to 33 gradients (11 <= s <= 16): the one-complex-per-lane kernel.
 hipError_t launch_narrow(int s, bool real, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z, float* Zlo,
-                         int64_t ldm, const double2* coef, int P, int64_t d) {
+                         int lo, int64_t ldm, const double2* coef, int P, int64_t d) {
     switch (s) {
-        case 11: return launch_encode_cyc_narrow_s<11>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
-        case 12: return launch_encode_cyc_narrow_s<12>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
-        case 13: return launch_encode_cyc_narrow_s<13>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
-        case 14: return launch_encode_cyc_narrow_s<14>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
-        case 15: return launch_encode_cyc_narrow_s<15>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
-        case 16: return launch_encode_cyc_narrow_s<16>(real, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+        case 11: return launch_encode_cyc_narrow_s<11>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 12: return launch_encode_cyc_narrow_s<12>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 13: return launch_encode_cyc_narrow_s<13>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 14: return launch_encode_cyc_narrow_s<14>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 15: return launch_encode_cyc_narrow_s<15>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 16: return launch_encode_cyc_narrow_s<16>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
         default: return hipErrorInvalidValue;
     }
 }
@@ -28,9 +28,11 @@ constexpr int kMaxNarrowS = 16;
 // wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
 // with wrap_rows == P it is the full [P][ldg] slab and row (node+t) mod P is
 // used (the all-node path for r > 2*kMaxCycS+1).  Same operation order as the
-// all-node kernel, so results are bit-identical.
+// all-node kernel, so results are bit-identical.  The second word, if any, goes to
+// element lo_off + column of the slab zlo, in the format lo.
 __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
                                                                  float* __restrict__ z, float* __restrict__ zlo,
+                                                                 int64_t lo_off, int lo,
                                                                  const double2* __restrict__ cn, int node, int P,
                                                                  int r, int wrap_rows, int m, int64_t d) {
     const int64_t c0 = lane_column<kSpreadEncodeCyc>();
@@ -58,10 +60,10 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
     if (nout == 4) st4(z + c0, out);
     else st4_partial(z + c0, out, nout);
     if (zlo != nullptr) {
-        const float4 lo = make_float4((float)(are0 - (double)out.x), (float)(aim0 - (double)out.y),
-                                      (float)(are1 - (double)out.z), (float)(aim1 - (double)out.w));
-        if (nout == 4) st4(zlo + c0, lo);
-        else st4_partial(zlo + c0, lo, nout);
+        const float4 lo4 = make_float4((float)(are0 - (double)out.x), (float)(aim0 - (double)out.y),
+                                       (float)(are1 - (double)out.z), (float)(aim1 - (double)out.w));
+        if (nout == 4) st_lo_rt<true>(zlo, lo_off + c0, lo4, nout, lo);
+        else st_lo_rt<false>(zlo, lo_off + c0, lo4, nout, lo);
     }
 }
 
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 // Same operation order as the one-node kernel: results are bit-identical to it.
 template <int TB, bool FULL>
 __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G, int64_t ldg,
-                                                     float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
+                                                     float* __restrict__ Z, float* __restrict__ Zlo, int lo, int64_t ldm,
                                                      const double2* __restrict__ coef, int P, int r, int64_t d,
                                                      float4* ring /* LDS [r][TB] */) {
     constexpr int Q = 4;
@@ -113,9 +115,9 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if (Zlo != nullptr) {
-                    const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
-                                                  (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                    const float4 lo4 = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                    st_lo_rt<FULL>(Zlo, (int64_t)n * ldm + c0, lo4, nout, lo);
                 }
                 if (++first == r) first = 0;
                 if (++last == r) last = 0;
@@ -127,11 +129,12 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
 template <int TB>
 __global__ __launch_bounds__(TB) void encode_cyc_ring_kernel(const float* __restrict__ G, int64_t ldg,
                                                                  float* __restrict__ Z, float* __restrict__ Zlo,
-                                                                 int64_t ldm, const double2* __restrict__ coef,
-                                                                 int P, int r, int64_t d) {
+                                                                 int lo, int64_t ldm,
+                                                                 const double2* __restrict__ coef, int P, int r,
+                                                                 int64_t d) {
     extern __shared__ float4 ring[];  // [r][TB]
-    if ((int64_t)(blockIdx.x + 1) * (TB * 4) <= d) encode_cyc_ring_body<TB, true>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
-    else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, ldm, coef, P, r, d, ring);
+    if ((int64_t)(blockIdx.x + 1) * (TB * 4) <= d) encode_cyc_ring_body<TB, true>(G, ldg, Z, Zlo, lo, ldm, coef, P, r, d, ring);
+    else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, lo, ldm, coef, P, r, d, ring);
 }
 
 // One node on the unpacked wire (real gradients, d complex entries out), any window width:
@@ -168,15 +171,15 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const floa
 // Launchers
 // ---------------------------------------------------------------------------
 
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm, const double2* coef, int P,
-                             int s, int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm, const double2* coef,
+                             int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, 1, Z, Zlo, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, 1, Z, Zlo, lo, ldm, coef, P, d);
 #define DRACO_CASE(S) \
-    case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, ldm, coef, P, d);
+    case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, lo, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
@@ -188,13 +191,12 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
             if (ring_bytes <= lds_per_cu()) {
                 allow_large_lds<encode_cyc_ring_kernel<TB>>();
                 const dim3 g64((unsigned)(((mlen + 3) / 4 + TB - 1) / TB));
-                hipLaunchKernelGGL(encode_cyc_ring_kernel<TB>, g64, dim3(TB), ring_bytes, stream, G, ldg, Z, Zlo, ldm,
-                                   coef, P, r, d);
+                hipLaunchKernelGGL(encode_cyc_ring_kernel<TB>, g64, dim3(TB), ring_bytes, stream, G, ldg, Z, Zlo, lo,
+                                   ldm, coef, P, r, d);
             } else {  // windows too wide for LDS: one launch per node
                 for (int j = 0; j < P; ++j)
                     hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                       Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, 1,
-                                       d);
+                                       Zlo, (int64_t)j * ldm, lo, coef + (int64_t)j * r, j, P, r, P, 1, d);
             }
         }
     }
@@ -207,7 +209,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(d)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, true, stream, G, ldg, 1, Z, nullptr, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, true, stream, G, ldg, 1, Z, nullptr, kLoNone, ldm, coef, P, d);
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_real_s<S>(one_per_cu, grid, stream, G, ldg, Z, ldm, coef, P, d);
     switch (s) {
@@ -222,21 +224,21 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int64_t ldm,
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo, int64_t ldm,
                                      const double2* coef, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
 #define DRACO_CASE(S) \
-    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, ldm, coef, P, d);
+    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   Zlo ? Zlo + (int64_t)j * ldm : nullptr, coef + (int64_t)j * r, j, P, r, P, m, d);
+                                   Zlo, (int64_t)j * ldm, lo, coef + (int64_t)j * r, j, P, r, P, m, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();
@@ -251,13 +253,13 @@ hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, c
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef, int node,
-                                  int P, int s, int64_t d, hipStream_t stream) {
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, int lo, const double2* coef,
+                                  int node, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
-    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, coef + (int64_t)node * r, node,
-                       P, r, 0, 1, d);
+    hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, (int64_t)0, lo,
+                       coef + (int64_t)node * r, node, P, r, 0, 1, d);
     return hipGetLastError();
 }
 

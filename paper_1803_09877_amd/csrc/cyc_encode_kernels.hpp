@@ -15,7 +15,7 @@ namespace draco {
 // rows 0..2s-1, needed again by the last 2s nodes, are parked in LDS (each lane
 // reads back only what it wrote: no barrier).  Rows are fetched NB-1 rounds of
 // R = 2s+1 ahead of the arithmetic (a ring of NB register buffers).
-template <int S, int NB, bool FULL, bool WIDE>
+template <int S, int NB, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int64_t ldg, float* __restrict__ Z,
                                                 float* __restrict__ Zlo, int64_t ldm,
                                                 const double2* __restrict__ coef, int P, int64_t d,
@@ -63,10 +63,10 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
                 }
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
-                if constexpr (WIDE) {  // second word of the wide wire: what the first rounding lost
+                if constexpr (LO != kLoNone) {  // second word of the wide wire: what the first rounding lost
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
                 }
             }
         }
@@ -95,14 +95,14 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
     }
 }
 
-template <int S, int NB, bool WIDE>
+template <int S, int NB, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
                                                             float* __restrict__ Z, float* __restrict__ Zlo,
                                                             int64_t ldm, const double2* __restrict__ coef, int P,
                                                             int64_t d) {
     extern __shared__ float4 head[];  // [2S][kBlock]
-    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_body<S, NB, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
-    else encode_cyc_body<S, NB, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_body<S, NB, true, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    else encode_cyc_body<S, NB, false, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
 }
 
 // The same encoder with a wider lane: a lane owns C float4 of every row (its wavefront's C
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_kernel(const float* __
 // k*m+m-1 of the sample slab): the same sliding window, but a window entry is the fp64
 // sum of m rows, formed as the rows arrive; the first 2s unit sums are parked in LDS in
 // fp64 for the wrap-around.  Units are fetched one round ahead.
-template <int S, bool FULL, bool WIDE>
+template <int S, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ G, int64_t ldg, int m,
                                                       float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
                                                       const double2* __restrict__ coef, int P, int64_t d,
@@ -390,10 +390,10 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
                 }
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
-                if constexpr (WIDE) {
+                if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
                 }
             }
         }
@@ -420,7 +420,7 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
 // walk with the next D rows always in flight (a ring of D raw rows whose slot is the row
 // index mod D, static because m is a multiple of D), so the loads of the next unit overlap
 // the sums of this one.  Same additions in the same order as above: identical bits.
-template <int S, int D, bool FULL, bool WIDE>
+template <int S, int D, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restrict__ G, int64_t ldg, int m,
                                                            float* __restrict__ Z, float* __restrict__ Zlo,
                                                            int64_t ldm, const double2* __restrict__ coef, int P,
@@ -489,10 +489,10 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
                 }
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
-                if constexpr (WIDE) {
+                if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
                 }
             }
         }
@@ -502,7 +502,7 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
 // m = 4 (the paper's B = 180 on P = 45): two units, eight rows, in flight.  Row i sits in ring
 // slot i mod 8 = 4 (k mod 2) + t for row t of unit k, so the half a unit reads is fixed by the
 // parity of k; the node loop is unrolled over 2R nodes to make that parity static.
-template <int S, bool FULL, bool WIDE>
+template <int S, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restrict__ G, int64_t ldg,
                                                            float* __restrict__ Z, float* __restrict__ Zlo,
                                                            int64_t ldm, const double2* __restrict__ coef, int P,
@@ -575,56 +575,57 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
                 }
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
-                if constexpr (WIDE) {
+                if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    stx<FULL>(Zlo + (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
                 }
             }
         }
     }
 }
 
-template <int S, bool WIDE>
+template <int S, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_four_kernel(const float* __restrict__ G, int64_t ldg,
                                                                        float* __restrict__ Z, float* __restrict__ Zlo,
                                                                        int64_t ldm, const double2* __restrict__ coef,
                                                                        int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
     if (block_is_full<kSpreadEncodeCyc>(d))
-        encode_cyc_multi_four_body<S, true, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_four_body<S, true, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
     else
-        encode_cyc_multi_four_body<S, false, WIDE>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_four_body<S, false, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 
-template <int S, int D, bool WIDE>
+template <int S, int D, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_ring_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                        float* __restrict__ Z, float* __restrict__ Zlo,
                                                                        int64_t ldm, const double2* __restrict__ coef,
                                                                        int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
     if (block_is_full<kSpreadEncodeCyc>(d))
-        encode_cyc_multi_ring_body<S, D, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_ring_body<S, D, true, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
     else
-        encode_cyc_multi_ring_body<S, D, false, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_ring_body<S, D, false, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 
-template <int S, bool WIDE>
+template <int S, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                   float* __restrict__ Z, float* __restrict__ Zlo,
                                                                   int64_t ldm, const double2* __restrict__ coef,
                                                                   int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
-    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_multi_body<S, true, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
-    else encode_cyc_multi_body<S, false, WIDE>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_multi_body<S, true, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    else encode_cyc_multi_body<S, false, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
 }
 
 
 // Launch of the all-node encoder for one s (defined in the translation unit of that s).
 // one_per_cu selects the launch shape: one workgroup per CU with deep prefetch, or two.
+// lo: format of the second word (kLoF32 / kLoBf16) when Zlo is not null.
 template <int S>
 hipError_t launch_encode_cyc_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg, float* Z,
-                               float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
+                               float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
 // Same for the unpacked wire (real gradients in, d complex entries out).
 template <int S>
 hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg,
@@ -632,6 +633,6 @@ hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stre
 // Same for the B > P form (m per-sample rows per unit gradient).
 template <int S>
 hipError_t launch_encode_cyc_multi_s(dim3 grid, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
-                                     float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
+                                     float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
 
 }  // namespace draco

@@ -20,8 +20,9 @@ namespace draco {
 
 template <int S, bool REAL, bool MULTI, bool FULL>
 __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__ G, int64_t ldg, int m,
-                                                       float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
-                                                       const double2* __restrict__ coef, int P, int64_t d) {
+                                                       float* __restrict__ Z, float* __restrict__ Zlo, int lo,
+                                                       int64_t ldm, const double2* __restrict__ coef, int P,
+                                                       int64_t d) {
     constexpr int R = 2 * S + 1;
     constexpr int U = 4;
     // unit gradients 0 .. 2s-1 of this lane's pair, parked for the wrap-around: the fp64 sums
@@ -105,8 +106,8 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
                     const float hr = (float)are[i], hi = (float)aim[i];
                     st2(Z + (int64_t)(n0 + i) * ldm + c0, make_float2(hr, hi));
                     if (Zlo != nullptr)   // second word of the wide wire: what the first rounding lost
-                        st2(Zlo + (int64_t)(n0 + i) * ldm + c0,
-                            make_float2((float)(are[i] - (double)hr), (float)(aim[i] - (double)hi)));
+                        st_lo2_rt(Zlo, (int64_t)(n0 + i) * ldm + c0,
+                                  make_float2((float)(are[i] - (double)hr), (float)(aim[i] - (double)hi)), lo);
                 }
             }
         }
@@ -187,16 +188,17 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
 template <int S, bool REAL, bool MULTI>
 __global__ __launch_bounds__(kBlock) void encode_cyc_narrow_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                    float* __restrict__ Z, float* __restrict__ Zlo,
-                                                                   int64_t ldm, const double2* __restrict__ coef,
-                                                                   int P, int64_t d) {
+                                                                   int lo, int64_t ldm,
+                                                                   const double2* __restrict__ coef, int P,
+                                                                   int64_t d) {
     // every lane of the workgroup has both floats of its pair inside the gradient
-    if ((int64_t)(blockIdx.x + 1) * (kBlock * 2) <= d) encode_cyc_narrow_body<S, REAL, MULTI, true>(G, ldg, m, Z, Zlo, ldm, coef, P, d);
-    else encode_cyc_narrow_body<S, REAL, MULTI, false>(G, ldg, m, Z, Zlo, ldm, coef, P, d);
+    if ((int64_t)(blockIdx.x + 1) * (kBlock * 2) <= d) encode_cyc_narrow_body<S, REAL, MULTI, true>(G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+    else encode_cyc_narrow_body<S, REAL, MULTI, false>(G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
 }
 
 // Launch for one s (defined in the translation unit of that s).
 template <int S>
 hipError_t launch_encode_cyc_narrow_s(bool real, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
-                                      float* Zlo, int64_t ldm, const double2* coef, int P, int64_t d);
+                                      float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
 
 }  // namespace draco

@@ -82,6 +82,79 @@ __device__ __forceinline__ void stx(float* p, float4 v, int n) {
     else st4_partial(p, v, n);
 }
 
+// --- second word of the two-word wire ------------------------------------------
+// A message of the two-word wire is hi + lo, hi = fp32(z) and lo the rounding residual
+// z - hi.  lo travels either as fp32 (kLoF32: the pair carries z to 48 bits) or as
+// bfloat16 (kLoBf16: 32 bits of z at 1.5 words per value); kLoNone is the one-word wire.
+// A bfloat16 slab has the element layout of the fp32 one (row stride ldm ELEMENTS, same
+// column index), so the kernels address both with the same offsets; the pointer is typed
+// float* either way and reinterpreted here.
+enum : int { kLoNone = 0, kLoF32 = kSecondWordF32, kLoBf16 = kSecondWordBf16 };
+typedef __bf16 vbf4 __attribute__((ext_vector_type(4)));
+typedef __bf16 vbf2 __attribute__((ext_vector_type(2)));
+
+template <bool FULL, int LO>
+__device__ __forceinline__ void st_lo(float* base, int64_t off, float4 v, int n) {
+    static_assert(LO == kLoF32 || LO == kLoBf16, "a second word has a format");
+    if constexpr (LO == kLoF32) {
+        stx<FULL>(base + off, v, n);
+    } else {
+        __bf16* p = reinterpret_cast<__bf16*>(base) + off;
+        vfloat4 w;
+        w.x = v.x;
+        w.y = v.y;
+        w.z = v.z;
+        w.w = v.w;
+        const vbf4 b = __builtin_convertvector(w, vbf4);   // round to nearest even
+        if constexpr (FULL) {
+            __builtin_nontemporal_store(b, reinterpret_cast<vbf4*>(p));
+        } else {
+            if (n > 0) p[0] = b.x;
+            if (n > 1) p[1] = b.y;
+            if (n > 2) p[2] = b.z;
+            if (n > 3) p[3] = b.w;
+        }
+    }
+}
+template <bool FULL, int LO>
+__device__ __forceinline__ float4 ld_lo(const float* base, int64_t off, int n) {
+    static_assert(LO == kLoF32 || LO == kLoBf16, "a second word has a format");
+    if constexpr (LO == kLoF32) {
+        return ldx<FULL>(base + off, n);
+    } else {
+        const __bf16* p = reinterpret_cast<const __bf16*>(base) + off;
+        if constexpr (FULL) {
+            const vbf4 b = __builtin_nontemporal_load(reinterpret_cast<const vbf4*>(p));
+            return make_float4((float)b.x, (float)b.y, (float)b.z, (float)b.w);
+        } else {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n > 0) v.x = (float)p[0];
+            if (n > 1) v.y = (float)p[1];
+            if (n > 2) v.z = (float)p[2];
+            if (n > 3) v.w = (float)p[3];
+            return v;
+        }
+    }
+}
+// The same with the format chosen at run time (kernels off the hot path).
+template <bool FULL>
+__device__ __forceinline__ void st_lo_rt(float* base, int64_t off, float4 v, int n, int lo) {
+    if (lo == kLoBf16) st_lo<FULL, kLoBf16>(base, off, v, n);
+    else st_lo<FULL, kLoF32>(base, off, v, n);
+}
+// Two values (one complex coordinate) of the second word.
+__device__ __forceinline__ void st_lo2_rt(float* base, int64_t off, float2 v, int lo) {
+    if (lo == kLoBf16) {
+        vfloat2 w;
+        w.x = v.x;
+        w.y = v.y;
+        __builtin_nontemporal_store(__builtin_convertvector(w, vbf2),
+                                    reinterpret_cast<vbf2*>(reinterpret_cast<__bf16*>(base) + off));
+    } else {
+        st2(base + off, v);
+    }
+}
+
 // --- workgroup footprint ------------------------------------------------------
 // Which 4 KiB of a row a workgroup touches.  Contiguous (SPREAD = false): workgroup t owns
 // floats [1024 t, 1024 t + 1024).  Spread: the row is cut into windows of 128 KiB; workgroup

@@ -33,6 +33,8 @@ constexpr double kTauH = 32.0 / 16777216.0;
 // The same for the two-word wire, whose messages carry 48 bits: clean syndromes sit
 // near 1e-14 (the fp64 projection's own rounding); 2^-36 leaves three decimal orders.
 constexpr double kTauHWide = 1.0 / 68719476736.0;
+// Two-word wire with a bfloat16 second word: 32 bits of the message, so 32 of ITS ulps.
+constexpr double kTauHBf16 = 32.0 / 8589934592.0;
 
 // phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns

@@ -46,13 +46,16 @@ hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint6
 // B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,
                                      int s, int64_t d, hipStream_t stream);
-hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int64_t ldm,
-                                     const double2* coef, int P, int s, int64_t d, hipStream_t stream);
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo,
+                                     int64_t ldm, const double2* coef, int P, int s, int64_t d, hipStream_t stream);
 
 // ---- cyclic code ----
 // coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
-// Zlo / zlo / Rlo below: second word of the wide wire (message = hi + lo), or nullptr.
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int64_t ldm,
+// Zlo / zlo / Rlo below: second word of the two-word wire (message = hi + lo), or nullptr;
+// lo names its format: kSecondWordF32 (a float slab) or kSecondWordBf16 (a bfloat16 slab with
+// the same row stride counted in ELEMENTS).  Ignored when the pointer is null.
+constexpr int kSecondWordF32 = 1, kSecondWordBf16 = 2;
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm,
                              const double2* coef, int P, int s, int64_t d, hipStream_t stream);
 // Unpacked wire: real gradients [P][d] in, messages of d complex entries (2d floats) out.
 hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
@@ -60,8 +63,8 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
 // Gn holds only the node's 2s+1 gradients, in assignment order.
 hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node,
                                        int P, int s, int64_t d, hipStream_t stream);
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, const double2* coef,
-                                  int node, int P, int s, int64_t d, hipStream_t stream);
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, int lo,
+                                  const double2* coef, int node, int P, int s, int64_t d, hipStream_t stream);
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
 int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
@@ -70,7 +73,7 @@ int64_t project_tiles(int64_t d);
 // f == nullptr: the entries of f are generated from f_seed (projection_rng.hpp).
 // d is the number of floats a message carries (odd d: one more, zero); realout (unpacked
 // wire, messages of d/2 complex entries): u receives only the real parts, d/2 floats.
-hipError_t launch_cyc_project(const float* R, const float* Rlo, int64_t ldm, const float* f,
+hipError_t launch_cyc_project(const float* R, const float* Rlo, int lo, int64_t ldm, const float* f,
                               uint64_t f_seed, double2* partial, double2* gamma, const double2* b0,
                               float* u, bool realout, int32_t* spec_state, int P, int64_t d,
                               hipStream_t stream);
@@ -83,7 +86,7 @@ hipError_t launch_cyc_locate(const double2* gamma, const double2* roots, int P, 
                              uint64_t* mask_out, int32_t* status_out, double2* b_out, int32_t* idx_out,
                              int32_t* nu_out, int32_t* spec_state, hipStream_t stream);
 // u <- unpack( sum_{q < *nu} b[q] * R[idx[q]] ); nu is read from device memory.
-hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int64_t ldm, const double2* b,
+hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int lo, int64_t ldm, const double2* b,
                                 const int32_t* idx, const int32_t* nu, const int32_t* spec_state, int P,
                                 float* u, bool realout, int64_t d, hipStream_t stream);
 

@@ -20,10 +20,14 @@ class Case:
     f  [ceil(d/2)] phi's random projection vector (cyclic code)
     """
 
-    def __init__(self, w: synth.Workload, device: str = "cuda:0", wide: bool = False, unpacked: bool = False):
-        """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word);
+    def __init__(self, w: synth.Workload, device: str = "cuda:0", wide=False, unpacked: bool = False):
+        """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word): True or
+        "f32" for a float32 second word, "bf16" for a bfloat16 one;
         unpacked: cyclic code with d complex entries per message (f then has d entries)."""
         self.w = w
+        assert wide in (False, True, "f32", "bf16")
+        self.lo_dtype = torch.bfloat16 if wide == "bf16" else torch.float32
+        wide = bool(wide)
         self.wide = wide
         self.unpacked = unpacked
         assert not ((wide or unpacked) and w.code != "cyc") and not (wide and unpacked)
@@ -32,13 +36,15 @@ class Case:
         self.plan = B.Plan(code, w.P, w.s, w.d)
         if unpacked:
             self.plan.set_wire(B.WIRE_UNPACKED)
+        if self.lo_dtype == torch.bfloat16:
+            self.plan.set_second_word(B.SECOND_WORD_BF16)
         self.mlen = self.plan.message_len
         self.ld_g = synth.padded_len(w.d)
         self.ld_m = synth.padded_len(self.mlen)
         self.G = synth.make_gradients(w.P * w.m, w.d, w.sigma, w.seed, device=self.device, ld=self.ld_g)
         self.Z = torch.zeros((w.P, self.ld_m), dtype=torch.float32, device=self.device)
         self.R = None
-        self.Zlo = torch.zeros_like(self.Z) if wide else None
+        self.Zlo = torch.zeros_like(self.Z, dtype=self.lo_dtype) if wide else None
         self.Rlo = None
         self.u = torch.zeros(synth.padded_len(w.d), dtype=torch.float32, device=self.device)
         self.f = None
