@@ -54,6 +54,9 @@ TAU_H = 32.0 * 2.0 ** -24   # syndromes with max|h_m| <= TAU_H * rho count as ze
 TAU_H_WIDE = 2.0 ** -36
 # And for a two-word wire whose second word is a bfloat16 (32 bits of the message): 32 of its ulps.
 TAU_H_BF16 = 32.0 * 2.0 ** -33
+# And for an 8-bit second word (a fixed-point residual in units of the first word's ulp, 2^-32 of
+# the message at worst): 32 of its ulps.
+TAU_H_I8 = 32.0 * 2.0 ** -32
 
 
 # --------------------------------------------------------------------------
@@ -303,15 +306,47 @@ def round_to_bfloat16(x: np.ndarray) -> np.ndarray:
     return np.where(np.isnan(x), x, out).astype(np.float32)
 
 
+def _ulp_exponent(hi: np.ndarray) -> np.ndarray:
+    """k with 2^k = the spacing of fp32 numbers at hi, from hi's exponent field E: k = max(E, 24) - 150
+    (fields below 24, numbers under 2^-103, share the spacing 2^-126: their residuals do not matter)."""
+    E = ((np.ascontiguousarray(hi, dtype=np.float32).view(np.uint32) >> 23) & 0xFF).astype(np.int64)
+    return np.maximum(E, 24) - 150
+
+
+def residual_code8(hi: np.ndarray, r: np.ndarray) -> np.ndarray:
+    """The rounding residual r = z - hi (|r| <= half the spacing u of fp32 numbers at hi) as an
+    8-bit fixed-point code: q = r / u * 254 rounded to the nearest integer, ties to even, so
+    q in [-127, 127]; 0 where hi is not finite.  The arithmetic is fp32, as the encoder kernels do
+    it: (fp32(r) * 2^-8 / u) * (254 * 2^8), the first product exact, the second rounded once."""
+    hi = np.ascontiguousarray(hi, dtype=np.float32)
+    r32 = np.asarray(r, dtype=np.float32)
+    k = _ulp_exponent(hi)
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = (r32 * np.ldexp(np.float32(1.0), (-8 - k).astype(np.int32)).astype(np.float32)) * np.float32(65024.0)
+        q = np.clip(np.rint(t), -127.0, 127.0)
+    q = np.where(np.isfinite(hi) & np.isfinite(q), q, 0.0)
+    return q.astype(np.int8)
+
+
+def residual_from_code8(hi: np.ndarray, q: np.ndarray) -> np.ndarray:
+    """What a code of residual_code8 stands for: q * u / 254 (fp64)."""
+    return np.asarray(q, dtype=np.float64) * np.ldexp(1.0, _ulp_exponent(hi)) / 254.0
+
+
 def two_word_wire(Z: np.ndarray, second: str = "f32"):
     """An fp64 message slab as two words per value: hi = fp32(z) and lo = the rounding
-    residual z - hi, itself rounded to fp32 ("f32") or to bfloat16 ("bf16").  Both fp32 arrays."""
+    residual z - hi, itself rounded to fp32 ("f32"), to bfloat16 ("bf16"), or to the 8-bit
+    code of residual_code8 ("i8").  Returns hi (fp32) and the VALUE the second word stands
+    for (fp32; fp64 for "i8", whose values need not be fp32 numbers)."""
     Z = np.asarray(Z, dtype=np.float64)
-    hi = Z.astype(np.float32)
+    with np.errstate(over="ignore"):
+        hi = Z.astype(np.float32)
     with np.errstate(invalid="ignore"):
         lo = (Z - hi.astype(np.float64)).astype(np.float32)
     if second == "bf16":
         lo = round_to_bfloat16(lo)
+    elif second == "i8":
+        lo = residual_from_code8(hi, residual_code8(hi, lo))
     elif second != "f32":
         raise ValueError(second)
     return hi, lo

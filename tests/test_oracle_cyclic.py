@@ -651,3 +651,72 @@ def test_bfloat16_threshold_sits_between_the_floors():
         gamma = o.project(o.wire_to_complex(R), f)
         floors.append(np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma)))
     assert floors[0] <= o.TAU_H_BF16 / 8 and 8 * o.TAU_H_BF16 <= floors[1], floors
+
+
+# ------------------------------------------ two-word wire with an 8-bit second word --
+def test_residual_code8_hand_values():
+    """hi = 1 (spacing 2^-23): a residual of a quarter spacing is code 63.5 -> 64 (tie to even),
+    half a spacing is 127, its negative -127, nothing is 0; hi = 6 (spacing 2^-21) scales alike;
+    a non-finite first word carries no residual."""
+    u1, u6 = 2.0 ** -23, 2.0 ** -21
+    hi = np.array([1.0, 1.0, 1.0, 1.0, 1.0, 6.0, 6.0, -6.0, np.inf, np.nan, 0.0, 1e-35], dtype=np.float32)
+    r = np.array([u1 / 4, u1 / 2, -u1 / 2, 0.0, u1 / 254, u6 / 254 * 10, -u6 / 254 * 100.4, u6 / 254 * 7,
+                  1.0, 1.0, 1e-50, 1e-43])
+    want = np.array([64, 127, -127, 0, 1, 10, -100, 7, 0, 0, 0, 0], dtype=np.int8)
+    got = o.residual_code8(hi, r)
+    assert got.dtype == np.int8 and np.array_equal(got, want), got
+    back = o.residual_from_code8(hi[:8], got[:8])
+    assert np.allclose(back, [64 * u1 / 254, u1 / 2, -u1 / 2, 0, u1 / 254, 10 * u6 / 254, -100 * u6 / 254, 7 * u6 / 254],
+                       rtol=1e-15, atol=0)
+
+
+def test_two_word_wire_with_code8_carries_32_bits():
+    """hi + lo within 1/508 of the spacing at hi -- at most 2^-23 |z| / 508, about 2^-32 |z| -- over
+    twelve decades; every code is used; powers of two, where the spacing changes, included."""
+    rng = np.random.default_rng(12)
+    z = rng.standard_normal(200_000) * 10.0 ** rng.uniform(-6, 6, 200_000)
+    z[:64] = np.ldexp(1.0, np.arange(-32, 32)) * (1 - 2.0 ** -26)        # just under a power of two: hi rounds up to it
+    hi, lo = o.two_word_wire(z, "i8")
+    assert hi.dtype == np.float32 and lo.dtype == np.float64
+    err = np.abs(hi.astype(np.float64) + lo - z)
+    assert (err <= 2.0 ** -23 / 508 * np.abs(z) * (1 + 1e-6)).all()
+    assert err.max() > 2.0 ** -36 * np.abs(z).min()
+    q = o.residual_code8(hi, z - hi.astype(np.float64))
+    assert q.min() == -127 and q.max() == 127 and len(np.unique(q)) == 255
+    # the code is the nearest one: no other code is closer to the residual
+    u = np.ldexp(1.0, o._ulp_exponent(hi))
+    assert (np.abs((z - hi.astype(np.float64)) / u * 254 - q) <= 0.5 + 1e-6).all()
+
+
+def test_code8_second_word_end_to_end_at_p45():
+    """(P, s) = (45, 3): the 5-byte wire leaves the decoded sum within a few 1e-6 of the true one,
+    two orders inside the 1e-4 reading of Definition 2 where one fp32 word is outside it; and at the
+    paper's (45, 5), where W grows to 1.8e5, still an order inside."""
+    for (P, s, bar) in ((45, 3, 5e-6), (45, 5, 2e-5)):
+        d = 20_000
+        G = _grads(P, d, 21, 1e-2)
+        ref = np.sum(G.astype(np.float64), axis=0)
+        Z = o.encode_cyclic(G, s)
+        f = _f(d // 2, 3)
+        hi, lo = o.two_word_wire(Z, "i8")
+        u, mask, st = o.decode_cyclic(hi.astype(np.float64) + lo, f, s, d, tau_h=o.TAU_H_I8)
+        assert st == o.OK and not mask.any()
+        e8 = np.linalg.norm(u - ref) / np.linalg.norm(ref)
+        u1, _, _ = o.decode_cyclic(Z.astype(np.float32), f, s, d)
+        e1 = np.linalg.norm(u1 - ref) / np.linalg.norm(ref)
+        assert e8 < bar < 1e-4 < e1, (P, s, e8, e1)
+        assert 50 < e1 / e8 < 1000, (e1, e8)
+
+
+def test_code8_threshold_sits_between_the_floors():
+    """Clean syndromes of the 5-byte wire against TAU_H_I8, as for the other wires."""
+    P, s, d = 45, 3, 40_000
+    G = _grads(P, d, 4, 1e-2)
+    Z = o.encode_cyclic(G, s)
+    hi, lo = o.two_word_wire(Z, "i8")
+    f = _f(d // 2, 8)
+    floors = []
+    for R in (hi.astype(np.float64) + lo, hi.astype(np.float64)):
+        gamma = o.project(o.wire_to_complex(R), f)
+        floors.append(np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma)))
+    assert floors[0] <= o.TAU_H_I8 / 8 and 4 * o.TAU_H_I8 <= floors[1], floors
