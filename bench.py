@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the DRACO encode/decode hot path on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--wire auto|one|wide16|wide|unpacked]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--wire auto|one|wide8|wide16|wide|unpacked]
 
 A step is one pass of the whole hot path over one batch of synthetic gradient
 slabs already resident in HBM: the encoder of all P nodes (G -> Z), then the
@@ -9,16 +9,17 @@ parameter-server decoder on the received messages R (Z with the workload's
 adversarial rows), through the synchronous C-ABI entry points (sum left on the
 device, mask and status on the host).  The headline workload is the largest
 one, the cyclic code at P = 45, s = 3, d = 25.6 M with full encode and decode,
-on the narrowest wire that meets the 1e-4 bar END TO END there (an fp32 word plus a
-bfloat16 word per float, 6 bytes: that leaves 4e-7; one fp32 word leaves 3e-4).  The metric is the benchmark contract's "decoded gradient
+on the narrowest wire that meets the 1e-4 bar END TO END there (an fp32 word plus an
+8-bit code of its rounding residual per float, 5 bytes: that leaves 1.2e-6; one fp32 word
+leaves 3e-4).  The metric is the benchmark contract's "decoded gradient
 GB/s consumed": P*d*4 bytes per step divided by the step time.
 
 One JSON line is printed.  Beside the headline it carries
   * `roofline`: the dominant kernel's algorithmic bytes over its HIP-event duration
     (events recorded by the library on the launch stream) against 8 TB/s;
   * `cpu_baseline`: the CPU oracle timed on a bounded sample on this machine's cores;
-  * `configs`: one record per benchmark configuration (and the headline's shape on two fp32
-    words and on one, and the paper-shaped row) with per-kernel avg / median / min, encode-only and decode-only
+  * `configs`: one record per benchmark configuration (and the headline's shape on the 6-byte,
+    8-byte and one-word wires, and the paper-shaped row) with per-kernel avg / median / min, encode-only and decode-only
     "consumed" GB/s, the end-to-end error against the true gradient sum, and the oracle's
     seconds.
 """
@@ -39,16 +40,16 @@ KIND_NAMES = ["encode", "vote", "project", "recombine", "locate"]
 KIND_KERNEL = {"encode": "encode_", "vote": "decode_rep", "project": "cyc_project_kernel", "recombine": "cyc_recombine"}
 TOL_END_TO_END = {"rep": 1e-5, "cyc": 1e-4}
 # two-word wires: format of the second word, and fp32 words per message float
-WIRE_SECOND = {"wide": "f32", "wide16": "bf16"}
-WIRE_WORDS = {"one": 1.0, "wide": 2.0, "wide16": 1.5, "unpacked": 1.0}
+WIRE_SECOND = {"wide": "f32", "wide16": "bf16", "wide8": "i8"}
+WIRE_WORDS = {"one": 1.0, "wide": 2.0, "wide16": 1.5, "wide8": 1.25, "unpacked": 1.0}
 WIRE_TEXT = {"one": "one fp32 word", "wide": "two fp32 words (hi+lo)", "wide16": "fp32 word + bfloat16 word (hi+lo)",
-             "unpacked": "unpacked complex, one word"}
+             "wide8": "fp32 word + 8-bit residual code (hi+lo)", "unpacked": "unpacked complex, one word"}
 
 
 def algorithmic_bytes(w, mlen, n_honest, words):
     """Bytes each kernel must move per launch (every input read once, every output written
     once); `words` = fp32 words per message float (2 on the wide wire, 1.5 with a bfloat16
-    second word); the encoder reads
+    second word, 1.25 with an 8-bit one); the encoder reads
     B = m*P per-sample rows."""
     P, d, h = w.P, w.d, mlen // 2   # h: complex entries per message = entries of f
     return {
@@ -133,7 +134,7 @@ def oracle_time(w, wire, budget_s, d_cap):
             elif unpacked:
                 _, mask, st, _ = o.decode_cyclic_unpacked(R.numpy(), f, ws.s)
             else:
-                _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s, tau_h={"wide": o.TAU_H_WIDE, "wide16": o.TAU_H_BF16}.get(wire, o.TAU_H))
+                _, mask, st = o.decode_cyclic(R.numpy(), f, ws.s, d_s, tau_h={"wide": o.TAU_H_WIDE, "wide16": o.TAU_H_BF16, "wide8": o.TAU_H_I8}.get(wire, o.TAU_H))
             t_dec += time.perf_counter() - t1
             assert st == 0 and sorted(np.flatnonzero(mask)) == sorted(j for j, _ in ws.adversaries())
         reps += 1
@@ -156,12 +157,12 @@ def oracle_time(w, wire, budget_s, d_cap):
 
 def pick_wire(w, wire):
     """auto: the narrowest wire that meets 1e-4 end to end -- one fp32 word, or, where the entries
-    of W reach 1e4 and more (from P = 32 on) and one word cannot, fp32 + bfloat16."""
+    of W reach 1e4 and more (from P = 32 on) and one word cannot, fp32 + an 8-bit residual code."""
     if w.code == "rep":
         return "one"
     if wire != "auto":
         return wire
-    return "wide16" if w.P >= 32 else "one"
+    return "wide8" if w.P >= 32 else "one"
 
 
 def stats(ms):
@@ -181,7 +182,7 @@ def measure(w, wire, steps, warmup, headline):
     wide, unpacked = wire in WIRE_SECOND, wire == "unpacked"
     words = WIRE_WORDS[wire]
     c = Case(w, "cuda:0", wide=WIRE_SECOND.get(wire, False), unpacked=unpacked)
-    name = w.name + {"one": "+one_word_wire", "wide": "+wide_wire", "wide16": "+wide16_wire",
+    name = w.name + {"one": "+one_word_wire", "wide": "+wide_wire", "wide16": "+wide16_wire", "wide8": "+wide8_wire",
                      "unpacked": "+unpacked_wire"}[wire] \
         if (w.code == "cyc" and wire != pick_wire(w, "auto")) else w.name
     rec = {"workload": name, "code": w.code, "P": w.P, "s": w.s, "d": w.d, "B": w.P * w.m,
@@ -297,7 +298,7 @@ def main():
     ap.add_argument("--config", type=int, default=4,
                     help="headline workload: index into the benchmark's configurations (default 4: cyclic, P=45, "
                          "s=3, d=25.6M, encode+decode); 5 = the paper-shaped row (P=45, s=5, B=180)")
-    ap.add_argument("--wire", choices=["auto", "one", "wide", "wide16", "unpacked"], default="auto",
+    ap.add_argument("--wire", choices=["auto", "one", "wide", "wide16", "wide8", "unpacked"], default="auto",
                     help="cyclic message format (auto: two words where one cannot meet 1e-4 end to end)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration records")
@@ -351,9 +352,10 @@ def main():
         out["cpu_baseline"] = oracle_time(w, wire, 10.0, 8_000_000 if w.code == "cyc" else 16_000_000)
 
     if not args.no_configs:
-        # every benchmark configuration on its default wire, then the headline's shape on two fp32
-        # words and on one (reported: out of tolerance end to end), then the paper-shaped row
-        plan = [(i, "auto") for i in range(5)] + [(4, "wide"), (4, "one"), (5, "auto")]
+        # every benchmark configuration on its default wire, then the headline's shape with a bfloat16
+        # and an fp32 second word and on one word (reported: out of tolerance end to end), then the
+        # paper-shaped row
+        plan = [(i, "auto") for i in range(5)] + [(4, "wide16"), (4, "wide"), (4, "one"), (5, "auto")]
         recs = []
         for i, wr in plan:
             wi = synth.WORKLOADS[i]

@@ -106,11 +106,20 @@ int draco_plan_set_wire(draco_plan* plan, int wire);
  * every pass over the messages moves a quarter fewer bytes.  messages_lo_dev
  * then points at [P][ld_m] 16-bit values: SAME ld_m and column index as the
  * first word, counted in elements, so its rows are half as long in bytes.
+ * DRACO_SECOND_WORD_I8: lo is an 8-bit signed code q of the residual in units
+ * of the spacing u of fp32 numbers at hi: with E the exponent field of hi,
+ * u = 2^(max(E, 24) - 150), q = (z - hi) / u * 254 rounded to nearest even,
+ * -127 <= q <= 127 (0 where hi is not finite); it stands for q * u / 254.
+ * hi + lo is within u / 508 <= 2^-32 |z| of z at 5 bytes per value: the
+ * decoded sum stays within about 1e-6 of the true one at (P, s) = (45, 3)
+ * and 5e-6 at (45, 5).  messages_lo_dev then points at [P][ld_m] bytes,
+ * same ld_m and column index, rows a quarter as long in bytes.
  * May be changed at any time; encoder and decoder must agree.  DRACO_EINVAL
  * for the repetition code, the unpacked wire, or an unknown value. */
 enum {
     DRACO_SECOND_WORD_F32 = 0,
-    DRACO_SECOND_WORD_BF16 = 1
+    DRACO_SECOND_WORD_BF16 = 1,
+    DRACO_SECOND_WORD_I8 = 2
 };
 int draco_plan_set_second_word(draco_plan* plan, int format);
 
@@ -303,7 +312,8 @@ int draco_decode_cyclic_hostphi(draco_plan* plan, const float* messages_dev, int
  * counts a syndrome as zero below DRACO_TAU_WIDE (instead of DRACO_TAU) times
  * the median projection: the wide wire's clean syndromes sit near 1e-14, so
  * much smaller lies can be told from rounding.  With a bfloat16 second word
- * (draco_plan_set_second_word) the threshold is DRACO_TAU_BF16. */
+ * (draco_plan_set_second_word) the threshold is DRACO_TAU_BF16, with an 8-bit
+ * one DRACO_TAU_I8. */
 int draco_decode_cyclic_wide(draco_plan* plan, const float* messages_hi_dev,
                              const void* messages_lo_dev, int64_t ld_m, const float* f_dev,
                              float* sum_dev, uint64_t* mask_host, void* stream);
@@ -322,10 +332,11 @@ int draco_cyclic_locate(const draco_plan* plan, const double* gamma_host,
                         uint64_t* mask_host, double* t_host);
 /* Same with the relative zero threshold of the syndromes given (0 < tau < 1):
  * DRACO_TAU is what the one-word decoders use, DRACO_TAU_WIDE the wide ones,
- * DRACO_TAU_BF16 the wide ones with a bfloat16 second word. */
+ * DRACO_TAU_BF16 / DRACO_TAU_I8 the wide ones with a bfloat16 / 8-bit second word. */
 #define DRACO_TAU (32.0 / 16777216.0)        /* 32 ulps of an fp32 wire */
 #define DRACO_TAU_WIDE (1.0 / 68719476736.0) /* 2^-36 */
 #define DRACO_TAU_BF16 (32.0 / 8589934592.0) /* 32 ulps of the 32-bit fp32 + bfloat16 wire */
+#define DRACO_TAU_I8 (32.0 / 4294967296.0)   /* 32 ulps of the fp32 + 8-bit wire */
 int draco_cyclic_locate_tol(const draco_plan* plan, const double* gamma_host, double tau,
                             uint64_t* mask_host, double* t_host);
 

@@ -31,8 +31,8 @@ BUILD_DIR = os.path.join(_HERE, "_build")
 
 CODE_REPETITION, CODE_CYCLIC = 0, 1
 WIRE_PACKED, WIRE_UNPACKED = 0, 1
-TAU, TAU_WIDE, TAU_BF16 = 32.0 / 16777216.0, 1.0 / 68719476736.0, 32.0 / 8589934592.0
-SECOND_WORD_F32, SECOND_WORD_BF16 = 0, 1
+TAU, TAU_WIDE, TAU_BF16, TAU_I8 = 32.0 / 16777216.0, 1.0 / 68719476736.0, 32.0 / 8589934592.0, 32.0 / 4294967296.0
+SECOND_WORD_F32, SECOND_WORD_BF16, SECOND_WORD_I8 = 0, 1, 2
 OK, NO_MAJORITY, LOCATE_FAILED = 0, 1, 2
 EINVAL, EALIGN, EHIP, ENOMEM = -1, -2, -3, -4
 KIND_ENCODE, KIND_VOTE, KIND_PROJECT, KIND_RECOMBINE, KIND_LOCATE = 0, 1, 2, 3, 4
@@ -366,13 +366,14 @@ class Plan:
         _check(lib().draco_plan_set_wire(self._h, wire))
 
     def set_second_word(self, fmt: int) -> None:
-        """Two-word wire: SECOND_WORD_F32 (float32 slab) or SECOND_WORD_BF16 (bfloat16 slab, same shape)."""
+        """Two-word wire: SECOND_WORD_F32 (float32 slab), SECOND_WORD_BF16 (bfloat16 slab) or
+        SECOND_WORD_I8 (int8 slab), all of the first word's shape."""
         _check(lib().draco_plan_set_second_word(self._h, fmt))
         self._second_word = fmt
 
     def _check_lo(self, hi, lo) -> None:
         """The second slab has the first one's row stride in elements and the plan's element type."""
-        want = "torch.bfloat16" if self._second_word == SECOND_WORD_BF16 else "torch.float32"
+        want = {SECOND_WORD_BF16: "torch.bfloat16", SECOND_WORD_I8: "torch.int8"}.get(self._second_word, "torch.float32")
         assert hi.stride(0) == lo.stride(0) and str(lo.dtype) == want, (lo.dtype, want)
 
     def set_projection_seed(self, seed: int) -> None:

@@ -82,11 +82,13 @@ bool unpacked(const draco_plan* p) { return p->wire == DRACO_WIRE_UNPACKED; }
 
 // Second-word format as the launchers name it, and the locator's zero threshold for a wire.
 int lo_format(const draco_plan* p) {
-    return p->second_word == DRACO_SECOND_WORD_BF16 ? kSecondWordBf16 : kSecondWordF32;
+    return p->second_word == DRACO_SECOND_WORD_BF16 ? kSecondWordBf16
+           : p->second_word == DRACO_SECOND_WORD_I8 ? kSecondWordI8 : kSecondWordF32;
 }
 double tau_of(const draco_plan* p, bool wide) {
     if (!wide) return kTauH;
-    return p->second_word == DRACO_SECOND_WORD_BF16 ? kTauHBf16 : kTauHWide;
+    return p->second_word == DRACO_SECOND_WORD_BF16 ? kTauHBf16
+           : p->second_word == DRACO_SECOND_WORD_I8 ? kTauHI8 : kTauHWide;
 }
 
 int64_t message_len(const draco_plan* p) {
@@ -652,7 +654,8 @@ int draco_plan_set_wire(draco_plan* p, int wire) {
 
 int draco_plan_set_second_word(draco_plan* p, int format) {
     if (p == nullptr || p->code != DRACO_CODE_CYCLIC || unpacked(p)) return DRACO_EINVAL;
-    if (format != DRACO_SECOND_WORD_F32 && format != DRACO_SECOND_WORD_BF16) return DRACO_EINVAL;
+    if (format != DRACO_SECOND_WORD_F32 && format != DRACO_SECOND_WORD_BF16 && format != DRACO_SECOND_WORD_I8)
+        return DRACO_EINVAL;
     p->second_word = format;
     return DRACO_OK;
 }

@@ -60,7 +60,7 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
         double xr0[K], xi0[K], xr1[K], xi1[K];  // the wire values in fp64 (hi + lo is exact)
         if constexpr (LO != kLoNone) {
             const int64_t rowl = (int64_t)j * ldm + q0 * 4;
-            float4 xl[K];
+            lo_raw_t<LO> xl[K];
             if (tile_full) {
 #pragma unroll
                 for (int k = 0; k < K; ++k) xl[k] = ld_lo<true, LO>(Rlo, rowl + (int64_t)k * kBlock * 4, 4);
@@ -70,10 +70,11 @@ __device__ __forceinline__ void cyc_project_body(const float* __restrict__ Rm, c
             }
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                xr0[k] = (double)x[k].x + (double)xl[k].x;
-                xi0[k] = (double)x[k].y + (double)xl[k].y;
-                xr1[k] = (double)x[k].z + (double)xl[k].z;
-                xi1[k] = (double)x[k].w + (double)xl[k].w;
+                const float4 l = lo_values<LO>(xl[k], x[k]);
+                xr0[k] = (double)x[k].x + (double)l.x;
+                xi0[k] = (double)x[k].y + (double)l.y;
+                xr1[k] = (double)x[k].z + (double)l.z;
+                xi1[k] = (double)x[k].w + (double)l.w;
             }
         } else {
 #pragma unroll
@@ -197,7 +198,8 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
     const int nout = FULL ? 4 : clamp4(d - c0);
     double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
     for (int q0 = 0; q0 < nu; q0 += UN) {
-        float4 x[UN], xl[LO != kLoNone ? UN : 1];
+        float4 x[UN];
+        lo_raw_t<LO> xl[LO != kLoNone ? UN : 1];
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
             if (q0 + i < nu) {
@@ -210,8 +212,9 @@ __device__ __forceinline__ void cyc_recombine_body(const float* __restrict__ Rm,
             if (q0 + i < nu) {
                 const double br = b[q0 + i].x, bi = b[q0 + i].y;
                 if constexpr (LO != kLoNone) {
-                    cmac(br, bi, (double)x[i].x + (double)xl[i].x, (double)x[i].y + (double)xl[i].y, are0, aim0);
-                    cmac(br, bi, (double)x[i].z + (double)xl[i].z, (double)x[i].w + (double)xl[i].w, are1, aim1);
+                    const float4 l = lo_values<LO>(xl[i], x[i]);
+                    cmac(br, bi, (double)x[i].x + (double)l.x, (double)x[i].y + (double)l.y, are0, aim0);
+                    cmac(br, bi, (double)x[i].z + (double)l.z, (double)x[i].w + (double)l.w, are1, aim1);
                 } else {
                     cmac(br, bi, (double)x[i].x, (double)x[i].y, are0, aim0);
                     cmac(br, bi, (double)x[i].z, (double)x[i].w, are1, aim1);
@@ -277,6 +280,9 @@ hipError_t launch_cyc_project(const float* R, const float* Rlo, int lo, int64_t 
     else if (lo == kLoBf16)
         hipLaunchKernelGGL(cyc_project_kernel<kLoBf16>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
                            f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
+    else if (lo == kLoI8)
+        hipLaunchKernelGGL(cyc_project_kernel<kLoI8>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
+                           f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
     else
         hipLaunchKernelGGL(cyc_project_kernel<kLoF32>, dim3((unsigned)tiles), dim3(kBlock), 0, stream, R, Rlo, ldm, f,
                            f_seed, partial, b0, u, realout ? 1 : 0, spec_state, P, d);
@@ -307,6 +313,10 @@ hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int lo, int64_
         // at 0.82 of the HBM peak at (P, s, d) = (45, 3, 25.6 M), two at 0.69-0.76
         allow_large_lds<cyc_recombine_kernel<kLoBf16, kRecombineRowsBf16>>();
         hipLaunchKernelGGL((cyc_recombine_kernel<kLoBf16, kRecombineRowsBf16>), grid, block, throttle_lds(4, 0, 0), stream,
+                           R, Rlo, ldm, b, idx, nu, spec_state, P, u, realout ? 1 : 0, d);
+    } else if (lo == kLoI8) {
+        allow_large_lds<cyc_recombine_kernel<kLoI8, kRecombineRowsBf16>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<kLoI8, kRecombineRowsBf16>), grid, block, throttle_lds(4, 0, 0), stream,
                            R, Rlo, ldm, b, idx, nu, spec_state, P, u, realout ? 1 : 0, d);
     } else {
         allow_large_lds<cyc_recombine_kernel<kLoF32, kRecombineRowsWide>>();

@@ -62,8 +62,8 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
     if (zlo != nullptr) {
         const float4 lo4 = make_float4((float)(are0 - (double)out.x), (float)(aim0 - (double)out.y),
                                        (float)(are1 - (double)out.z), (float)(aim1 - (double)out.w));
-        if (nout == 4) st_lo_rt<true>(zlo, lo_off + c0, lo4, nout, lo);
-        else st_lo_rt<false>(zlo, lo_off + c0, lo4, nout, lo);
+        if (nout == 4) st_lo_rt<true>(zlo, lo_off + c0, out, lo4, nout, lo);
+        else st_lo_rt<false>(zlo, lo_off + c0, out, lo4, nout, lo);
     }
 }
 
@@ -117,7 +117,7 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
                 if (Zlo != nullptr) {
                     const float4 lo4 = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                    (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    st_lo_rt<FULL>(Zlo, (int64_t)n * ldm + c0, lo4, nout, lo);
+                    st_lo_rt<FULL>(Zlo, (int64_t)n * ldm + c0, hi, lo4, nout, lo);
                 }
                 if (++first == r) first = 0;
                 if (++last == r) last = 0;

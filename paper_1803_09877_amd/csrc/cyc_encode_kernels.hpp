@@ -66,7 +66,7 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
                 if constexpr (LO != kLoNone) {  // second word of the wide wire: what the first rounding lost
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, hi, lo, nout);
                 }
             }
         }
@@ -393,7 +393,7 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
                 if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, hi, lo, nout);
                 }
             }
         }
@@ -492,7 +492,7 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
                 if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, hi, lo, nout);
                 }
             }
         }
@@ -578,7 +578,7 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
                 if constexpr (LO != kLoNone) {
                     const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
                                                   (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
-                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, lo, nout);
+                    st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + c0, hi, lo, nout);
                 }
             }
         }

@@ -106,7 +106,7 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
                     const float hr = (float)are[i], hi = (float)aim[i];
                     st2(Z + (int64_t)(n0 + i) * ldm + c0, make_float2(hr, hi));
                     if (Zlo != nullptr)   // second word of the wide wire: what the first rounding lost
-                        st_lo2_rt(Zlo, (int64_t)(n0 + i) * ldm + c0,
+                        st_lo2_rt(Zlo, (int64_t)(n0 + i) * ldm + c0, make_float2(hr, hi),
                                   make_float2((float)(are[i] - (double)hr), (float)(aim[i] - (double)hi)), lo);
                 }
             }

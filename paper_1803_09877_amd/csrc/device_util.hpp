@@ -84,21 +84,47 @@ __device__ __forceinline__ void stx(float* p, float4 v, int n) {
 
 // --- second word of the two-word wire ------------------------------------------
 // A message of the two-word wire is hi + lo, hi = fp32(z) and lo the rounding residual
-// z - hi.  lo travels either as fp32 (kLoF32: the pair carries z to 48 bits) or as
-// bfloat16 (kLoBf16: 32 bits of z at 1.5 words per value); kLoNone is the one-word wire.
-// A bfloat16 slab has the element layout of the fp32 one (row stride ldm ELEMENTS, same
-// column index), so the kernels address both with the same offsets; the pointer is typed
-// float* either way and reinterpreted here.
-enum : int { kLoNone = 0, kLoF32 = kSecondWordF32, kLoBf16 = kSecondWordBf16 };
+// z - hi.  lo travels as fp32 (kLoF32: the pair carries z to 48 bits), as bfloat16
+// (kLoBf16: 32 bits of z at 1.5 words per value), or as an 8-bit fixed-point code in
+// units of hi's spacing (kLoI8: 32 bits at 1.25 words); kLoNone is the one-word wire.
+// A second-word slab has the element layout of the fp32 one (row stride ldm ELEMENTS,
+// same column index), so the kernels address both with the same offsets; the pointer is
+// typed float* either way and reinterpreted here.
+enum : int { kLoNone = 0, kLoF32 = kSecondWordF32, kLoBf16 = kSecondWordBf16, kLoI8 = kSecondWordI8 };
 typedef __bf16 vbf4 __attribute__((ext_vector_type(4)));
 typedef __bf16 vbf2 __attribute__((ext_vector_type(2)));
 
+// The 8-bit code.  With E the exponent field of hi, u = 2^(max(E, 24) - 150) is the spacing of
+// fp32 numbers at hi (numbers below 2^-103 share the spacing 2^-126: their residuals do not
+// matter) and |z - hi| <= u / 2.  Code q = rint(lo / u * 254) in [-127, 127], computed in fp32:
+// lo * 254 rounds once, the scaling by 1 / u is exact.  Value of a code: q * u / 254.  Next to a
+// non-finite hi the code is arbitrary (hi + anything stays non-finite).
+__device__ __forceinline__ int lo8_field(float hi) {
+    const int e = (int)((__float_as_uint(hi) >> 23) & 0xFFu);
+    return e < 24 ? 24 : e;
+}
+// The code in the low byte of the result (upper bytes: junk).  Adding 1.5 * 2^23 rounds to the
+// nearest integer, ties to even, and leaves it in the low mantissa bits in two's complement.
+__device__ __forceinline__ unsigned lo8_code(float hi, float lo) {
+    const float t = ldexpf(lo * 254.0f, 150 - lo8_field(hi));
+    return __float_as_uint(t + 12582912.0f);
+}
+__device__ __forceinline__ float lo8_value(float hi, int q) {
+    return ldexpf((float)q * (1.0f / 254.0f), lo8_field(hi) - 150);
+}
+
+// What one lane holds of the second word for its 4 values, as loaded.
+template <int LO> struct lo_raw { typedef float4 type; };
+template <> struct lo_raw<kLoBf16> { typedef vbf4 type; };
+template <> struct lo_raw<kLoI8> { typedef unsigned type; };
+template <int LO> using lo_raw_t = typename lo_raw<LO>::type;
+
 template <bool FULL, int LO>
-__device__ __forceinline__ void st_lo(float* base, int64_t off, float4 v, int n) {
-    static_assert(LO == kLoF32 || LO == kLoBf16, "a second word has a format");
+__device__ __forceinline__ void st_lo(float* base, int64_t off, float4 hi, float4 v, int n) {
+    static_assert(LO == kLoF32 || LO == kLoBf16 || LO == kLoI8, "a second word has a format");
     if constexpr (LO == kLoF32) {
         stx<FULL>(base + off, v, n);
-    } else {
+    } else if constexpr (LO == kLoBf16) {
         __bf16* p = reinterpret_cast<__bf16*>(base) + off;
         vfloat4 w;
         w.x = v.x;
@@ -114,42 +140,84 @@ __device__ __forceinline__ void st_lo(float* base, int64_t off, float4 v, int n)
             if (n > 2) p[2] = b.z;
             if (n > 3) p[3] = b.w;
         }
-    }
-}
-template <bool FULL, int LO>
-__device__ __forceinline__ float4 ld_lo(const float* base, int64_t off, int n) {
-    static_assert(LO == kLoF32 || LO == kLoBf16, "a second word has a format");
-    if constexpr (LO == kLoF32) {
-        return ldx<FULL>(base + off, n);
     } else {
-        const __bf16* p = reinterpret_cast<const __bf16*>(base) + off;
+        signed char* p = reinterpret_cast<signed char*>(base) + off;
+        const unsigned q0 = lo8_code(hi.x, v.x), q1 = lo8_code(hi.y, v.y), q2 = lo8_code(hi.z, v.z),
+                       q3 = lo8_code(hi.w, v.w);
         if constexpr (FULL) {
-            const vbf4 b = __builtin_nontemporal_load(reinterpret_cast<const vbf4*>(p));
-            return make_float4((float)b.x, (float)b.y, (float)b.z, (float)b.w);
+            const unsigned w = (q0 & 0xFFu) | ((q1 & 0xFFu) << 8) | ((q2 & 0xFFu) << 16) | (q3 << 24);
+            __builtin_nontemporal_store(w, reinterpret_cast<unsigned*>(p));
         } else {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n > 0) v.x = (float)p[0];
-            if (n > 1) v.y = (float)p[1];
-            if (n > 2) v.z = (float)p[2];
-            if (n > 3) v.w = (float)p[3];
-            return v;
+            if (n > 0) p[0] = (signed char)q0;
+            if (n > 1) p[1] = (signed char)q1;
+            if (n > 2) p[2] = (signed char)q2;
+            if (n > 3) p[3] = (signed char)q3;
         }
     }
 }
-// The same with the format chosen at run time (kernels off the hot path).
+// Load of a lane's 4 second words, unconverted (missing ones read as zero).
+template <bool FULL, int LO>
+__device__ __forceinline__ lo_raw_t<LO> ld_lo(const float* base, int64_t off, int n) {
+    static_assert(LO == kLoF32 || LO == kLoBf16 || LO == kLoI8, "a second word has a format");
+    if constexpr (LO == kLoF32) {
+        return ldx<FULL>(base + off, n);
+    } else if constexpr (LO == kLoBf16) {
+        const __bf16* p = reinterpret_cast<const __bf16*>(base) + off;
+        if constexpr (FULL) {
+            return __builtin_nontemporal_load(reinterpret_cast<const vbf4*>(p));
+        } else {
+            vbf4 b = {(__bf16)0.0f, (__bf16)0.0f, (__bf16)0.0f, (__bf16)0.0f};
+            if (n > 0) b.x = p[0];
+            if (n > 1) b.y = p[1];
+            if (n > 2) b.z = p[2];
+            if (n > 3) b.w = p[3];
+            return b;
+        }
+    } else {
+        const unsigned char* p = reinterpret_cast<const unsigned char*>(base) + off;
+        if constexpr (FULL) {
+            return __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(p));
+        } else {
+            unsigned w = 0;
+            if (n > 0) w |= (unsigned)p[0];
+            if (n > 1) w |= (unsigned)p[1] << 8;
+            if (n > 2) w |= (unsigned)p[2] << 16;
+            if (n > 3) w |= (unsigned)p[3] << 24;
+            return w;
+        }
+    }
+}
+// The values a lane's 4 second words stand for, next to their first words.
+template <int LO>
+__device__ __forceinline__ float4 lo_values(lo_raw_t<LO> raw, float4 hi) {
+    if constexpr (LO == kLoF32) {
+        return raw;
+    } else if constexpr (LO == kLoBf16) {
+        return make_float4((float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w);
+    } else {
+        const int w = (int)raw;
+        return make_float4(lo8_value(hi.x, (w << 24) >> 24), lo8_value(hi.y, (w << 16) >> 24),
+                           lo8_value(hi.z, (w << 8) >> 24), lo8_value(hi.w, w >> 24));
+    }
+}
+// Stores with the format chosen at run time (kernels off the hot path).
 template <bool FULL>
-__device__ __forceinline__ void st_lo_rt(float* base, int64_t off, float4 v, int n, int lo) {
-    if (lo == kLoBf16) st_lo<FULL, kLoBf16>(base, off, v, n);
-    else st_lo<FULL, kLoF32>(base, off, v, n);
+__device__ __forceinline__ void st_lo_rt(float* base, int64_t off, float4 hi, float4 v, int n, int lo) {
+    if (lo == kLoBf16) st_lo<FULL, kLoBf16>(base, off, hi, v, n);
+    else if (lo == kLoI8) st_lo<FULL, kLoI8>(base, off, hi, v, n);
+    else st_lo<FULL, kLoF32>(base, off, hi, v, n);
 }
 // Two values (one complex coordinate) of the second word.
-__device__ __forceinline__ void st_lo2_rt(float* base, int64_t off, float2 v, int lo) {
+__device__ __forceinline__ void st_lo2_rt(float* base, int64_t off, float2 hi, float2 v, int lo) {
     if (lo == kLoBf16) {
         vfloat2 w;
         w.x = v.x;
         w.y = v.y;
         __builtin_nontemporal_store(__builtin_convertvector(w, vbf2),
                                     reinterpret_cast<vbf2*>(reinterpret_cast<__bf16*>(base) + off));
+    } else if (lo == kLoI8) {
+        const unsigned short w = (unsigned short)((lo8_code(hi.x, v.x) & 0xFFu) | ((lo8_code(hi.y, v.y) & 0xFFu) << 8));
+        __builtin_nontemporal_store(w, reinterpret_cast<unsigned short*>(reinterpret_cast<signed char*>(base) + off));
     } else {
         st2(base + off, v);
     }

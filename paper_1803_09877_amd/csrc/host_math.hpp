@@ -35,6 +35,8 @@ constexpr double kTauH = 32.0 / 16777216.0;
 constexpr double kTauHWide = 1.0 / 68719476736.0;
 // Two-word wire with a bfloat16 second word: 32 bits of the message, so 32 of ITS ulps.
 constexpr double kTauHBf16 = 32.0 / 8589934592.0;
+// And with an 8-bit second word (the residual in 254ths of the first word's spacing).
+constexpr double kTauHI8 = 32.0 / 4294967296.0;
 
 // phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns

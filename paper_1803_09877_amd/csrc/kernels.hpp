@@ -52,9 +52,10 @@ hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* 
 // ---- cyclic code ----
 // coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
 // Zlo / zlo / Rlo below: second word of the two-word wire (message = hi + lo), or nullptr;
-// lo names its format: kSecondWordF32 (a float slab) or kSecondWordBf16 (a bfloat16 slab with
-// the same row stride counted in ELEMENTS).  Ignored when the pointer is null.
-constexpr int kSecondWordF32 = 1, kSecondWordBf16 = 2;
+// lo names its format: kSecondWordF32 (a float slab), kSecondWordBf16 (a bfloat16 slab) or
+// kSecondWordI8 (a slab of 8-bit residual codes), each with the same row stride counted in
+// ELEMENTS.  Ignored when the pointer is null.
+constexpr int kSecondWordF32 = 1, kSecondWordBf16 = 2, kSecondWordI8 = 3;
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm,
                              const double2* coef, int P, int s, int64_t d, hipStream_t stream);
 // Unpacked wire: real gradients [P][d] in, messages of d complex entries (2d floats) out.

@@ -22,11 +22,11 @@ class Case:
 
     def __init__(self, w: synth.Workload, device: str = "cuda:0", wide=False, unpacked: bool = False):
         """wide: cyclic code with the two-word wire (Zlo / Rlo hold the second word): True or
-        "f32" for a float32 second word, "bf16" for a bfloat16 one;
+        "f32" for a float32 second word, "bf16" for a bfloat16 one, "i8" for an 8-bit residual code;
         unpacked: cyclic code with d complex entries per message (f then has d entries)."""
         self.w = w
-        assert wide in (False, True, "f32", "bf16")
-        self.lo_dtype = torch.bfloat16 if wide == "bf16" else torch.float32
+        assert wide in (False, True, "f32", "bf16", "i8")
+        self.lo_dtype = {"bf16": torch.bfloat16, "i8": torch.int8}.get(wide, torch.float32)
         wide = bool(wide)
         self.wide = wide
         self.unpacked = unpacked
@@ -36,8 +36,8 @@ class Case:
         self.plan = B.Plan(code, w.P, w.s, w.d)
         if unpacked:
             self.plan.set_wire(B.WIRE_UNPACKED)
-        if self.lo_dtype == torch.bfloat16:
-            self.plan.set_second_word(B.SECOND_WORD_BF16)
+        if self.lo_dtype != torch.float32:
+            self.plan.set_second_word(B.SECOND_WORD_BF16 if self.lo_dtype == torch.bfloat16 else B.SECOND_WORD_I8)
         self.mlen = self.plan.message_len
         self.ld_g = synth.padded_len(w.d)
         self.ld_m = synth.padded_len(self.mlen)

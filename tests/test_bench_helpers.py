@@ -28,19 +28,22 @@ def test_algorithmic_bytes_count_every_input_and_output_once():
     assert bench.algorithmic_bytes(paper, mlen, paper.P - 5, 2)["encode"] == (4 + 2) * slab
     half = bench.algorithmic_bytes(w, mlen, w.P - 3, 1.5)                       # fp32 word + bfloat16 word
     assert half["encode"] == 2 * slab + slab // 2 and half["project"] == slab + slab // 2 + (mlen // 2) * 4
-    assert all(isinstance(v, int) for v in half.values())
+    quarter = bench.algorithmic_bytes(w, mlen, w.P - 3, 1.25)                   # fp32 word + 8-bit code
+    assert quarter["encode"] == 2 * slab + slab // 4 and quarter["recombine"] == (w.P - 3) * w.d * 5 + w.d * 4
+    assert all(isinstance(v, int) for v in list(half.values()) + list(quarter.values()))
 
 
 def test_wire_choice_follows_the_end_to_end_tolerance():
     assert bench.pick_wire(synth.WORKLOADS[1], "auto") == "one"               # repetition: plain fp32
     assert bench.pick_wire(synth.WORKLOADS[2], "auto") == "one"               # P = 15: one word meets 1e-4
-    assert bench.pick_wire(synth.WORKLOADS[4], "auto") == "wide16"            # P = 45: it does not; 6 bytes do
+    assert bench.pick_wire(synth.WORKLOADS[4], "auto") == "wide8"             # P = 45: it does not; 5 bytes do
     assert bench.pick_wire(synth.WORKLOADS[4], "one") == "one"
 
 
 @pytest.mark.parametrize("workload,kind,idx,words", [
-    ("cyc_P45_s3_d25.6M", "encode", 4, 1.5), ("cyc_P45_s3_d25.6M", "project", 4, 1.5),
-    ("cyc_P45_s3_d25.6M", "recombine", 4, 1.5), ("cyc_P45_s3_d25.6M+wide_wire", "encode", 4, 2),
+    ("cyc_P45_s3_d25.6M", "encode", 4, 1.25), ("cyc_P45_s3_d25.6M", "project", 4, 1.25),
+    ("cyc_P45_s3_d25.6M", "recombine", 4, 1.25), ("cyc_P45_s3_d25.6M+wide16_wire", "encode", 4, 1.5),
+    ("cyc_P45_s3_d25.6M+wide_wire", "encode", 4, 2),
     ("cyc_P45_s3_d25.6M+one_word_wire", "encode", 4, 1), ("rep_P45_s2_d11.2M", "vote", 1, 1),
 ])
 def test_traffic_is_read_from_the_committed_profile(workload, kind, idx, words):

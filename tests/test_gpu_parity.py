@@ -48,6 +48,17 @@ def assert_sum_close(ug, uo, tol, what):
     assert max_abs_err(ug, uo) <= bound, (what, max_abs_err(ug, uo), bound)
 
 
+WIDE = {"f32": (48, o.TAU_H_WIDE), "bf16": (33, o.TAU_H_BF16), "i8": (31.98, o.TAU_H_I8)}   # bits carried, threshold
+
+
+def second_word_values(hi, lo, second):
+    """fp64 values of a second-word slab (torch) next to its first words (numpy fp32): the stored
+    number itself, or what an 8-bit code stands for at that first word."""
+    if second == "i8":
+        return o.residual_from_code8(hi, lo.cpu().numpy())
+    return lo.double().cpu().numpy()
+
+
 def wl(code, P, s, d, attacks=(), placement="any", sigma=1.0, seed=0):
     return synth.Workload(name=f"{code}_{P}_{s}_{d}", code=code, P=P, s=s, d=d, sigma=sigma,
                           attacks=tuple(attacks), placement=placement, seed=synth.SEED_BASE + 1000 + seed)
@@ -547,10 +558,10 @@ def test_cyc_large_s_takes_the_host_form():
     (30, 12, 1_030, ("noise",), "any", 1.0),                              # LDS-ring encoder
     (40, 17, 1_001, ("noise", "signflip"), "any", 1.0),                  # host phi fallback
 ])
-@pytest.mark.parametrize("second", ["f32", "bf16"])
+@pytest.mark.parametrize("second", ["f32", "bf16", "i8"])
 def test_cyc_wide_wire(P, s, d, attacks, placement, sigma, second):
-    """Two-word wire: hi + lo carries the fp64 message to 48 bits (32 with a bfloat16 second
-    word), so the decoded sum meets Definition 2 END TO END (against the true gradient sum)
+    """Two-word wire: hi + lo carries the fp64 message to 48 bits (32 with a bfloat16 or an
+    8-bit second word), so the decoded sum meets Definition 2 END TO END (against the true gradient sum)
     far inside the 1e-4 bar also at P = 45, where the one-word wire cannot."""
     run_wide(wl("cyc", P, s, d, attacks, placement, sigma), second)
 
@@ -559,16 +570,16 @@ def run_wide(w, second="f32", e2e=None):
     P = w.P
     print(f"wide case {w.name} second word {second} attacks={w.attacks} seed={w.seed}", flush=True)
     c = Case(w, wide=second)
-    bits, tau = (48, o.TAU_H_WIDE) if second == "f32" else (33, o.TAU_H_BF16)
+    bits, tau = WIDE[second]
     try:
         c.Z.fill_(float("nan"))
-        c.Zlo.fill_(float("nan"))
+        c.Zlo.fill_(77 if second == "i8" else float("nan"))
         c.encode()
         torch.cuda.synchronize()
-        assert c.Zlo.dtype == (torch.float32 if second == "f32" else torch.bfloat16)
+        assert c.Zlo.dtype == {"f32": torch.float32, "bf16": torch.bfloat16, "i8": torch.int8}[second]
         Zhi = c.Z[:, :c.mlen].cpu().numpy()
-        Zlo = c.Zlo[:, :c.mlen].float().cpu().numpy()
-        Zw = Zhi.astype(np.float64) + Zlo.astype(np.float64)
+        Zlo = second_word_values(Zhi, c.Zlo[:, :c.mlen], second)
+        Zw = Zhi.astype(np.float64) + Zlo
         Zo = o.encode_cyclic(c.G[:, :w.d].cpu().numpy(), w.s)
         # hi + lo against the fp64 message: what the wire's bits allow, element by element, plus the
         # two sides' fp64 summation orders (W itself agrees to 1e-14)
@@ -583,17 +594,20 @@ def run_wide(w, second="f32", e2e=None):
         # sides' 1e-15 then break differently: the first word is a correct rounding either way)
         assert (np.abs(Zhi.astype(np.float64) - Zo) <= 2.0 ** -24 * np.abs(Zo) * (1 + 2.0 ** -20) + 2.0 ** -43 * np.abs(Zo).max()).all()
         assert same_hi.mean() >= 0.8
-        if second == "bf16":     # (an fp32 residual resolves the 1e-16 itself: covered by the bound above)
+        if second != "f32":     # (an fp32 residual resolves the 1e-16 itself: covered by the bound above)
             # (a message that IS an fp32 number leaves a residual of rounding noise, 1e-16 of either sign)
-            same_lo = (Zlo.view(np.uint32) == lo_o.view(np.uint32)) | (np.abs(Zlo - lo_o) <= 2.0 ** -43 * np.abs(Zo).max())
+            same_lo = (Zlo == lo_o) | (np.abs(Zlo - lo_o) <= 2.0 ** -43 * np.abs(Zo).max())
             assert same_lo[same_hi].mean() >= 0.99
         if c.ld_m > c.mlen:
-            assert torch.isnan(c.Z[:, c.mlen:]).all() and torch.isnan(c.Zlo[:, c.mlen:].float()).all()
+            assert torch.isnan(c.Z[:, c.mlen:]).all()
+            pad = c.Zlo[:, c.mlen:]
+            assert (pad == 77).all() if second == "i8" else torch.isnan(pad.float()).all()
         c.receive()
         c.u.fill_(float("nan"))
         mask, status = c.decode()
         torch.cuda.synchronize()
-        Rw = c.R[:, :c.mlen].double().cpu().numpy() + c.Rlo[:, :c.mlen].double().cpu().numpy()
+        Rhi = c.R[:, :c.mlen].cpu().numpy()
+        Rw = Rhi.astype(np.float64) + second_word_values(Rhi, c.Rlo[:, :c.mlen], second)
         uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), w.s, w.d, tau_h=tau)
         assert status == so == 0
         assert np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
@@ -601,7 +615,7 @@ def run_wide(w, second="f32", e2e=None):
         assert_sum_close(ug, uo, 1e-6, second)
         ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
         # fp32 output rounding is 6e-8; the 32-bit wire's own floor is W's growth times 2^-33
-        assert rel_l2(ug, ref) <= (e2e if e2e is not None else 1e-6 if second == "f32" else 1e-5)
+        assert rel_l2(ug, ref) <= (e2e if e2e is not None else {"f32": 1e-6, "bf16": 1e-5, "i8": 3e-5}[second])
         if c.u.numel() > w.d:
             assert torch.isnan(c.u[w.d:]).all()
     finally:
@@ -674,13 +688,14 @@ def test_lengths_around_the_footprint_windows(d):
     narrow-window cyclic encoder owns four pieces 8 KiB apart), so a row that ends near a piece, a
     wavefront stride or a window boundary leaves workgroups with some wavefronts inside the row and
     some outside: lengths one below, on and one above each boundary, for both codes, both packed
-    cyclic encoders (rounds of rows; four pieces per lane) and all four wires."""
+    cyclic encoders (rounds of rows; four pieces per lane) and all five wires."""
     run_and_check(wl("rep", 9, 1, d, ("noise",), "any"), check_true_sum=1e-6)
     run_and_check(wl("rep", 25, 2, d, ("signflip",), "any"), check_true_sum=1e-6)
     run_and_check(wl("cyc", 9, 1, d, ("noise",), "any"), check_true_sum=1e-5)
     run_and_check(wl("cyc", 33, 2, d, ("noise", "signflip"), "any", 1e-2))      # four pieces per lane
     run_wide(wl("cyc", 33, 3, d, ("noise", "offset", "signflip"), "any", 1e-2))
     run_wide(wl("cyc", 33, 3, d, ("noise", "offset", "signflip"), "any", 1e-2), "bf16")
+    run_wide(wl("cyc", 33, 3, d, ("noise", "offset", "signflip"), "any", 1e-2), "i8")
     run_unpacked(wl("cyc", 9, 2, d, ("noise",), "any"))
 
 
@@ -822,8 +837,8 @@ def test_random_shapes_and_attacks_on_the_other_wires():
         w = wl("cyc", P, s, d, attacks, "any", float(rng.choice([1.0, 1e-2])), seed=500 + case)
         if case % 4 == 0:
             run_wide(w)
-        elif case % 4 == 2:
-            run_wide(w, "bf16", e2e=1e-3)     # that wire's floor depends on (P, s); parity is the check here
+        elif case % 4 == 2:     # these wires' floors depend on (P, s); parity is the check here
+            run_wide(w, "bf16" if case % 8 == 2 else "i8", e2e=1e-3)
         else:
             run_unpacked(w, e2e=1.0)          # the fp32-wire floor depends on (P, s); parity is the check here
 
