@@ -44,6 +44,8 @@ struct draco_plan {
     bool prepared = false;
     int device = -1;
     double2* coef_dev = nullptr;     // P*(2s+1): W[(n+t) mod P][n]
+    double* taps_dev = nullptr;      // the factored W: rho[2s+1] (padded to even), rotA[P], rotB[P+2s]
+    CycTaps taps{nullptr, nullptr, nullptr};
     double2* partial_dev = nullptr;  // project_tiles(d) * P
     double2* gamma_dev = nullptr;    // P
     double2* b_dev = nullptr;        // P
@@ -182,6 +184,23 @@ int prepare(draco_plan* p) {
                 tmp[2 * ((size_t)n * r + t) + 1] = (double)w.imag();
             }
         HIP_TRY(hipMemcpy(p->coef_dev, tmp.data(), tmp.size() * sizeof(double), hipMemcpyHostToDevice));
+        // the factored form for the packed encoders: real taps, then the two tables of unit phases
+        const int nrho = (r + 1) / 2 * 2, nB = P + 2 * p->s;   // rho padded so the phases stay 16-byte aligned
+        std::vector<double> fac((size_t)nrho + 2 * P + 2 * nB, 0.0);
+        for (int t = 0; t < r; ++t) fac[t] = (double)p->cyc.real_taps[t];
+        for (int j = 0; j < P; ++j) {
+            fac[nrho + 2 * j] = (double)p->cyc.node_phase[j].real();
+            fac[nrho + 2 * j + 1] = (double)p->cyc.node_phase[j].imag();
+        }
+        for (int k = 0; k < nB; ++k) {
+            fac[nrho + 2 * P + 2 * k] = (double)p->cyc.row_phase[k].real();
+            fac[nrho + 2 * P + 2 * k + 1] = (double)p->cyc.row_phase[k].imag();
+        }
+        HIP_TRY(hipMalloc(&p->taps_dev, fac.size() * sizeof(double)));
+        HIP_TRY(hipMemcpy(p->taps_dev, fac.data(), fac.size() * sizeof(double), hipMemcpyHostToDevice));
+        p->taps.rho = p->taps_dev;
+        p->taps.rotA = reinterpret_cast<const double2*>(p->taps_dev + nrho);
+        p->taps.rotB = reinterpret_cast<const double2*>(p->taps_dev + nrho + 2 * P);
     }
     p->prepared = true;
     return DRACO_OK;
@@ -247,6 +266,7 @@ void draco_plan_destroy(draco_plan* p) {
     if (p->device >= 0) {
         (void)hipDeviceSynchronize();
         (void)hipFree(p->coef_dev);
+        (void)hipFree(p->taps_dev);
         (void)hipFree(p->partial_dev);
         (void)hipFree(p->gamma_dev);
         (void)hipFree(p->b_dev);
@@ -326,7 +346,7 @@ int encode_impl(draco_plan* p, const float* grads_dev, int64_t ld_g, float* hi_d
     else if (unpacked(p))
         HIP_TRY(launch_encode_cyc_real(grads_dev, ld_g, hi_dev, ld_m, p->coef_dev, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->coef_dev,
+        HIP_TRY(launch_encode_cyc(grads_dev, ld_g, hi_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->taps,
                                   p->P, p->s, p->d, st));
     return DRACO_OK;
 }
@@ -367,7 +387,7 @@ int encode_samples_impl(draco_plan* p, const float* samples_dev, int64_t B, int6
     if (p->code == DRACO_CODE_REPETITION)
         HIP_TRY(launch_encode_rep_samples(samples_dev, ld_g, m, messages_dev, ld_m, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->coef_dev,
+        HIP_TRY(launch_encode_cyc_samples(samples_dev, ld_g, m, messages_dev, wide ? lo_dev : nullptr, lo_format(p), ld_m, p->taps,
                                           p->P, p->s, p->d, st));
     return DRACO_OK;
 }
@@ -400,7 +420,7 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     else if (unpacked(p))
         HIP_TRY(launch_encode_cyc_real_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, kSecondWordF32, p->coef_dev, node, p->P, p->s, p->d,
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, kSecondWordF32, p->taps, node, p->P, p->s, p->d,
                                        st));
     return DRACO_OK;
 }

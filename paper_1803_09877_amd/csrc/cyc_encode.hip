@@ -9,14 +9,14 @@ namespace {
 
 // Windows of 23 to 33 gradients (11 <= s <= 16): the one-complex-per-lane kernel.
 hipError_t launch_narrow(int s, bool real, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z, float* Zlo,
-                         int lo, int64_t ldm, const double2* coef, int P, int64_t d) {
+                         int lo, int64_t ldm, const double2* coef, const CycTaps& tab, int P, int64_t d) {
     switch (s) {
-        case 11: return launch_encode_cyc_narrow_s<11>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-        case 12: return launch_encode_cyc_narrow_s<12>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-        case 13: return launch_encode_cyc_narrow_s<13>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-        case 14: return launch_encode_cyc_narrow_s<14>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-        case 15: return launch_encode_cyc_narrow_s<15>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-        case 16: return launch_encode_cyc_narrow_s<16>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+        case 11: return launch_encode_cyc_narrow_s<11>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+        case 12: return launch_encode_cyc_narrow_s<12>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+        case 13: return launch_encode_cyc_narrow_s<13>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+        case 14: return launch_encode_cyc_narrow_s<14>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+        case 15: return launch_encode_cyc_narrow_s<15>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+        case 16: return launch_encode_cyc_narrow_s<16>(real, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
         default: return hipErrorInvalidValue;
     }
 }
@@ -24,7 +24,8 @@ constexpr int kMaxNarrowS = 16;
 
 }  // namespace
 
-// One node: z = sum_t cn[t] * g_t with cn = this node's row of coef.  With
+// One node: z = A_node * sum_t rho_t * (B_{node+t} g_t), W in the factored form the all-node
+// kernels use (tap_sum in cyc_encode_kernels.hpp); each tap rotates its row as it reads it.  With
 // wrap_rows == 0, Gn holds only the node's r gradients in assignment order;
 // with wrap_rows == P it is the full [P][ldg] slab and row (node+t) mod P is
 // used (the all-node path for r > 2*kMaxCycS+1).  Same operation order as the
@@ -33,14 +34,14 @@ constexpr int kMaxNarrowS = 16;
 __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __restrict__ Gn, int64_t ldg,
                                                                  float* __restrict__ z, float* __restrict__ zlo,
                                                                  int64_t lo_off, int lo,
-                                                                 const double2* __restrict__ cn, int node, int P,
+                                                                 const CycTaps tab, int node, int P,
                                                                  int r, int wrap_rows, int m, int64_t d) {
     const int64_t c0 = lane_column<kSpreadEncodeCyc>();
     const int64_t mlen = 2 * ((d + 1) / 2);
     if (c0 >= mlen) return;
     const int nin = clamp4(d - c0);
     const int nout = clamp4(mlen - c0);
-    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+    double sr0 = 0.0, si0 = 0.0, sr1 = 0.0, si1 = 0.0;
     for (int t = 0; t < r; ++t) {
         int k = node + t;
         if (k >= P) k -= P;
@@ -53,9 +54,18 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
             gz += (double)raw.z;
             gw += (double)raw.w;
         }
-        cmac(cn[t].x, cn[t].y, gx, gy, are0, aim0);
-        cmac(cn[t].x, cn[t].y, gz, gw, are1, aim1);
+        double re[2], im[2];
+        rotate_in(tab, node + t, gx, gy, gz, gw, re, im);
+        const double rho = tab.rho[t];
+        sr0 = fma(rho, re[0], sr0);
+        si0 = fma(rho, im[0], si0);
+        sr1 = fma(rho, re[1], sr1);
+        si1 = fma(rho, im[1], si1);
     }
+    double are0, aim0, are1, aim1;
+    const double2 A = tab.rotA[node];
+    cmul(A.x, A.y, sr0, si0, are0, aim0);
+    cmul(A.x, A.y, sr1, si1, are1, aim1);
     const float4 out = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
     if (nout == 4) st4(z + c0, out);
     else st4_partial(z + c0, out, nout);
@@ -77,7 +87,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_node_kernel(const float* __
 template <int TB, bool FULL>
 __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G, int64_t ldg,
                                                      float* __restrict__ Z, float* __restrict__ Zlo, int lo, int64_t ldm,
-                                                     const double2* __restrict__ coef, int P, int r, int64_t d,
+                                                     const CycTaps tab, int P, int r, int64_t d,
                                                      float4* ring /* LDS [r][TB] */) {
     constexpr int Q = 4;
     const int64_t c0 = ((int64_t)blockIdx.x * TB + threadIdx.x) * 4;
@@ -103,15 +113,23 @@ __device__ __forceinline__ void encode_cyc_ring_body(const float* __restrict__ G
             if (n < P) {
                 mine[last * TB] = ahead[q];
                 if (n + Q < P) ahead[q] = fetch(n + Q + r - 1);
-                const double2* cn = coef + (int64_t)n * r;
-                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
+                double sr0 = 0.0, si0 = 0.0, sr1 = 0.0, si1 = 0.0;
                 int slot = first;
                 for (int t = 0; t < r; ++t) {
                     const float4 x = mine[slot * TB];
-                    cmac(cn[t].x, cn[t].y, (double)x.x, (double)x.y, are0, aim0);
-                    cmac(cn[t].x, cn[t].y, (double)x.z, (double)x.w, are1, aim1);
+                    double re[2], im[2];
+                    rotate_in(tab, n + t, (double)x.x, (double)x.y, (double)x.z, (double)x.w, re, im);
+                    const double rho = tab.rho[t];
+                    sr0 = fma(rho, re[0], sr0);
+                    si0 = fma(rho, im[0], si0);
+                    sr1 = fma(rho, re[1], sr1);
+                    si1 = fma(rho, im[1], si1);
                     if (++slot == r) slot = 0;
                 }
+                double are0, aim0, are1, aim1;
+                const double2 A = tab.rotA[n];
+                cmul(A.x, A.y, sr0, si0, are0, aim0);
+                cmul(A.x, A.y, sr1, si1, are1, aim1);
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if (Zlo != nullptr) {
@@ -130,11 +148,11 @@ template <int TB>
 __global__ __launch_bounds__(TB) void encode_cyc_ring_kernel(const float* __restrict__ G, int64_t ldg,
                                                                  float* __restrict__ Z, float* __restrict__ Zlo,
                                                                  int lo, int64_t ldm,
-                                                                 const double2* __restrict__ coef, int P, int r,
+                                                                 const CycTaps tab, int P, int r,
                                                                  int64_t d) {
     extern __shared__ float4 ring[];  // [r][TB]
-    if ((int64_t)(blockIdx.x + 1) * (TB * 4) <= d) encode_cyc_ring_body<TB, true>(G, ldg, Z, Zlo, lo, ldm, coef, P, r, d, ring);
-    else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, lo, ldm, coef, P, r, d, ring);
+    if ((int64_t)(blockIdx.x + 1) * (TB * 4) <= d) encode_cyc_ring_body<TB, true>(G, ldg, Z, Zlo, lo, ldm, tab, P, r, d, ring);
+    else encode_cyc_ring_body<TB, false>(G, ldg, Z, Zlo, lo, ldm, tab, P, r, d, ring);
 }
 
 // One node on the unpacked wire (real gradients, d complex entries out), any window width:
@@ -171,15 +189,15 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_node_kernel(const floa
 // Launchers
 // ---------------------------------------------------------------------------
 
-hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm, const double2* coef,
+hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm, const CycTaps& tab,
                              int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, 1, Z, Zlo, lo, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, 1, Z, Zlo, lo, ldm, nullptr, tab, P, d);
 #define DRACO_CASE(S) \
-    case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, lo, ldm, coef, P, d);
+    case S: return launch_encode_cyc_s<S>(one_per_cu, grid, stream, G, ldg, Z, Zlo, lo, ldm, tab, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
@@ -192,11 +210,11 @@ hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, 
                 allow_large_lds<encode_cyc_ring_kernel<TB>>();
                 const dim3 g64((unsigned)(((mlen + 3) / 4 + TB - 1) / TB));
                 hipLaunchKernelGGL(encode_cyc_ring_kernel<TB>, g64, dim3(TB), ring_bytes, stream, G, ldg, Z, Zlo, lo,
-                                   ldm, coef, P, r, d);
+                                   ldm, tab, P, r, d);
             } else {  // windows too wide for LDS: one launch per node
                 for (int j = 0; j < P; ++j)
                     hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                       Zlo, (int64_t)j * ldm, lo, coef + (int64_t)j * r, j, P, r, P, 1, d);
+                                       Zlo, (int64_t)j * ldm, lo, tab, j, P, r, P, 1, d);
             }
         }
     }
@@ -209,7 +227,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(d)), block(kBlock);
     const int r = 2 * s + 1;
     const bool one_per_cu = s <= 3 && P >= 32;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, true, stream, G, ldg, 1, Z, nullptr, kLoNone, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, true, stream, G, ldg, 1, Z, nullptr, kLoNone, ldm, coef, CycTaps{nullptr, nullptr, nullptr}, P, d);
 #define DRACO_CASE(S) \
     case S: return launch_encode_cyc_real_s<S>(one_per_cu, grid, stream, G, ldg, Z, ldm, coef, P, d);
     switch (s) {
@@ -225,20 +243,20 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
 }
 
 hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo, int64_t ldm,
-                                     const double2* coef, int P, int s, int64_t d, hipStream_t stream) {
+                                     const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
-    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+    if (s > kMaxCycS && s <= kMaxNarrowS) return launch_narrow(s, false, stream, G, ldg, m, Z, Zlo, lo, ldm, nullptr, tab, P, d);
 #define DRACO_CASE(S) \
-    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+    case S: return launch_encode_cyc_multi_s<S>(grid, stream, G, ldg, m, Z, Zlo, lo, ldm, tab, P, d);
     switch (s) {
         DRACO_CASE(0) DRACO_CASE(1) DRACO_CASE(2) DRACO_CASE(3) DRACO_CASE(4) DRACO_CASE(5) DRACO_CASE(6) DRACO_CASE(7)
         DRACO_CASE(8) DRACO_CASE(9) DRACO_CASE(10)
         default:
             for (int j = 0; j < P; ++j)
                 hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, G, ldg, Z + (int64_t)j * ldm,
-                                   Zlo, (int64_t)j * ldm, lo, coef + (int64_t)j * r, j, P, r, P, m, d);
+                                   Zlo, (int64_t)j * ldm, lo, tab, j, P, r, P, m, d);
     }
 #undef DRACO_CASE
     return hipGetLastError();
@@ -253,13 +271,13 @@ hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, c
     return hipGetLastError();
 }
 
-hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, int lo, const double2* coef,
+hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, int lo, const CycTaps& tab,
                                   int node, int P, int s, int64_t d, hipStream_t stream) {
     const int64_t mlen = 2 * ((d + 1) / 2);
     const dim3 grid(grid_cols<kSpreadEncodeCyc>(mlen)), block(kBlock);
     const int r = 2 * s + 1;
     hipLaunchKernelGGL(encode_cyc_node_kernel, grid, block, 0, stream, Gn, ldg, z, zlo, (int64_t)0, lo,
-                       coef + (int64_t)node * r, node, P, r, 0, 1, d);
+                       tab, node, P, r, 0, 1, d);
     return hipGetLastError();
 }
 

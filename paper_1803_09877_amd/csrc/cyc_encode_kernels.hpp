@@ -8,17 +8,51 @@
 
 namespace draco {
 
-// E^Cyc for all nodes: z_n = sum_{t=0}^{2s} coef[n][t] * g_{(n+t) mod P} with
-// coef[n][t] = W[(n+t) mod P][n], on packed complex coordinates in fp64.  A lane
+// E^Cyc for all nodes: z_n = sum_{t=0}^{2s} W[(n+t) mod P][n] * g_{(n+t) mod P} on packed
+// complex coordinates in fp64, W in the factored form described at tap_sum below.  A lane
 // keeps the window g_n .. g_{n+2s} of its two complex coordinates in registers
 // and slides it down the P rows, so every gradient row is read from HBM once;
 // rows 0..2s-1, needed again by the last 2s nodes, are parked in LDS (each lane
 // reads back only what it wrote: no barrier).  Rows are fetched NB-1 rounds of
 // R = 2s+1 ahead of the arithmetic (a ring of NB register buffers).
+// W factors as W[k][j] = A_j * rho_t * B_k for k = j + t (t = 0..2s), with REAL taps rho_t: the
+// nodes that do not hold gradient k are consecutive on the circle, so every factor
+// w^j - w^m of W's closed form is a unit phase times a sine.  A message is therefore
+//   z_j = A_j * sum_t rho_t * (B_{j+t} g_{j+t}),
+// one complex rotation per gradient row as it enters the window, 2 real multiply-adds per tap and
+// complex coordinate (instead of 4), one rotation per output.  B is indexed by the UNWRAPPED row
+// j + t < P + 2s (its half-angle phase is not P-periodic).  Every packed encoder below forms
+// these products in this order, so their messages agree bit for bit.
+// Window entry of unwrapped gradient row kappa for a lane's two complex coordinates.
+__device__ __forceinline__ void rotate_in(const CycTaps& tab, int kappa, double x, double y, double z, double w,
+                                          double (&re)[2], double (&im)[2]) {
+    const double2 B = tab.rotB[kappa];
+    cmul(B.x, B.y, x, y, re[0], im[0]);
+    cmul(B.x, B.y, z, w, re[1], im[1]);
+}
+// Node n's two message entries from the window: taps on slots (first + t) mod R, then A_n.
+template <int R>
+__device__ __forceinline__ void tap_sum(const CycTaps& tab, int n, const double (&wre)[R][2], const double (&wim)[R][2],
+                                        int first, double& are0, double& aim0, double& are1, double& aim1) {
+    double sr0 = 0.0, si0 = 0.0, sr1 = 0.0, si1 = 0.0;
+#pragma unroll
+    for (int t = 0; t < R; ++t) {
+        const int slot = (first + t) % R;
+        const double r = tab.rho[t];
+        sr0 = fma(r, wre[slot][0], sr0);
+        si0 = fma(r, wim[slot][0], si0);
+        sr1 = fma(r, wre[slot][1], sr1);
+        si1 = fma(r, wim[slot][1], si1);
+    }
+    const double2 A = tab.rotA[n];
+    cmul(A.x, A.y, sr0, si0, are0, aim0);
+    cmul(A.x, A.y, sr1, si1, are1, aim1);
+}
+
 template <int S, int NB, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int64_t ldg, float* __restrict__ Z,
                                                 float* __restrict__ Zlo, int64_t ldm,
-                                                const double2* __restrict__ coef, int P, int64_t d,
+                                                const CycTaps tab, int P, int64_t d,
                                                 float4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     const int64_t c0 = lane_column<kSpreadEncodeCyc>();
@@ -29,11 +63,8 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
 
     double wre[R][2], wim[R][2];  // window slot = row index mod R
 
-    auto put = [&](int slot, const float4& raw) {
-        wre[slot][0] = (double)raw.x;
-        wim[slot][0] = (double)raw.y;
-        wre[slot][1] = (double)raw.z;
-        wim[slot][1] = (double)raw.w;
+    auto put = [&](int slot, const float4& raw, int kappa) {
+        rotate_in(tab, kappa, (double)raw.x, (double)raw.y, (double)raw.z, (double)raw.w, wre[slot], wim[slot]);
     };
     // fetch the rows that nodes n0 .. n0+R-1 bring into the window
     auto issue = [&](int n0, float4 (&buf)[R]) {
@@ -51,16 +82,9 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
         for (int uu = 0; uu < R; ++uu) {
             const int n = n0 + uu;
             if (n < P) {
-                put((uu + 2 * S) % R, buf[uu]);
-                const double2* cn = coef + (int64_t)n * R;
-                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
-#pragma unroll
-                for (int t = 0; t < R; ++t) {
-                    const int slot = (uu + t) % R;
-                    const double cr = cn[t].x, ci = cn[t].y;
-                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
-                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
-                }
+                put((uu + 2 * S) % R, buf[uu], n + 2 * S);
+                double are0, aim0, are1, aim1;
+                tap_sum<R>(tab, n, wre, wim, uu % R, are0, aim0, are1, aim1);
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if constexpr (LO != kLoNone) {  // second word of the wide wire: what the first rounding lost
@@ -76,7 +100,7 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
     for (int k = 0; k < 2 * S; ++k) {
         const float4 raw = ldx<FULL>(G + (int64_t)k * ldg + c0, nin);
         head[k * kBlock + threadIdx.x] = raw;
-        put(k, raw);
+        put(k, raw, k);
     }
     float4 buf[NB][R];
 #pragma unroll
@@ -98,11 +122,11 @@ __device__ __forceinline__ void encode_cyc_body(const float* __restrict__ G, int
 template <int S, int NB, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restrict__ G, int64_t ldg,
                                                             float* __restrict__ Z, float* __restrict__ Zlo,
-                                                            int64_t ldm, const double2* __restrict__ coef, int P,
+                                                            int64_t ldm, const CycTaps tab, int P,
                                                             int64_t d) {
     extern __shared__ float4 head[];  // [2S][kBlock]
-    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_body<S, NB, true, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
-    else encode_cyc_body<S, NB, false, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_body<S, NB, true, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head);
+    else encode_cyc_body<S, NB, false, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head);
 }
 
 // The same encoder with a wider lane: a lane owns C float4 of every row (its wavefront's C
@@ -117,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
 template <int S, int C, int D, bool FULL>
 __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ G, int64_t ldg,
                                                       float* __restrict__ Z, int64_t ldm,
-                                                      const double2* __restrict__ coef, int P, int64_t d,
+                                                      const CycTaps tab, int P, int64_t d,
                                                       float4* head /* LDS [2S][C][kBlock] */,
                                                       const int64_t (&cq)[C]) {
     constexpr int R = 2 * S + 1;
@@ -129,15 +153,12 @@ __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ 
         nin[q] = FULL ? 4 : clamp4(d - cq[q]);
         nout[q] = FULL ? 4 : clamp4(mlen - cq[q]);
     }
-    double wre[R][C][2], wim[R][C][2];  // window slot = row index mod R
-    auto put = [&](int slot, const float4 (&raw)[C]) {
+    double wre[C][R][2], wim[C][R][2];  // [piece][window slot = row index mod R]
+    auto put = [&](int slot, const float4 (&raw)[C], int kappa) {
 #pragma unroll
-        for (int q = 0; q < C; ++q) {
-            wre[slot][q][0] = (double)raw[q].x;
-            wim[slot][q][0] = (double)raw[q].y;
-            wre[slot][q][1] = (double)raw[q].z;
-            wim[slot][q][1] = (double)raw[q].w;
-        }
+        for (int q = 0; q < C; ++q)
+            rotate_in(tab, kappa, (double)raw[q].x, (double)raw[q].y, (double)raw[q].z, (double)raw[q].w,
+                      wre[q][slot], wim[q][slot]);
     };
     auto fetch = [&](int k, float4 (&dst)[C]) {  // row k; k >= P wraps to the rows parked in LDS
         if (k < P) {
@@ -157,7 +178,7 @@ __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ 
             fetch(k, row);
 #pragma unroll
             for (int q = 0; q < C; ++q) head[(k * C + q) * kBlock + threadIdx.x] = row[q];
-            put(k, row);
+            put(k, row, k);
         }
     }
 #pragma unroll
@@ -168,19 +189,12 @@ __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ 
         for (int uu = 0; uu < U; ++uu) {
             const int n = n0 + uu;
             if (n < P) {
-                put((uu + 2 * S) % R, ring[uu]);
+                put((uu + 2 * S) % R, ring[uu], n + 2 * S);
                 if (n + D < P) fetch(n + D + 2 * S, ring[(uu + D) % U]);
-                const double2* cn = coef + (int64_t)n * R;
 #pragma unroll
                 for (int q = 0; q < C; ++q) {
-                    double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
-#pragma unroll
-                    for (int t = 0; t < R; ++t) {
-                        const int slot = (uu + t) % R;
-                        const double cr = cn[t].x, ci = cn[t].y;
-                        cmac(cr, ci, wre[slot][q][0], wim[slot][q][0], are0, aim0);
-                        cmac(cr, ci, wre[slot][q][1], wim[slot][q][1], are1, aim1);
-                    }
+                    double are0, aim0, are1, aim1;
+                    tap_sum<R>(tab, n, wre[q], wim[q], uu % R, are0, aim0, are1, aim1);
                     if (FULL || nout[q] > 0)
                         stx<FULL>(Z + (int64_t)n * ldm + cq[q],
                                   make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout[q]);
@@ -193,7 +207,7 @@ __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ 
 template <int S, int C, int D>
 __global__ __launch_bounds__(kBlock) void encode_cyc_strip_kernel(const float* __restrict__ G, int64_t ldg,
                                                                   float* __restrict__ Z, int64_t ldm,
-                                                                  const double2* __restrict__ coef, int P,
+                                                                  const CycTaps tab, int P,
                                                                   int64_t d) {
     extern __shared__ float4 head[];  // [2S][C][kBlock]
     constexpr int64_t u = kWindow / (4 * C);   // floats between neighbouring pieces of the workgroup
@@ -202,8 +216,8 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_strip_kernel(const float* _
     int64_t cq[C];
 #pragma unroll
     for (int q = 0; q < C; ++q) cq[q] = base + ((threadIdx.x >> 6) + 4 * q) * u + (threadIdx.x & 63) * 4;
-    if (base + (4 * C - 1) * u + 256 <= d) encode_cyc_strip_body<S, C, D, true>(G, ldg, Z, ldm, coef, P, d, head, cq);
-    else encode_cyc_strip_body<S, C, D, false>(G, ldg, Z, ldm, coef, P, d, head, cq);
+    if (base + (4 * C - 1) * u + 256 <= d) encode_cyc_strip_body<S, C, D, true>(G, ldg, Z, ldm, tab, P, d, head, cq);
+    else encode_cyc_strip_body<S, C, D, false>(G, ldg, Z, ldm, tab, P, d, head, cq);
 }
 // Workgroups of encode_cyc_strip_kernel<S, C, D> for messages of mlen floats.
 template <int C>
@@ -326,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_real_kernel(const float* __
 template <int S, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ G, int64_t ldg, int m,
                                                       float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
-                                                      const double2* __restrict__ coef, int P, int64_t d,
+                                                      const CycTaps tab, int P, int64_t d,
                                                       double4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     constexpr int UN = 4;
@@ -337,11 +351,8 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
     const int nout = FULL ? 4 : clamp4(mlen - c0);
 
     double wre[R][2], wim[R][2];
-    auto put = [&](int slot, const double4& v) {
-        wre[slot][0] = v.x;
-        wim[slot][0] = v.y;
-        wre[slot][1] = v.z;
-        wim[slot][1] = v.w;
+    auto put = [&](int slot, const double4& v, int kappa) {
+        rotate_in(tab, kappa, v.x, v.y, v.z, v.w, wre[slot], wim[slot]);
     };
     auto unit_sum = [&](int k) -> double4 {  // g_k = sum of its m sample rows, ascending, in fp64
         double4 acc = make_double4(0.0, 0.0, 0.0, 0.0);
@@ -378,16 +389,9 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
         for (int uu = 0; uu < R; ++uu) {
             const int n = n0 + uu;
             if (n < P) {
-                put((uu + 2 * S) % R, buf[uu]);
-                const double2* cn = coef + (int64_t)n * R;
-                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
-#pragma unroll
-                for (int t = 0; t < R; ++t) {
-                    const int slot = (uu + t) % R;
-                    const double cr = cn[t].x, ci = cn[t].y;
-                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
-                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
-                }
+                put((uu + 2 * S) % R, buf[uu], n + 2 * S);
+                double are0, aim0, are1, aim1;
+                tap_sum<R>(tab, n, wre, wim, uu % R, are0, aim0, are1, aim1);
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if constexpr (LO != kLoNone) {
@@ -402,7 +406,7 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
     for (int k = 0; k < 2 * S; ++k) {
         const double4 v = unit_sum(k);
         head[k * kBlock + threadIdx.x] = v;
-        put(k, v);
+        put(k, v, k);
     }
     double4 bufA[R], bufB[R];
     issue(0, bufA);
@@ -423,7 +427,7 @@ __device__ __forceinline__ void encode_cyc_multi_body(const float* __restrict__ 
 template <int S, int D, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restrict__ G, int64_t ldg, int m,
                                                            float* __restrict__ Z, float* __restrict__ Zlo,
-                                                           int64_t ldm, const double2* __restrict__ coef, int P,
+                                                           int64_t ldm, const CycTaps tab, int P,
                                                            int64_t d, double4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     const int64_t c0 = lane_column<kSpreadEncodeCyc>();
@@ -458,17 +462,14 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
         return acc;
     };
     double wre[R][2], wim[R][2];
-    auto put = [&](int slot, const double4& v) {
-        wre[slot][0] = v.x;
-        wim[slot][0] = v.y;
-        wre[slot][1] = v.z;
-        wim[slot][1] = v.w;
+    auto put = [&](int slot, const double4& v, int kappa) {
+        rotate_in(tab, kappa, v.x, v.y, v.z, v.w, wre[slot], wim[slot]);
     };
 #pragma unroll
     for (int k = 0; k < 2 * S; ++k) {
         const double4 v = unit_sum();
         head[k * kBlock + threadIdx.x] = v;
-        put(k, v);
+        put(k, v, k);
     }
     for (int n0 = 0; n0 < P; n0 += R) {
 #pragma unroll
@@ -477,16 +478,9 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
             if (n < P) {
                 const int kk = n + 2 * S;
                 const double4 v = kk < P ? unit_sum() : head[(kk - P) * kBlock + threadIdx.x];
-                put((uu + 2 * S) % R, v);
-                const double2* cn = coef + (int64_t)n * R;
-                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
-#pragma unroll
-                for (int t = 0; t < R; ++t) {
-                    const int slot = (uu + t) % R;
-                    const double cr = cn[t].x, ci = cn[t].y;
-                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
-                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
-                }
+                put((uu + 2 * S) % R, v, kk);
+                double are0, aim0, are1, aim1;
+                tap_sum<R>(tab, n, wre, wim, uu % R, are0, aim0, are1, aim1);
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if constexpr (LO != kLoNone) {
@@ -505,7 +499,7 @@ __device__ __forceinline__ void encode_cyc_multi_ring_body(const float* __restri
 template <int S, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restrict__ G, int64_t ldg,
                                                            float* __restrict__ Z, float* __restrict__ Zlo,
-                                                           int64_t ldm, const double2* __restrict__ coef, int P,
+                                                           int64_t ldm, const CycTaps tab, int P,
                                                            int64_t d, double4* head /* LDS [2S][kBlock] */) {
     constexpr int R = 2 * S + 1;
     const int64_t c0 = lane_column<kSpreadEncodeCyc>();
@@ -539,11 +533,8 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
         return acc;
     };
     double wre[R][2], wim[R][2];
-    auto put = [&](int slot, const double4& v) {
-        wre[slot][0] = v.x;
-        wim[slot][0] = v.y;
-        wre[slot][1] = v.z;
-        wim[slot][1] = v.w;
+    auto put = [&](int slot, const double4& v, int kappa) {
+        rotate_in(tab, kappa, v.x, v.y, v.z, v.w, wre[slot], wim[slot]);
     };
 #pragma unroll
     for (int k = 0; k < 2 * S; ++k) {
@@ -551,7 +542,7 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
         if (k % 2 == 0) v = unit_sum(std::integral_constant<int, 0>());
         else v = unit_sum(std::integral_constant<int, 1>());
         head[k * kBlock + threadIdx.x] = v;
-        put(k, v);
+        put(k, v, k);
     }
     for (int n0 = 0; n0 < P; n0 += 2 * R) {
 #pragma unroll
@@ -563,16 +554,9 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
                 if (kk >= P) v = head[(kk - P) * kBlock + threadIdx.x];
                 else if (uu % 2 == 0) v = unit_sum(std::integral_constant<int, 0>());
                 else v = unit_sum(std::integral_constant<int, 1>());
-                put((uu + 2 * S) % R, v);
-                const double2* cn = coef + (int64_t)n * R;
-                double are0 = 0.0, aim0 = 0.0, are1 = 0.0, aim1 = 0.0;
-#pragma unroll
-                for (int t = 0; t < R; ++t) {
-                    const int slot = (uu + t) % R;
-                    const double cr = cn[t].x, ci = cn[t].y;
-                    cmac(cr, ci, wre[slot][0], wim[slot][0], are0, aim0);
-                    cmac(cr, ci, wre[slot][1], wim[slot][1], are1, aim1);
-                }
+                put((uu + 2 * S) % R, v, kk);
+                double are0, aim0, are1, aim1;
+                tap_sum<R>(tab, n, wre, wim, uu % R, are0, aim0, are1, aim1);
                 const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
                 stx<FULL>(Z + (int64_t)n * ldm + c0, hi, nout);
                 if constexpr (LO != kLoNone) {
@@ -588,35 +572,35 @@ __device__ __forceinline__ void encode_cyc_multi_four_body(const float* __restri
 template <int S, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_four_kernel(const float* __restrict__ G, int64_t ldg,
                                                                        float* __restrict__ Z, float* __restrict__ Zlo,
-                                                                       int64_t ldm, const double2* __restrict__ coef,
+                                                                       int64_t ldm, const CycTaps tab,
                                                                        int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
     if (block_is_full<kSpreadEncodeCyc>(d))
-        encode_cyc_multi_four_body<S, true, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_four_body<S, true, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head_sums);
     else
-        encode_cyc_multi_four_body<S, false, LO>(G, ldg, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_four_body<S, false, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head_sums);
 }
 
 template <int S, int D, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_ring_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                        float* __restrict__ Z, float* __restrict__ Zlo,
-                                                                       int64_t ldm, const double2* __restrict__ coef,
+                                                                       int64_t ldm, const CycTaps tab,
                                                                        int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
     if (block_is_full<kSpreadEncodeCyc>(d))
-        encode_cyc_multi_ring_body<S, D, true, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_ring_body<S, D, true, LO>(G, ldg, m, Z, Zlo, ldm, tab, P, d, head_sums);
     else
-        encode_cyc_multi_ring_body<S, D, false, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+        encode_cyc_multi_ring_body<S, D, false, LO>(G, ldg, m, Z, Zlo, ldm, tab, P, d, head_sums);
 }
 
 template <int S, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                   float* __restrict__ Z, float* __restrict__ Zlo,
-                                                                  int64_t ldm, const double2* __restrict__ coef,
+                                                                  int64_t ldm, const CycTaps tab,
                                                                   int P, int64_t d) {
     extern __shared__ double4 head_sums[];  // [2S][kBlock]
-    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_multi_body<S, true, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
-    else encode_cyc_multi_body<S, false, LO>(G, ldg, m, Z, Zlo, ldm, coef, P, d, head_sums);
+    if (block_is_full<kSpreadEncodeCyc>(d)) encode_cyc_multi_body<S, true, LO>(G, ldg, m, Z, Zlo, ldm, tab, P, d, head_sums);
+    else encode_cyc_multi_body<S, false, LO>(G, ldg, m, Z, Zlo, ldm, tab, P, d, head_sums);
 }
 
 
@@ -625,7 +609,7 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_multi_kernel(const float* _
 // lo: format of the second word (kLoF32 / kLoBf16) when Zlo is not null.
 template <int S>
 hipError_t launch_encode_cyc_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg, float* Z,
-                               float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
+                               float* Zlo, int lo, int64_t ldm, const CycTaps& tab, int P, int64_t d);
 // Same for the unpacked wire (real gradients in, d complex entries out).
 template <int S>
 hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stream, const float* G, int64_t ldg,
@@ -633,6 +617,6 @@ hipError_t launch_encode_cyc_real_s(bool one_per_cu, dim3 grid, hipStream_t stre
 // Same for the B > P form (m per-sample rows per unit gradient).
 template <int S>
 hipError_t launch_encode_cyc_multi_s(dim3 grid, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
-                                     float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
+                                     float* Zlo, int lo, int64_t ldm, const CycTaps& tab, int P, int64_t d);
 
 }  // namespace draco

@@ -21,8 +21,8 @@ namespace draco {
 template <int S, bool REAL, bool MULTI, bool FULL>
 __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__ G, int64_t ldg, int m,
                                                        float* __restrict__ Z, float* __restrict__ Zlo, int lo,
-                                                       int64_t ldm, const double2* __restrict__ coef, int P,
-                                                       int64_t d) {
+                                                       int64_t ldm, const double2* __restrict__ coef,
+                                                       const CycTaps tab, int P, int64_t d) {
     constexpr int R = 2 * S + 1;
     constexpr int U = 4;
     // unit gradients 0 .. 2s-1 of this lane's pair, parked for the wrap-around: the fp64 sums
@@ -42,6 +42,18 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
         else return ld2_partial(p, nin);
     };
     auto widen = [](float2 x) { return make_double2((double)x.x, (double)x.y); };
+    // a unit gradient as it enters the window: on the packed wire rotated by B of its unwrapped
+    // row index (see tap_sum in cyc_encode_kernels.hpp), on the unpacked wire as it is
+    auto enter = [&](double2 v, int kappa) -> double2 {
+        if constexpr (REAL) {
+            return v;
+        } else {
+            const double2 B = tab.rotB[kappa];
+            double2 h;
+            cmul(B.x, B.y, v.x, v.y, h.x, h.y);
+            return h;
+        }
+    };
     auto unit_sum = [&](int k) -> double2 {   // MULTI: unit gradient k < P, the fp64 sum of its m rows, ascending
         double2 acc = make_double2(0.0, 0.0);
         const int64_t first = (int64_t)k * m;
@@ -63,8 +75,8 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
     // U outputs n0 .. n0+U-1 from window positions i .. i+2s; the taps of the U outputs are
     // interleaved so that 2U (4U on the unpacked wire) independent accumulators are in flight
     auto outputs = [&](int n0, const double2 (&w)[2 * S + U], int count) {
-        const double2* cn = coef + (int64_t)n0 * R;
         if constexpr (REAL) {
+            const double2* cn = coef + (int64_t)n0 * R;
             double re0[U], im0[U], re1[U], im1[U];
 #pragma unroll
             for (int i = 0; i < U; ++i) re0[i] = im0[i] = re1[i] = im1[i] = 0.0;
@@ -91,18 +103,25 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
                 }
             }
         } else {
-            double are[U], aim[U];
+            double sr[U], si[U], are[U], aim[U];
 #pragma unroll
-            for (int i = 0; i < U; ++i) are[i] = aim[i] = 0.0;
+            for (int i = 0; i < U; ++i) sr[i] = si[i] = 0.0;
 #pragma unroll
             for (int t = 0; t < R; ++t) {
+                const double r = tab.rho[t];
 #pragma unroll
-                for (int i = 0; i < U; ++i)
-                    if (i < count) cmac(cn[i * R + t].x, cn[i * R + t].y, w[i + t].x, w[i + t].y, are[i], aim[i]);
+                for (int i = 0; i < U; ++i) {
+                    if (i < count) {
+                        sr[i] = fma(r, w[i + t].x, sr[i]);
+                        si[i] = fma(r, w[i + t].y, si[i]);
+                    }
+                }
             }
 #pragma unroll
             for (int i = 0; i < U; ++i) {
                 if (i < count) {
+                    const double2 A = tab.rotA[n0 + i];
+                    cmul(A.x, A.y, sr[i], si[i], are[i], aim[i]);
                     const float hr = (float)are[i], hi = (float)aim[i];
                     st2(Z + (int64_t)(n0 + i) * ldm + c0, make_float2(hr, hi));
                     if (Zlo != nullptr)   // second word of the wide wire: what the first rounding lost
@@ -119,7 +138,7 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
         for (int k = 0; k < 2 * S; ++k) {
             const double2 v = unit_sum(k);
             parked[k * kBlock + threadIdx.x] = v;
-            w[k] = v;
+            w[k] = enter(v, k);
         }
     } else {   // all 2s loads in flight before the first is parked
         float2 x[2 * S];
@@ -128,7 +147,7 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
 #pragma unroll
         for (int k = 0; k < 2 * S; ++k) {
             parked[k * kBlock + threadIdx.x] = x[k];
-            w[k] = widen(x[k]);
+            w[k] = enter(widen(x[k]), k);
         }
     }
     float2 pre[MULTI ? 1 : U];   // rows 2s + i of the coming step, in flight (plain rows only)
@@ -141,8 +160,8 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
     for (; n0 + U + 2 * S <= P; n0 += U) {
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-            if constexpr (MULTI) w[2 * S + i] = unit_sum(n0 + i + 2 * S);
-            else w[2 * S + i] = widen(pre[i]);
+            if constexpr (MULTI) w[2 * S + i] = enter(unit_sum(n0 + i + 2 * S), n0 + i + 2 * S);
+            else w[2 * S + i] = enter(widen(pre[i]), n0 + i + 2 * S);
         }
         if constexpr (!MULTI) {
 #pragma unroll
@@ -163,11 +182,11 @@ __device__ __forceinline__ void encode_cyc_narrow_body(const float* __restrict__
             const int k = n0 + i + 2 * S;
             if (i < count) {
                 if (k >= P) {
-                    if constexpr (MULTI) w[2 * S + i] = parked[(k - P) * kBlock + threadIdx.x];
-                    else w[2 * S + i] = widen(parked[(k - P) * kBlock + threadIdx.x]);
+                    if constexpr (MULTI) w[2 * S + i] = enter(parked[(k - P) * kBlock + threadIdx.x], k);
+                    else w[2 * S + i] = enter(widen(parked[(k - P) * kBlock + threadIdx.x]), k);
                 } else {
-                    if constexpr (MULTI) w[2 * S + i] = unit_sum(k);
-                    else w[2 * S + i] = widen(pre[i]);
+                    if constexpr (MULTI) w[2 * S + i] = enter(unit_sum(k), k);
+                    else w[2 * S + i] = enter(widen(pre[i]), k);
                 }
             }
         }
@@ -189,16 +208,17 @@ template <int S, bool REAL, bool MULTI>
 __global__ __launch_bounds__(kBlock) void encode_cyc_narrow_kernel(const float* __restrict__ G, int64_t ldg, int m,
                                                                    float* __restrict__ Z, float* __restrict__ Zlo,
                                                                    int lo, int64_t ldm,
-                                                                   const double2* __restrict__ coef, int P,
-                                                                   int64_t d) {
+                                                                   const double2* __restrict__ coef,
+                                                                   const CycTaps tab, int P, int64_t d) {
     // every lane of the workgroup has both floats of its pair inside the gradient
-    if ((int64_t)(blockIdx.x + 1) * (kBlock * 2) <= d) encode_cyc_narrow_body<S, REAL, MULTI, true>(G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
-    else encode_cyc_narrow_body<S, REAL, MULTI, false>(G, ldg, m, Z, Zlo, lo, ldm, coef, P, d);
+    if ((int64_t)(blockIdx.x + 1) * (kBlock * 2) <= d) encode_cyc_narrow_body<S, REAL, MULTI, true>(G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
+    else encode_cyc_narrow_body<S, REAL, MULTI, false>(G, ldg, m, Z, Zlo, lo, ldm, coef, tab, P, d);
 }
 
 // Launch for one s (defined in the translation unit of that s).
 template <int S>
 hipError_t launch_encode_cyc_narrow_s(bool real, hipStream_t stream, const float* G, int64_t ldg, int m, float* Z,
-                                      float* Zlo, int lo, int64_t ldm, const double2* coef, int P, int64_t d);
+                                      float* Zlo, int lo, int64_t ldm, const double2* coef, const CycTaps& tab, int P,
+                                      int64_t d);
 
 }  // namespace draco

@@ -269,6 +269,13 @@ __device__ __forceinline__ void cmac(double tr, double ti, double x, double y, d
 }
 
 
+// (hr + i hi) = (br + i bi) * (x + i y): one instruction sequence wherever it is used
+__device__ __forceinline__ void cmul(double br, double bi, double x, double y, double& hr, double& hi) {
+    hr = fma(-bi, y, br * x);
+    hi = fma(bi, x, br * y);
+}
+
+
 // ---------------------------------------------------------------------------
 // Launch helpers (host)
 // ---------------------------------------------------------------------------

@@ -169,12 +169,24 @@ void CyclicCode::build(int P_, int s_) {
         taps[t] = prod;
     }
     for (int k = 0; k < P; ++k) rot[k] = root_of_unity(P, (long long)k * D);
+    // The non-holders are consecutive on the circle, so each factor above is a unit phase times a
+    // sine: w^a - w^b = e^{i pi (a+b)/P} * 2i sin(pi (a-b)/P).  Collecting the phases,
+    // taps[t] = c * e^{-i pi D t / P} * rho[t] with rho real and c one constant phase, hence
+    // W[j+t][j] = rot[j+t] * taps[t] = (c e^{i pi D j / P}) * rho[t] * e^{i pi D (j+t) / P}.
+    const cplx_t c = taps[0] / std::abs(taps[0]);
+    real_taps.assign(r, 0);
+    node_phase.assign(P, cplx_t(0));
+    row_phase.assign(P + 2 * s, cplx_t(0));
+    for (int t = 0; t < r; ++t)
+        real_taps[t] = (taps[t] * std::conj(c) * root_of_unity(2 * P, (long long)D * t)).real();
+    for (int j = 0; j < P; ++j) node_phase[j] = c * root_of_unity(2 * P, (long long)D * j);
+    for (int k = 0; k < P + 2 * s; ++k) row_phase[k] = root_of_unity(2 * P, (long long)D * k);
 }
 
 cplx_t CyclicCode::W(int k, int j) const {
     const int t = ((k - j) % P + P) % P;
     if (t > 2 * s) return cplx_t(0);
-    return rot[k] * taps[t];
+    return node_phase[j] * real_taps[t] * row_phase[j + t];
 }
 
 bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_in, std::vector<uint8_t>& mask,

@@ -23,6 +23,12 @@ struct CyclicCode {
     // node j's message is sum_t taps[t] * (rot[j+t] * g_{j+t}).
     std::vector<cplx_t> taps;  // 2s+1
     std::vector<cplx_t> rot;   // P, unimodular
+    // The same weights with REAL taps: W[j+t][j] = node_phase[j] * real_taps[t] * row_phase[j+t],
+    // row_phase indexed by the unwrapped row j + t < P + 2s (its half-angle phase is not
+    // P-periodic).  This is the form W() returns and the packed encoders compute with.
+    std::vector<real_t> real_taps;    // 2s+1
+    std::vector<cplx_t> node_phase;   // P, unimodular
+    std::vector<cplx_t> row_phase;    // P + 2s, unimodular
     void build(int P_, int s_);
     cplx_t W(int k, int j) const;  // weight of gradient k in node j's message
 };

@@ -46,18 +46,27 @@ hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint6
 // B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,
                                      int s, int64_t d, hipStream_t stream);
+struct CycTaps;
 hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo,
-                                     int64_t ldm, const double2* coef, int P, int s, int64_t d, hipStream_t stream);
+                                     int64_t ldm, const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream);
 
 // ---- cyclic code ----
-// coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient.
+// coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient
+// (used by the unpacked wire).  The packed encoders take W factored, W[(n+t) mod P][n] =
+// rotA[n] * rho[t] * rotB[n+t] with real rho[2s+1], unit rotA[P] and unit rotB[P+2s] (indexed by
+// the unwrapped row n + t): device pointers.
+struct CycTaps {
+    const double* rho;
+    const double2* rotA;
+    const double2* rotB;
+};
 // Zlo / zlo / Rlo below: second word of the two-word wire (message = hi + lo), or nullptr;
 // lo names its format: kSecondWordF32 (a float slab), kSecondWordBf16 (a bfloat16 slab) or
 // kSecondWordI8 (a slab of 8-bit residual codes), each with the same row stride counted in
 // ELEMENTS.  Ignored when the pointer is null.
 constexpr int kSecondWordF32 = 1, kSecondWordBf16 = 2, kSecondWordI8 = 3;
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm,
-                             const double2* coef, int P, int s, int64_t d, hipStream_t stream);
+                             const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream);
 // Unpacked wire: real gradients [P][d] in, messages of d complex entries (2d floats) out.
 hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t ldm, const double2* coef,
                                   int P, int s, int64_t d, hipStream_t stream);
@@ -65,7 +74,7 @@ hipError_t launch_encode_cyc_real(const float* G, int64_t ldg, float* Z, int64_t
 hipError_t launch_encode_cyc_real_node(const float* Gn, int64_t ldg, float* z, const double2* coef, int node,
                                        int P, int s, int64_t d, hipStream_t stream);
 hipError_t launch_encode_cyc_node(const float* Gn, int64_t ldg, float* z, float* zlo, int lo,
-                                  const double2* coef, int node, int P, int s, int64_t d, hipStream_t stream);
+                                  const CycTaps& tab, int node, int P, int s, int64_t d, hipStream_t stream);
 // Number of workgroups (= rows of `partial`) the projection uses for gradient length d.
 int64_t project_tiles(int64_t d);
 // partial[tile][P] <- per-tile sums of f_i * R[j][i]; gamma[P] <- their sum in tile order.
