@@ -181,6 +181,7 @@ __global__ __launch_bounds__(kBlock) void cyc_project_reduce_kernel(const double
 constexpr int kRecombineRows = 6;      // message rows a lane has in flight (one word per float)
 constexpr int kRecombineRowsWide = 3;  // the same on the two-word wire (two loads per row)
 constexpr int kRecombineRowsBf16 = 3;  // and with a bfloat16 second word (a 16- and an 8-byte load per row)
+constexpr int kRecombineRowsI8 = 2;    // and with an 8-bit one (a 16- and a 4-byte load per row)
 
 // u = R_{.,U} b on packed complex messages, unpacked to reals: honest rows in
 // ascending node order, fp64 accumulation, one rounding to fp32.
@@ -315,8 +316,9 @@ hipError_t launch_cyc_recombine(const float* R, const float* Rlo, int lo, int64_
         hipLaunchKernelGGL((cyc_recombine_kernel<kLoBf16, kRecombineRowsBf16>), grid, block, throttle_lds(4, 0, 0), stream,
                            R, Rlo, ldm, b, idx, nu, spec_state, P, u, realout ? 1 : 0, d);
     } else if (lo == kLoI8) {
-        allow_large_lds<cyc_recombine_kernel<kLoI8, kRecombineRowsBf16>>();
-        hipLaunchKernelGGL((cyc_recombine_kernel<kLoI8, kRecombineRowsBf16>), grid, block, throttle_lds(4, 0, 0), stream,
+        // sweep at (45, 3, 25.6 M): 0.81 of the HBM peak with 4 workgroups x 2 rows (also 2 x 6 and 6 x 1)
+        allow_large_lds<cyc_recombine_kernel<kLoI8, kRecombineRowsI8>>();
+        hipLaunchKernelGGL((cyc_recombine_kernel<kLoI8, kRecombineRowsI8>), grid, block, throttle_lds(4, 0, 0), stream,
                            R, Rlo, ldm, b, idx, nu, spec_state, P, u, realout ? 1 : 0, d);
     } else {
         allow_large_lds<cyc_recombine_kernel<kLoF32, kRecombineRowsWide>>();

@@ -661,6 +661,43 @@ def test_cyc_wide_wire_tells_tiny_lies_from_rounding(P, s, d, size, second):
         c.close()
 
 
+@pytest.mark.parametrize("second", ["f32", "bf16", "i8"])
+def test_cyc_wide_wire_survives_broken_and_hostile_words(second):
+    """Two-word wire, s = 2: one node's FIRST word holds an Inf, another node's SECOND words are
+    hostile -- NaN where the format has one, else the code 0x80 (which no encoder writes) under a
+    sign-flipped first word.  Both are flagged, neither row reaches the sum; mask, status and sum
+    as the oracle's on the same words."""
+    w = wl("cyc", 9, 2, 4_001)
+    c = Case(w, wide=second)
+    try:
+        c.encode()
+        c.receive()
+        c.R[2, 10] = float("inf")
+        if second == "i8":
+            c.Rlo[6, :c.mlen] = -128
+            c.R[6, :c.mlen] *= -100.0
+        else:
+            c.Rlo[6, 5] = float("nan")
+        Rhi = c.R[:, :c.mlen].cpu().numpy()
+        Rw = Rhi.astype(np.float64) + second_word_values(Rhi, c.Rlo[:, :c.mlen], second)
+        assert not np.isfinite(Rw[2]).all() and (second == "i8" or not np.isfinite(Rw[6]).all())
+        with np.errstate(invalid="ignore"):
+            uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), w.s, w.d, tau_h=WIDE[second][1])
+        assert so == o.OK and sorted(np.flatnonzero(mo)) == [2, 6]
+        for fn in (c.plan.decode_cyclic_wide,):
+            c.u.fill_(float("nan"))
+            mask, status = fn(c.R, c.Rlo, c.f, c.u)
+            torch.cuda.synchronize()
+            assert status == B.OK and np.array_equal(mask, mo)
+            ug = c.u[:w.d].cpu().numpy()
+            assert np.isfinite(ug).all()
+            assert_sum_close(ug, uo, 1e-6, second)
+        ref = c.G[:, :w.d].double().sum(0).cpu().numpy()
+        assert rel_l2(ug, ref) <= 1e-5
+    finally:
+        c.close()
+
+
 def test_cyc_determinism():
     w = wl("cyc", 15, 2, 100_003, ("offset", "offset"))
     c = Case(w)
