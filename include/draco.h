@@ -353,7 +353,11 @@ int draco_cyclic_recombination_vector(const draco_plan* plan, const uint64_t* ma
  * be A^Rep or A^Cyc of Sec. 3 for `code` (every row holds r = 2s+1 ones, which
  * fixes s), otherwise DRACO_EINVAL.  samples_dev is [B][ld_g] with B a multiple
  * of P (B = P: one unit gradient per row), as for draco_encode_samples; the
- * cyclic code uses the packed wire.  The library keeps one plan per
+ * cyclic code uses the packed wire with ONE fp32 word per message float (these
+ * calls take a single message slab): rounding the messages to fp32 leaves the
+ * decoded sum about 5e-7 from the true one at P = 15 but 3e-4 at P = 45 -- use
+ * the plan forms with a two-word wire (draco_encode_wide) where that matters.
+ * The library keeps one plan per
  * (code, P, s, d, device) behind these calls and prepares it on first use (that
  * call allocates; later ones do not).  Calls with the same parameters take
  * turns.  Asynchronous on `stream`. */

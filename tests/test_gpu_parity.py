@@ -917,6 +917,48 @@ def test_encode_samples_sums_the_unit_gradients_in_the_encoder(code, P, s, m, d)
         plan.close()
 
 
+@pytest.mark.parametrize("second", ["f32", "bf16", "i8"])
+@pytest.mark.parametrize("P,s,m,d", [(45, 5, 4, 8_002), (15, 2, 8, 3_001), (9, 1, 12, 8_193), (20, 8, 3, 1_001),
+                                     (25, 12, 2, 515), (45, 3, 4, 32_769)])
+def test_encode_samples_on_the_two_word_wires(P, s, m, d, second):
+    """B = m*P sample rows on every two-word wire and through every B > P kernel (four rows per unit,
+    rings of eight and four, the general form, the wide-window form): hi + lo against the oracle's
+    fp64 message to what the wire carries, element by element, and the second word bit for bit
+    wherever the first words agree."""
+    plan = B.Plan(B.CODE_CYCLIC, P, s, d)
+    try:
+        plan.set_second_word({"f32": B.SECOND_WORD_F32, "bf16": B.SECOND_WORD_BF16, "i8": B.SECOND_WORD_I8}[second])
+        ld = synth.padded_len(d)
+        S = synth.make_gradients(P * m, d, 1.0, synth.SEED_BASE + 37 * m + P, device="cuda:0", ld=ld)
+        mlen = plan.message_len
+        ldm = synth.padded_len(mlen)
+        Z = torch.full((P, ldm), float("nan"), dtype=torch.float32, device="cuda:0")
+        lo_dtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i8": torch.int8}[second]
+        Zlo = torch.full((P, ldm), 77 if second == "i8" else float("nan"), dtype=lo_dtype, device="cuda:0")
+        print(f"wide samples case P={P} s={s} m={m} d={d} second word {second}", flush=True)
+        plan.encode_samples_wide(S, Z, Zlo)
+        torch.cuda.synchronize()
+        units = S[:, :d].double().reshape(P, m, d).sum(1).cpu().numpy()
+        Zo = o.encode_cyclic(units, s)
+        Zhi = Z[:, :mlen].cpu().numpy()
+        Zl = second_word_values(Zhi, Zlo[:, :mlen], second)
+        bits = WIDE[second][0]
+        for j in range(P):
+            slack = 2.0 ** -bits * np.abs(Zo[j]) + 2.0 ** -43 * np.abs(Zo[j]).max()
+            assert (np.abs(Zhi[j].astype(np.float64) + Zl[j] - Zo[j]) <= slack).all(), j
+        hi_o, lo_o = o.two_word_wire(Zo, second)
+        same_hi = Zhi.view(np.uint32) == hi_o.view(np.uint32)
+        assert same_hi.mean() >= 0.8
+        if second != "f32":
+            same_lo = (Zl == lo_o) | (np.abs(Zl - lo_o) <= 2.0 ** -43 * np.abs(Zo).max())
+            assert same_lo[same_hi].mean() >= 0.99
+        if ldm > mlen:
+            assert torch.isnan(Z[:, mlen:]).all()
+            assert (Zlo[:, mlen:] == 77).all() if second == "i8" else torch.isnan(Zlo[:, mlen:].float()).all()
+    finally:
+        plan.close()
+
+
 # ------------------------------------------------------------ arguments -----
 def test_one_shot_forms():
     """The three calls without a plan: encode(assign, grads) -> messages and
