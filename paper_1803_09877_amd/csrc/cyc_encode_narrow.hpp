@@ -1,9 +1,10 @@
 // Cyclic encoder E^Cyc (Sec. 3, "Cyclic Code") for wide windows, 11 <= s <= 16: with r = 2s+1
-// up to 33 taps per output the pass is bound by fp64 multiply-adds (4 r per complex
-// coordinate), not by HBM, so a lane owns ONE complex coordinate (8-byte accesses) and keeps
-// the whole window g_n .. g_{n+2s} of it in registers as doubles.  The window is a shift
-// register: U = 4 outputs are formed per step from positions i .. i+2s, then everything
-// moves down by U (r/2 register moves against 4 r multiply-adds per output); the taps of the
+// up to 33 taps per output the pass is bound by fp64 multiply-adds (2 r + 8 per complex
+// coordinate on the packed wire, where W's taps are real; 4 r on the unpacked wire), not by
+// HBM, so a lane owns ONE complex coordinate (8-byte accesses) and keeps the whole window
+// g_n .. g_{n+2s} of it in registers as doubles (on the packed wire: rotated by the row
+// phase as it enters).  The window is a shift register: U = 4 outputs are formed per step
+// from positions i .. i+2s, then everything moves down by U; the taps of the
 // U outputs are interleaved, which keeps 2U independent accumulator chains in flight.  The
 // first 2s unit gradients are parked in LDS for the wrap-around; the next U rows are fetched
 // while the current outputs are computed.  One kernel covers the packed wire (one or two words), the

@@ -717,6 +717,57 @@ def test_cyc_determinism():
         c.close()
 
 
+# ------------------------------------ the two sides end to end, nothing shared ----
+@pytest.mark.parametrize("code,P,s,d,attacks,wire", [
+    ("rep", 15, 2, 30_001, ("signflip", "offset"), "one"),
+    ("cyc", 15, 2, 30_001, ("signflip", "offset"), "one"),
+    ("cyc", 45, 3, 30_002, ("signflip", "constant", "offset"), "f32"),
+    ("cyc", 45, 3, 30_002, ("signflip", "constant", "offset"), "bf16"),
+    ("cyc", 45, 3, 30_002, ("signflip", "constant", "offset"), "i8"),
+    ("cyc", 45, 5, 8_001, ("constant", "signflip", "constant", "signflip", "constant"), "i8"),
+])
+def test_both_sides_end_to_end_from_the_same_gradients(code, P, s, d, attacks, wire):
+    """Nothing of the library's output enters the oracle here: from the SAME gradients the oracle
+    encodes in fp64, puts its messages on its own model of the wire, applies the (deterministic)
+    attacks and decodes; the library encodes, receives the same attacks and decodes.  Masks equal,
+    sums within the code's tolerance of each other and of the true sum."""
+    w = wl(code, P, s, d, attacks, "any", 1e-2 if code == "cyc" else 1.0)
+    c = Case(w, wide=False if wire == "one" else wire)
+    try:
+        G = c.G[:, :d].cpu().numpy()
+        f = c.f.cpu().numpy() if code == "cyc" else None
+        # the oracle's side
+        Zo = o.encode_repetition(G, s) if code == "rep" else o.encode_cyclic(G, s)
+        if wire == "one":
+            hi, lo, tau = Zo.astype(np.float32), 0.0, o.TAU_H
+        else:
+            hi, lo = o.two_word_wire(Zo, wire)
+            tau = WIDE[wire][1]
+        hi_t = torch.from_numpy(hi.copy())
+        synth.apply_attacks(hi_t, hi.shape[1], c.adversaries, w.seed)          # edits the first word, as on the GPU
+        Ro = hi_t.numpy().astype(np.float64) + lo if wire != "one" else hi_t.numpy()
+        if code == "rep":
+            uo, mo, so = o.decode_repetition(Ro, s)
+        else:
+            uo, mo, so = o.decode_cyclic(Ro, f, s, d, tau_h=tau)
+        # the library's side
+        c.encode()
+        c.receive()
+        c.u.fill_(float("nan"))
+        mask, status = c.decode()
+        torch.cuda.synchronize()
+        assert status == so == 0
+        assert np.array_equal(mask, mo) and np.array_equal(mask, c.expected_mask())
+        ug = c.u[:d].cpu().numpy()
+        tol = TOL_SUM[code]
+        assert_sum_close(ug, uo, tol, wire)
+        ref = G.astype(np.float64).sum(0)
+        if not (code == "cyc" and wire == "one" and P >= 32):
+            assert rel_l2(ug, ref) <= tol and rel_l2(uo, ref) <= tol
+    finally:
+        c.close()
+
+
 # ------------------------------------------- workgroup footprint boundaries ----
 @pytest.mark.parametrize("d", [255, 256, 257, 1023, 1025, 8191, 8192, 8193, 8449, 16385, 24577, 32767, 32768, 32769,
                                32768 + 8192 + 3, 65535, 65536, 65537, 3 * 32768 - 1, 3 * 32768 + 2049])
