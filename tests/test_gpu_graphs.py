@@ -13,15 +13,18 @@ from paper_1803_09877_amd.runner import Case
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("code,P,s,d,attacks,placement,sigma", [
-    ("rep", 45, 2, 300_001, ("signflip", "signflip"), "distinct_groups", 1e-2),
-    ("cyc", 45, 3, 300_002, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2),
-    ("cyc", 15, 2, 100_001, ("offset", "offset"), "any", 1.0),
+@pytest.mark.parametrize("code,P,s,d,attacks,placement,sigma,wide", [
+    ("rep", 45, 2, 300_001, ("signflip", "signflip"), "distinct_groups", 1e-2, False),
+    ("cyc", 45, 3, 300_002, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2, False),
+    ("cyc", 15, 2, 100_001, ("offset", "offset"), "any", 1.0, False),
+    ("cyc", 45, 3, 300_002, ("noise", "signflip", "noise"), "adjacent_pair", 1e-2, "i8"),     # the benchmark's wire
+    ("cyc", 33, 2, 100_003, ("signflip", "offset"), "any", 1e-2, "bf16"),
+    ("cyc", 15, 2, 100_001, ("offset", "offset"), "any", 1.0, "f32"),
 ])
-def test_graph_replays_match_eager(code, P, s, d, attacks, placement, sigma):
+def test_graph_replays_match_eager(code, P, s, d, attacks, placement, sigma, wide):
     w = synth.Workload(name=f"graph_{code}", code=code, P=P, s=s, d=d, sigma=sigma, attacks=attacks,
                        placement=placement, seed=synth.SEED_BASE + 404)
-    c = Case(w)
+    c = Case(w, wide=wide)
     try:
         mask_dev = torch.zeros(4, dtype=torch.int64, device=c.device)
         status_dev = torch.full((1,), -1, dtype=torch.int32, device=c.device)
@@ -30,6 +33,8 @@ def test_graph_replays_match_eager(code, P, s, d, attacks, placement, sigma):
             c.encode()
             if code == "rep":
                 c.plan.decode_repetition_async(c.R, c.u, mask_dev, status_dev)
+            elif wide:
+                c.plan.decode_cyclic_wide_async(c.R, c.Rlo, c.f, c.u, mask_dev, status_dev)
             else:
                 c.plan.decode_cyclic_async(c.R, c.f, c.u, mask_dev, status_dev)
 
@@ -50,6 +55,8 @@ def test_graph_replays_match_eager(code, P, s, d, attacks, placement, sigma):
         for it in range(4):
             # new received slab: move the adversaries (honest rows restored from Z)
             c.R.copy_(c.Z)
+            if wide:
+                c.Rlo.copy_(c.Zlo)
             shift = [((j + 3 * it) % P, a) for j, a in c.adversaries]
             if code == "rep":                     # keep them in distinct groups
                 shift = [(((j // w.r + it) % (P // w.r)) * w.r + j % w.r, a) for j, a in c.adversaries]
