@@ -197,6 +197,14 @@ int draco_encode_samples_wide(draco_plan* plan, const float* samples_dev, int64_
 int draco_encode_node(draco_plan* plan, int node, const float* node_grads_dev,
                       int64_t ld_g, float* message_dev, void* stream);
 
+/* The same on the two-word wire: one row of each word (message_lo_dev in the
+ * format draco_plan_set_second_word selected, 16-byte aligned), bit-identical
+ * to row `node` of what draco_encode_wide writes.  DRACO_EINVAL for the
+ * repetition code or the unpacked wire. */
+int draco_encode_node_wide(draco_plan* plan, int node, const float* node_grads_dev,
+                           int64_t ld_g, float* message_hi_dev, void* message_lo_dev,
+                           void* stream);
+
 /* ---- decoder (parameter server) --------------------------------------- */
 
 /* D^Rep: per group of r consecutive nodes, majority vote (Algorithm 2, the

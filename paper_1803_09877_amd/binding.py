@@ -50,7 +50,7 @@ EXPORTS = [
     "draco_cyclic_locate_tol", "draco_decode_repetition_static",
     "draco_plan_last_projection_seed", "draco_encode_oneshot", "draco_decode_repetition_oneshot",
     "draco_decode_cyclic_oneshot", "draco_cache_clear", "draco_apply_update", "draco_encode_samples_wide",
-    "draco_plan_set_second_word",
+    "draco_plan_set_second_word", "draco_encode_node_wide",
 ]
 # the measuring instruments of include/draco_bench.h
 BENCH_EXPORTS = ["draco_copy_probe", "draco_plan_set_timing", "draco_plan_kernel_time", "draco_plan_kernel_times"]
@@ -138,6 +138,8 @@ def lib() -> ctypes.CDLL:
     L.draco_encode_samples.restype = i32
     L.draco_encode_samples_wide.argtypes = [vp, vp, i64, i64, vp, vp, i64, vp]
     L.draco_encode_samples_wide.restype = i32
+    L.draco_encode_node_wide.argtypes = [vp, i32, vp, i64, vp, vp, vp]
+    L.draco_encode_node_wide.restype = i32
     L.draco_encode_wide.argtypes = [vp, vp, i64, vp, vp, i64, vp]
     L.draco_encode_wide.restype = i32
     L.draco_decode_cyclic_wide.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
@@ -300,6 +302,12 @@ class Plan:
     def encode_node(self, node: int, node_grads, message, stream=None) -> None:
         _check(lib().draco_encode_node(self._h, node, node_grads.data_ptr(), node_grads.stride(0),
                                        message.data_ptr(), _stream_ptr(stream)))
+
+    def encode_node_wide(self, node: int, node_grads, hi, lo, stream=None) -> None:
+        want = {SECOND_WORD_BF16: "torch.bfloat16", SECOND_WORD_I8: "torch.int8"}.get(self._second_word, "torch.float32")
+        assert str(lo.dtype) == want, (lo.dtype, want)
+        _check(lib().draco_encode_node_wide(self._h, node, node_grads.data_ptr(), node_grads.stride(0), hi.data_ptr(),
+                                            lo.data_ptr(), _stream_ptr(stream)))
 
     def decode_repetition(self, messages, out_sum, stream=None):
         """-> (mask bool[P], status); the sum is written to ``out_sum``."""

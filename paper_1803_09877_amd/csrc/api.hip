@@ -404,13 +404,16 @@ int draco_encode_samples_wide(draco_plan* p, const float* samples_dev, int64_t B
     return encode_samples_impl(p, samples_dev, B, ld_g, messages_hi_dev, static_cast<float*>(messages_lo_dev), true, ld_m, stream);
 }
 
-int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
-                      void* stream) {
+namespace {
+
+int encode_node_impl(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
+                     float* lo_dev, bool wide, void* stream) {
     if (p == nullptr || node < 0 || node >= p->P) return DRACO_EINVAL;
+    if (wide && (p->code != DRACO_CODE_CYCLIC || unpacked(p) || lo_dev == nullptr)) return DRACO_EINVAL;
     int rc = check_slab(node_grads_dev, ld_g, p->d);
     if (rc != DRACO_OK) return rc;
     if (message_dev == nullptr) return DRACO_EINVAL;
-    if (!aligned16(message_dev)) return DRACO_EALIGN;
+    if (!aligned16(message_dev) || (wide && !aligned16(lo_dev))) return DRACO_EALIGN;
     rc = prepare(p);
     if (rc != DRACO_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -420,9 +423,22 @@ int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int6
     else if (unpacked(p))
         HIP_TRY(launch_encode_cyc_real_node(node_grads_dev, ld_g, message_dev, p->coef_dev, node, p->P, p->s, p->d, st));
     else
-        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, nullptr, kSecondWordF32, p->taps, node, p->P, p->s, p->d,
-                                       st));
+        HIP_TRY(launch_encode_cyc_node(node_grads_dev, ld_g, message_dev, wide ? lo_dev : nullptr, lo_format(p), p->taps,
+                                       node, p->P, p->s, p->d, st));
     return DRACO_OK;
+}
+
+}  // namespace
+
+int draco_encode_node(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g, float* message_dev,
+                      void* stream) {
+    return encode_node_impl(p, node, node_grads_dev, ld_g, message_dev, nullptr, false, stream);
+}
+
+int draco_encode_node_wide(draco_plan* p, int node, const float* node_grads_dev, int64_t ld_g,
+                           float* message_hi_dev, void* message_lo_dev, void* stream) {
+    return encode_node_impl(p, node, node_grads_dev, ld_g, message_hi_dev, static_cast<float*>(message_lo_dev), true,
+                            stream);
 }
 
 int draco_decode_repetition_async(draco_plan* p, const float* messages_dev, int64_t ld_m, float* sum_dev,

@@ -806,6 +806,38 @@ def test_encode_node_is_bit_identical_to_the_all_node_form(code, P, s, d):
         c.close()
 
 
+@pytest.mark.parametrize("second", ["f32", "bf16", "i8"])
+@pytest.mark.parametrize("P,s,d", [(15, 2, 3001), (45, 3, 2050), (21, 10, 1030), (45, 16, 1031), (40, 17, 515)])
+def test_encode_node_on_the_two_word_wires(P, s, d, second):
+    """A compute node's own call on its 2s+1 gradients writes both words of its message exactly as
+    the all-node encoder does: every window width's kernel against the one-node kernel, bit for bit."""
+    c = Case(wl("cyc", P, s, d), wide=second)
+    try:
+        c.encode()
+        torch.cuda.synchronize()
+        r = 2 * s + 1
+        for node in (0, 1, P - 2 * s, P - 1):
+            Gn = c.G[[(node + t) % P for t in range(r)]].contiguous()
+            z = torch.full((c.ld_m,), float("nan"), dtype=torch.float32, device=c.device)
+            zl = torch.full((c.ld_m,), 77 if second == "i8" else float("nan"), dtype=c.Zlo.dtype, device=c.device)
+            c.plan.encode_node_wide(node, Gn, z, zl)
+            torch.cuda.synchronize()
+            assert torch.equal(z[:c.mlen].view(torch.int32), c.Z[node, :c.mlen].view(torch.int32)), node
+            bits = {"f32": torch.int32, "bf16": torch.int16, "i8": torch.int8}[second]
+            assert torch.equal(zl[:c.mlen].view(bits), c.Zlo[node, :c.mlen].view(bits)), node
+            assert torch.isnan(z[c.mlen:]).all()
+            assert (zl[c.mlen:] == 77).all() if second == "i8" else torch.isnan(zl[c.mlen:].float()).all()
+        rep = B.Plan(B.CODE_REPETITION, 15, 2, 100)
+        try:
+            with pytest.raises(B.DracoError) as e:
+                rep.encode_node_wide(0, c.G[:5], c.Z[0], torch.zeros_like(c.Z[0]))
+            assert e.value.status == B.EINVAL
+        finally:
+            rep.close()
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------- random sweep -----
 def test_random_shapes_and_attacks():
     """Seeded random (code, P, s, d, adversary count, attack mix, placement) cases."""
