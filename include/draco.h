@@ -109,7 +109,8 @@ int draco_plan_set_wire(draco_plan* plan, int wire);
  * DRACO_SECOND_WORD_I8: lo is an 8-bit signed code q of the residual in units
  * of the spacing u of fp32 numbers at hi: with E the exponent field of hi,
  * u = 2^(max(E, 24) - 150), q = (z - hi) / u * 254 rounded to nearest even,
- * -127 <= q <= 127 (0 where hi is not finite); it stands for q * u / 254.
+ * -127 <= q <= 127 (unspecified next to a hi that is not finite); it stands
+ * for q * u / 254, and the decoder accepts any byte.
  * hi + lo is within u / 508 <= 2^-32 |z| of z at 5 bytes per value: the
  * decoded sum stays within about 1e-6 of the true one at (P, s) = (45, 3)
  * and 5e-6 at (45, 5).  messages_lo_dev then points at [P][ld_m] bytes,
