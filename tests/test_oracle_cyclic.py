@@ -720,3 +720,31 @@ def test_code8_threshold_sits_between_the_floors():
         gamma = o.project(o.wire_to_complex(R), f)
         floors.append(np.abs(o.syndromes(gamma, s)).max() / np.median(np.abs(gamma)))
     assert floors[0] <= o.TAU_H_I8 / 8 and 4 * o.TAU_H_I8 <= floors[1], floors
+
+
+# ------------------------------------------- structure of W the encoders rely on --
+@pytest.mark.parametrize("P,s", [(5, 1), (9, 1), (10, 2), (15, 2), (8, 3), (7, 3), (45, 3), (45, 5), (33, 16)])
+def test_weights_factor_into_unit_phases_and_real_taps(P, s):
+    """The nodes that do not hold a gradient are consecutive on the circle, so each factor
+    w^a - w^b of W's closed form (Sec. 3, the solve for q_j) is a unit phase times a sine and
+        W[(j+t) mod P][j] = A_j * rho_t * B_{j+t},   A_j = c e^{i pi D j / P},  B_k = e^{i pi D k / P},
+    D = P - 2s - 1, with REAL taps rho_t that do not depend on the node and are symmetric in t.
+    Checked on the oracle's own W (the product form and, where it is accurate, the solve)."""
+    D, r = P - 2 * s - 1, 2 * s + 1
+    mats = [o.cyclic_weights(P, s)] + ([o.cyclic_weights_solve(P, s)] if P <= 15 else [])
+    for W in mats:
+        c = W[0][0] / abs(W[0][0])
+        rho = np.zeros((P, r), dtype=np.complex128)
+        for j in range(P):
+            for t in range(r):
+                rho[j, t] = W[(j + t) % P][j] / (c * np.exp(1j * np.pi * D * j / P) * np.exp(1j * np.pi * D * (j + t) / P))
+        scale = np.abs(rho).max()
+        tol = 1e-11 if P <= 15 else 1e-8                       # the solve and the long products lose digits at P = 45
+        assert np.abs(rho.imag).max() <= tol * scale          # real
+        assert np.abs(rho - rho[0]).max() <= tol * scale      # the same taps at every node
+        assert np.abs(rho[0].real - rho[0].real[::-1]).max() <= tol * scale   # symmetric window
+        assert (rho[0].real > 0).all()
+        # and the closed form of a tap: (2^D / sqrt P) * prod over the non-holders of |sin(pi (t - u) / P)|
+        want = np.array([2.0 ** D / np.sqrt(P) * np.prod([abs(np.sin(np.pi * (t - u) / P)) for u in range(r, P)])
+                         for t in range(r)])
+        assert np.allclose(rho[0].real, want, rtol=1e-7 if P > 15 else 1e-10)
