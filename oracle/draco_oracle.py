@@ -423,6 +423,43 @@ def _unexplained(hk: np.ndarray, P: int, s: int, V: list) -> float:
     return float(np.max(np.abs(hk - M @ np.linalg.lstsq(M, hk, rcond=None)[0])))
 
 
+# A projection this many times tau_h * rho in size is beyond what fp64 syndromes resolve: its own
+# rounding (2^-53 of it) then reaches the zero threshold tau_h * rho.  See phi_from_projection.
+HUGE_OVER_TAU = 2.0 ** 48
+
+
+def _phi_attempt(gamma: np.ndarray, s: int, tau_h: float):
+    """One pass of phi's steps 2-4 on finite projections -> (located nodes in ranking order, t, found)."""
+    P = gamma.shape[0]
+    t = np.zeros(P, dtype=np.complex128)
+    rho = float(np.median(np.abs(gamma)))
+    hk = syndromes(gamma, s)
+    if _unexplained(hk, P, s, []) <= tau_h * rho:
+        return [], t, True
+    h = np.zeros(P, dtype=np.complex128)
+    h[P - 2 * s:] = hk
+    H = np.empty((s, s), dtype=np.complex128)
+    rhs = np.empty(s, dtype=np.complex128)
+    for i in range(1, s + 1):
+        for k in range(s):
+            H[i - 1, k] = h[P - s - i + k]
+        rhs[i - 1] = h[P - i]
+    Us, sv, Vh = np.linalg.svd(H)
+    keep = sv > tau_h * rho
+    beta = (Vh.conj().T[:, keep] * (1.0 / sv[keep])) @ (Us.conj().T[keep] @ rhs)
+    for ell in range(P - 2 * s):
+        acc = 0.0 + 0.0j
+        for u in range(s):
+            acc += beta[u] * h[(ell + u - s) % P]
+        h[ell] = acc
+    t = idft_matrix(P) @ h
+    order = [int(j) for j in np.argsort(-np.abs(t), kind="stable")[:s]]
+    for a in range(1, s + 1):
+        if _unexplained(hk, P, s, order[:a]) <= tau_h * rho:
+            return order[:a], t, True
+    return order, t, False
+
+
 def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     """phi's steps 2-4 on the P projections gamma' = f R.
 
@@ -444,51 +481,39 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     In exact arithmetic t has exactly |V| non-zeros and this is the same set.
     Returns (mask, t, status); LOCATE_FAILED when no leading part of length
     <= s accounts for the syndromes (more than s liars), with mask = the s
-    largest |t_j| as a best effort.  Non-finite projections: see the first
-    lines of the body.
+    largest |t_j| as a best effort.
+
+    Messages that are no vectors of R^d, or none that fp64 can weigh: a node
+    whose projection is NaN or Inf is flagged outright and its projection taken
+    as 0, which leaves an ordinary error f.(-z_j) at a known node for the steps
+    above to account for like any other.  A finite projection can still be so
+    large that its own fp64 rounding drowns the zero threshold (the adversary
+    may send 1e30): when the steps above find no set, every node whose
+    projection exceeds HUGE_OVER_TAU * tau_h * rho is treated the same way --
+    flagged, projection 0 -- and the steps run once more; if that flags more
+    than s nodes the decode fails as before.  (The paper's n_j are arbitrary
+    reals and its arithmetic exact; this is what keeps Definition 2 for them.)
     """
     gamma = np.array(gamma, dtype=np.complex128)
     P = gamma.shape[0]
     mask = np.zeros(P, dtype=bool)
-    t = np.zeros(P, dtype=np.complex128)
-    # A message with NaN or Inf entries is no vector of R^d: its node is flagged outright
-    # and its projection taken as 0, which leaves an ordinary error f.(-z_j) at a known node
-    # for the steps below to account for like any other.
     broken = ~np.isfinite(gamma)
     gamma[broken] = 0.0
     mask |= broken
     if s == 0:
-        return mask, t, (LOCATE_FAILED if broken.any() else OK)
+        return mask, np.zeros(P, dtype=np.complex128), (LOCATE_FAILED if broken.any() else OK)
     if int(broken.sum()) > s:
-        return mask, t, LOCATE_FAILED
-    rho = float(np.median(np.abs(gamma)))
-    hk = syndromes(gamma, s)
-    if _unexplained(hk, P, s, []) <= tau_h * rho:
-        return mask, t, OK
-    h = np.zeros(P, dtype=np.complex128)
-    h[P - 2 * s:] = hk
-    H = np.empty((s, s), dtype=np.complex128)
-    rhs = np.empty(s, dtype=np.complex128)
-    for i in range(1, s + 1):
-        for k in range(s):
-            H[i - 1, k] = h[P - s - i + k]
-        rhs[i - 1] = h[P - i]
-    Us, sv, Vh = np.linalg.svd(H)
-    keep = sv > tau_h * rho
-    beta = (Vh.conj().T[:, keep] * (1.0 / sv[keep])) @ (Us.conj().T[keep] @ rhs)
-    for ell in range(P - 2 * s):
-        acc = 0.0 + 0.0j
-        for u in range(s):
-            acc += beta[u] * h[(ell + u - s) % P]
-        h[ell] = acc
-    t = idft_matrix(P) @ h
-    order = [int(j) for j in np.argsort(-np.abs(t), kind="stable")[:s]]
-    for a in range(1, s + 1):
-        if _unexplained(hk, P, s, order[:a]) <= tau_h * rho:
-            mask[order[:a]] = True
-            return mask, t, (OK if int(mask.sum()) <= s else LOCATE_FAILED)
-    mask[order] = True
-    return mask, t, LOCATE_FAILED
+        return mask, np.zeros(P, dtype=np.complex128), LOCATE_FAILED
+    located, t, found = _phi_attempt(gamma, s, tau_h)
+    if not found:
+        rho = float(np.median(np.abs(gamma)))
+        huge = np.abs(gamma) > HUGE_OVER_TAU * tau_h * rho
+        if huge.any() and int((mask | huge).sum()) <= s:
+            gamma[huge] = 0.0
+            mask |= huge
+            located, t, found = _phi_attempt(gamma, s, tau_h)
+    mask[located] = True
+    return mask, t, (OK if found and int(mask.sum()) <= s else LOCATE_FAILED)
 
 
 def phi(Rc: np.ndarray, f: np.ndarray, s: int) -> np.ndarray:

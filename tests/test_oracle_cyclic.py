@@ -748,3 +748,97 @@ def test_weights_factor_into_unit_phases_and_real_taps(P, s):
         want = np.array([2.0 ** D / np.sqrt(P) * np.prod([abs(np.sin(np.pi * (t - u) / P)) for u in range(r, P)])
                          for t in range(r)])
         assert np.allclose(rho[0].real, want, rtol=1e-7 if P > 15 else 1e-10)
+
+
+# ------------------------------------------------ adversaries that send enormous values --
+TAUS = [("one", None, o.TAU_H), ("i8", "i8", o.TAU_H_I8), ("bf16", "bf16", o.TAU_H_BF16), ("f32", "f32", o.TAU_H_WIDE)]
+
+
+def _received(Z, second):
+    if second is None:
+        return Z.astype(np.float32).astype(np.float64)
+    hi, lo = o.two_word_wire(Z, second)
+    return hi.astype(np.float64) + np.asarray(lo, dtype=np.float64)
+
+
+@pytest.mark.parametrize("P,s,d", [(15, 2, 4_000), (45, 3, 6_000)])
+@pytest.mark.parametrize("name,second,tau", TAUS)
+def test_enormous_lies_are_located_on_every_wire(P, s, d, name, second, tau):
+    """Definition 2 puts no bound on what an adversary sends.  Lies from 1e2 to 1e30 times the size
+    of an honest message (up to the edge of fp32) are located and the sum recovered, on every wire's
+    threshold: up to about tau * 2^53 by phi as it stands, beyond that because the node is set aside
+    like one that sent NaN.  The sum's tolerance is the wire's."""
+    G = _grads(P, d, 5, 1e-2)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    R0 = _received(o.encode_cyclic(G, s), second)
+    f = _f(d // 2, 2)
+    scale = np.abs(R0).max()
+    rng = np.random.default_rng(P)
+    tol = 1e-3 if name == "one" else 1e-4
+    for mag in (1e2, 1e5, 1e8, 1e11, 1e14, 1e20, 1e30):
+        liars = sorted(rng.choice(P, size=s, replace=False).tolist())
+        R = R0.copy()
+        for k, j in enumerate(liars):                      # one coherent offset, one noise, one reversed message
+            if k % 3 == 0:
+                R[j] += mag * scale
+            elif k % 3 == 1:
+                R[j] = rng.standard_normal(R.shape[1]) * mag * scale
+            else:
+                R[j] *= -mag
+        u, mask, st = o.decode_cyclic(R, f, s, d, tau_h=tau)
+        assert st == o.OK and sorted(np.flatnonzero(mask)) == liars, (mag, st, np.flatnonzero(mask), liars)
+        assert np.linalg.norm(u - ref) <= tol * np.linalg.norm(ref), mag
+
+
+@pytest.mark.parametrize("name,second,tau", TAUS)
+def test_a_small_lie_cannot_hide_behind_an_enormous_one(name, second, tau):
+    """Two colluding nodes: one sends 1e25 times an honest message, the other a lie of ordinary size
+    (10 times).  The first one's fp64 rounding alone would bury the second's syndromes; with the
+    first set aside the second is found."""
+    P, s, d = 15, 2, 4_000
+    G = _grads(P, d, 6, 1.0)
+    ref = np.sum(G.astype(np.float64), axis=0)
+    R0 = _received(o.encode_cyclic(G, s), second)
+    f = _f(d // 2, 4)
+    rng = np.random.default_rng(3)
+    for (a, b) in ((2, 9), (7, 8), (14, 0)):
+        R = R0.copy()
+        R[a] = rng.standard_normal(R.shape[1]) * 1e25 * np.abs(R0).max()
+        R[b] += 10.0 * rng.standard_normal(R.shape[1]) * np.abs(R0).max()
+        u, mask, st = o.decode_cyclic(R, f, s, d, tau_h=tau)
+        assert st == o.OK and sorted(np.flatnonzero(mask)) == sorted((a, b))
+        assert np.linalg.norm(u - ref) <= 1e-4 * np.linalg.norm(ref)
+
+
+def test_a_heavy_tailed_honest_batch_is_not_mistaken_for_lies():
+    """Honest gradients may differ in size by many orders (one sample's gradient 3e9 times the
+    rest, so that its five holders' projections pass the size at which a node may be set aside):
+    large projections alone flag nobody -- nodes are set aside only after phi has failed."""
+    P, s, d = 15, 2, 2_000
+    G = _grads(P, d, 8, 1.0).astype(np.float64)
+    G[4] *= 3e9
+    G32 = G.astype(np.float32)
+    ref = np.sum(G32.astype(np.float64), axis=0)
+    Z = o.encode_cyclic(G32, s)
+    f = _f(d // 2, 5)
+    gamma = o.project(o.wire_to_complex(Z), f)
+    big = np.abs(gamma) > o.HUGE_OVER_TAU * o.TAU_H * np.median(np.abs(gamma))
+    assert big.sum() > s                                                # holders of that sample: more than s of them
+    u, mask, st = o.decode_cyclic(Z, f, s, d)                           # exact messages: nothing to find
+    assert st == o.OK and not mask.any()
+    assert np.linalg.norm(u - ref) <= 1e-6 * np.linalg.norm(ref)
+    R = Z.copy()
+    R[11] *= -100.0                                                     # and an ordinary liar among them is still found
+    u, mask, st = o.decode_cyclic(R, f, s, d)
+    assert st == o.OK and sorted(np.flatnonzero(mask)) == [11]
+
+
+def test_more_enormous_lies_than_s_still_fail():
+    P, s, d = 15, 2, 2_000
+    G = _grads(P, d, 9, 1.0)
+    R = o.encode_cyclic(G, s).astype(np.float32).astype(np.float64)
+    f = _f(d // 2, 6)
+    for j in (1, 5, 9):
+        R[j] *= 1e28
+    u, mask, st = o.decode_cyclic(R, f, s, d)
+    assert st == o.LOCATE_FAILED
