@@ -487,12 +487,16 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     whose projection is NaN or Inf is flagged outright and its projection taken
     as 0, which leaves an ordinary error f.(-z_j) at a known node for the steps
     above to account for like any other.  A finite projection can still be so
-    large that its own fp64 rounding drowns the zero threshold (the adversary
-    may send 1e30): when the steps above find no set, every node whose
-    projection exceeds HUGE_OVER_TAU * tau_h * rho is treated the same way --
-    flagged, projection 0 -- and the steps run once more; if that flags more
-    than s nodes the decode fails as before.  (The paper's n_j are arbitrary
-    reals and its arithmetic exact; this is what keeps Definition 2 for them.)
+    large that its own fp64 rounding drowns the zero threshold, or swallows a
+    smaller lie whole (the adversary may send 1e30).  Call a projection
+    enormous when it exceeds HUGE_OVER_TAU * tau_h * rho.  After the steps
+    above, the enormous nodes among those they located -- or, if they found no
+    set, all enormous nodes -- are treated like broken ones (flagged,
+    projection 0) and the steps run once more, provided that keeps the flagged
+    nodes within s; otherwise the first result stands.  Nodes that phi did not
+    locate are never set aside while phi succeeds, so an honest batch with a
+    heavy tail flags nobody.  (The paper's n_j are arbitrary reals and its
+    arithmetic exact; this is what keeps Definition 2 for them.)
     """
     gamma = np.array(gamma, dtype=np.complex128)
     P = gamma.shape[0]
@@ -505,13 +509,16 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     if int(broken.sum()) > s:
         return mask, np.zeros(P, dtype=np.complex128), LOCATE_FAILED
     located, t, found = _phi_attempt(gamma, s, tau_h)
-    if not found:
-        rho = float(np.median(np.abs(gamma)))
-        huge = np.abs(gamma) > HUGE_OVER_TAU * tau_h * rho
-        if huge.any() and int((mask | huge).sum()) <= s:
-            gamma[huge] = 0.0
-            mask |= huge
-            located, t, found = _phi_attempt(gamma, s, tau_h)
+    rho = float(np.median(np.abs(gamma)))
+    aside = np.abs(gamma) > HUGE_OVER_TAU * tau_h * rho
+    if found:
+        among = np.zeros(P, dtype=bool)
+        among[located] = True
+        aside &= among
+    if aside.any() and int((mask | aside).sum()) <= s:
+        gamma[aside] = 0.0
+        mask |= aside
+        located, t, found = _phi_attempt(gamma, s, tau_h)
     mask[located] = True
     return mask, t, (OK if found and int(mask.sum()) <= s else LOCATE_FAILED)
 

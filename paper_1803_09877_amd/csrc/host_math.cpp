@@ -189,6 +189,23 @@ cplx_t CyclicCode::W(int k, int j) const {
     return node_phase[j] * real_taps[t] * row_phase[j + t];
 }
 
+namespace {
+
+double median_size(int P, const std::complex<double>* gamma) {
+    std::vector<double> mags(P);
+    for (int j = 0; j < P; ++j) mags[j] = std::abs(gamma[j]);
+    std::sort(mags.begin(), mags.end());
+    return (P % 2) ? mags[P / 2] : (double)(((real_t)mags[P / 2 - 1] + (real_t)mags[P / 2]) / 2);
+}
+
+// One pass of phi's steps 2-4 over finite projections: flags the located nodes in `mask` (on
+// failure: the s largest |t_j|), fills t_out, returns whether a set of at most s nodes accounts
+// for the syndromes.
+bool locate_attempt(int P, int s, double tau, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
+                    std::vector<std::complex<double>>& t_out);
+
+}  // namespace
+
 bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_in, std::vector<uint8_t>& mask,
                    std::vector<std::complex<double>>& t_out) {
     mask.assign(P, 0);
@@ -196,7 +213,6 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
     // A message with NaN or Inf entries is no vector of R^d: its node is flagged outright and
     // its projection taken as 0, which leaves an ordinary error at a known node.
     std::vector<std::complex<double>> clean(gamma_in, gamma_in + P);
-    const std::complex<double>* gamma = clean.data();
     int broken = 0;
     for (int j = 0; j < P; ++j) {
         if (!std::isfinite(clean[j].real()) || !std::isfinite(clean[j].imag())) {
@@ -207,10 +223,46 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
     }
     if (s == 0) return broken == 0;
     if (broken > s) return false;
-    std::vector<double> mags(P);
-    for (int j = 0; j < P; ++j) mags[j] = std::abs(gamma[j]);
-    std::sort(mags.begin(), mags.end());
-    const real_t rho = (P % 2) ? (real_t)mags[P / 2] : ((real_t)mags[P / 2 - 1] + (real_t)mags[P / 2]) / 2;
+    std::vector<uint8_t> located;
+    bool found = locate_attempt(P, s, tau, clean.data(), located, t_out);
+    {
+        // A finite projection can be so large that its own fp64 rounding drowns the zero threshold
+        // or swallows a smaller lie whole (an adversary may send 1e30).  The enormous nodes among
+        // those phi located -- or all enormous nodes, if it found no set -- are set aside like
+        // broken ones and phi runs once more, provided the flagged nodes stay within s.  Nodes phi
+        // did not locate are never set aside while it succeeds: heavy-tailed honest batches flag nobody.
+        const double limit = kHugeOverTau * tau * median_size(P, clean.data());
+        std::vector<uint8_t> aside(P, 0);
+        int count = 0;
+        for (int j = 0; j < P; ++j) {
+            aside[j] = (std::abs(clean[j]) > limit && (!found || located[j])) ? 1 : 0;
+            count += aside[j];
+        }
+        if (count > 0 && broken + count <= s) {
+            for (int j = 0; j < P; ++j) {
+                if (aside[j]) {
+                    clean[j] = 0;
+                    mask[j] = 1;
+                }
+            }
+            found = locate_attempt(P, s, tau, clean.data(), located, t_out);
+        }
+    }
+    int total = 0;
+    for (int j = 0; j < P; ++j) {
+        mask[j] = (mask[j] || located[j]) ? 1 : 0;
+        total += mask[j];
+    }
+    return found && total <= s;
+}
+
+namespace {
+
+bool locate_attempt(int P, int s, double tau, const std::complex<double>* gamma, std::vector<uint8_t>& mask,
+                    std::vector<std::complex<double>>& t_out) {
+    mask.assign(P, 0);
+    t_out.assign(P, std::complex<double>(0, 0));
+    const real_t rho = (real_t)median_size(P, gamma);
     const real_t zero = (real_t)tau * rho;
     const real_t isq = 1 / std::sqrt((real_t)P);
 
@@ -270,14 +322,14 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
         std::vector<int> V(order.begin(), order.begin() + a);
         if (unexplained(P, s, hk, V) <= zero) {
             for (int j : V) mask[j] = 1;
-            int total = 0;
-            for (int j = 0; j < P; ++j) total += mask[j];
-            return total <= s;
+            return true;
         }
     }
     for (int j : order) mask[j] = 1;
     return false;
 }
+
+}  // namespace
 
 bool cyclic_recombination_vector(int P, int s, const std::vector<uint8_t>& mask,
                                  std::vector<cplx_t>& b) {

@@ -44,6 +44,10 @@ constexpr double kTauHBf16 = 32.0 / 8589934592.0;
 // And with an 8-bit second word (the residual in 254ths of the first word's spacing).
 constexpr double kTauHI8 = 32.0 / 4294967296.0;
 
+// A projection more than kHugeOverTau * tau * (median projection) in size is beyond what fp64
+// syndromes resolve (its rounding reaches the zero threshold): see cyclic_locate.
+constexpr double kHugeOverTau = 281474976710656.0;   // 2^48
+
 // phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns
 // true on success, false when no set of at most s nodes accounts for the

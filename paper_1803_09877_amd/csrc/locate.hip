@@ -20,6 +20,7 @@
 //     subtraction, never by an integer division;
 //   * the honest nodes are compacted with wavefront ballots.
 // Limits: P <= 256, s <= kLocateMaxS.
+#include "host_math.hpp"
 #include "kernels.hpp"
 
 namespace draco {
@@ -228,7 +229,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         my_broken += ok ? 0 : 1;
         sm.gam[j] = g;
         sm.root[j] = roots[j];
-        sm.mag[j] = sqrt(cnorm2(g));
         sm.mask[j] = ok ? 0 : 1;
     }
     if (lane == 0) sm.nv = 0;
@@ -236,7 +236,16 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     const int broken = (int)group_sum<kW>((double)my_broken);
 
     if (broken > s) status = 2;  // DRACO_LOCATE_FAILED: more broken messages than tolerated
-    if (s > 0 && broken <= s) {
+    // At most two passes of phi.  A projection beyond what fp64 syndromes resolve (more than
+    // kHugeOverTau * tau * rho in size: its rounding alone reaches the zero threshold or swallows a
+    // smaller lie whole; an adversary may send 1e30) is "enormous".  After the first pass the
+    // enormous nodes among those it located -- or all enormous nodes, if it found no set -- are set
+    // aside like broken ones and phi runs once more, provided the flagged nodes stay within s.
+    // Every branch below is taken by all 64 lanes together.
+    int aside = broken;  // nodes flagged outright so far
+    for (int pass = 0; pass < 2 && s > 0 && broken <= s; ++pass) {
+        for (int j = lane; j < P; j += kW) sm.mag[j] = sqrt(cnorm2(sm.gam[j]));
+        __syncthreads();
         // rho = median |gamma_j| by rank counting
         for (int j = lane; j < P; j += kW) {
             const double mj = sm.mag[j];
@@ -280,6 +289,9 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         __syncthreads();
         const double hmax2 = group_max<kW>(mymax);
 
+        int found = 0;      // length of the leading part of the ranking that accounts for the syndromes
+        bool located = true;
+        fitted = 0;
         if (hmax2 > zero2) {
             // ---- beta: least squares on the s x s system, singular values <= zero dropped
             // (one-sided Jacobi; lane i owns row i of A and of V)
@@ -388,7 +400,6 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             __syncthreads();
             // ---- shortest leading part of the ranking whose errors account for the syndromes: the
             // residual of the syndromes loses its component along each new orthonormal column
-            int found = 0;
             double2 res = lane < 2 * s ? sm.hk[lane] : make_double2(0.0, 0.0);
             for (int a = 1; a <= s; ++a) {
                 const int v = sm.order[a - 1];
@@ -407,14 +418,46 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                     break;
                 }
             }
-            const int take = found ? found : s;
-            if (!found) status = 2;
+            located = found != 0;
             fitted = found;
-            if (lane < take) sm.mask[sm.order[lane]] = 1;
+        }
+        bool last = pass == 1;
+        if (!last) {
+            const double limit = kHugeOverTau * tau * rho;
+            auto set_aside = [&](int j) {   // enormous, not flagged yet, and located if anything was
+                if (sm.mask[j] != 0 || !(sqrt(cnorm2(sm.gam[j])) > limit)) return false;
+                if (!located) return true;
+                for (int i = 0; i < found; ++i)
+                    if (sm.order[i] == j) return true;
+                return false;
+            };
+            int mine = 0;
+            for (int j = lane; j < P; j += kW) mine += set_aside(j) ? 1 : 0;
+            const int huge = (int)group_sum<kW>((double)mine);
+            if (huge == 0 || aside + huge > s) {
+                last = true;   // nothing to set aside, or too many: the first pass stands
+            } else {
+                bool go[(kMaxNodes + kW - 1) / kW];
+                for (int j = lane, k = 0; j < P; j += kW, ++k) go[k] = set_aside(j);
+                for (int j = lane, k = 0; j < P; j += kW, ++k) {
+                    if (go[k]) {
+                        sm.gam[j] = make_double2(0.0, 0.0);
+                        sm.mask[j] = 1;
+                    }
+                }
+                aside += huge;
+                __syncthreads();
+            }
+        }
+        if (last) {
+            const int take = located ? found : s;   // a failed decode flags the s largest |t_j|
+            if (!located) status = 2;
+            if (hmax2 > zero2 && lane < take) sm.mask[sm.order[lane]] = 1;
             __syncthreads();
             int mine = 0;
             for (int j = lane; j < P; j += kW) mine += sm.mask[j];
             if ((int)group_sum<kW>((double)mine) > s) status = 2;
+            break;
         }
     }
 

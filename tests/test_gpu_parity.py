@@ -292,6 +292,56 @@ def test_cyc_nonfinite_messages_are_flagged_and_survived(bad):
     c = run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, check_true_sum=1e-5)
 
 
+@pytest.mark.parametrize("wire", ["one", "i8", "bf16", "f32"])
+@pytest.mark.parametrize("P,s,d", [(15, 2, 8_001), (45, 3, 20_000)])
+def test_cyc_enormous_lies_are_located(P, s, d, wire):
+    """Definition 2 bounds nothing an adversary sends: first words scaled by 1e2 .. 1e30 (the edge
+    of fp32), alone or with an ordinary lie at another node hiding behind them, on every wire.
+    Mask, status and sum as the oracle's on the same received words; both decoder forms."""
+    w = wl("cyc", P, s, d, (), "any", 1e-2)
+    c = Case(w, wide=False if wire == "one" else wire)
+    tau = o.TAU_H if wire == "one" else WIDE[wire][1]
+    try:
+        c.encode()
+        torch.cuda.synchronize()
+        ref = c.G[:, :d].double().sum(0).cpu().numpy()
+        g = torch.Generator(device=c.device)
+        g.manual_seed(5)
+        for it, mag in enumerate((1e2, 1e6, 1e9, 1e12, 1e20, 1e30)):
+            c.receive()
+            big, small = (3 + it) % P, (4 + 5 * it) % P
+            scale = float(c.Z[:, :c.mlen].abs().max())
+            if it % 2 == 0:
+                c.R[big, :c.mlen] = torch.randn(c.mlen, generator=g, device=c.device) * min(mag * scale, 1e37)
+            else:
+                c.R[big, :c.mlen] *= -mag
+            liars = {big}
+            if s >= 2 and small != big:
+                c.R[small, :c.mlen] += 10.0 * scale * torch.randn(c.mlen, generator=g, device=c.device)
+                liars.add(small)
+            Rhi = c.R[:, :c.mlen].cpu().numpy()
+            Rw = Rhi.astype(np.float64) + (second_word_values(Rhi, c.Rlo[:, :c.mlen], wire) if wire != "one" else 0.0)
+            uo, mo, so = o.decode_cyclic(Rw, c.f.cpu().numpy(), s, d, tau_h=tau)
+            assert so == o.OK and set(np.flatnonzero(mo)) == liars, (mag, np.flatnonzero(mo), liars)
+            for hostphi in ((False, True) if wire == "one" else (False,)):
+                c.u.fill_(float("nan"))
+                mask, status = c.decode(hostphi=hostphi)
+                torch.cuda.synchronize()
+                assert status == B.OK and np.array_equal(mask, mo), (mag, hostphi, status, np.flatnonzero(mask))
+                ug = c.u[:d].cpu().numpy()
+                assert_sum_close(ug, uo, 1e-4 if wire == "one" else 1e-6, (mag, hostphi))
+                assert rel_l2(ug, ref) <= (2e-3 if wire == "one" and P >= 32 else 1e-4)
+    finally:
+        c.close()
+
+
+def test_cyc_more_enormous_lies_than_s_is_reported():
+    def edit(c):
+        for j in (1, 4, 6):
+            c.R[j, :c.mlen] *= 1e28
+    run_and_check(wl("cyc", 9, 2, 4001), extra_edit=edit, expect_status=B.LOCATE_FAILED)
+
+
 def test_cyc_more_broken_messages_than_s_is_reported():
     def edit(c):
         for j in (1, 4, 6):

@@ -169,6 +169,38 @@ def test_locator_flags_nonfinite_projections_and_still_locates():
         assert sorted(np.flatnonzero(mask)) == sorted(V) == sorted(np.flatnonzero(omask))
 
 
+@pytest.mark.parametrize("tau", [B.TAU, B.TAU_I8, B.TAU_BF16, B.TAU_WIDE])
+def test_locator_sets_enormous_projections_aside(tau):
+    """Lies of 1e2 .. 1e30 times an honest message, on every wire's threshold: the library's host
+    locator and the oracle's flag the same nodes (the enormous ones are set aside like broken ones
+    once phi has failed); a small lie behind an enormous one is found; more than s enormous lies fail."""
+    P, s, h = 15, 2, 200
+    plan = B.Plan(B.CODE_CYCLIC, P, s, 2 * h)
+    rng = np.random.default_rng(12)
+    G = rng.standard_normal((P, 2 * h)).astype(np.float32)
+    Zc = o.encode_cyclic_complex(o.pack_complex(G), s)
+    f = 1.0 + rng.standard_normal(h)
+    scale = np.abs(Zc).max()
+    for mag in (1e2, 1e6, 1e10, 1e14, 1e20, 1e30):
+        for V in ((3,), (3, 4), (0, 14), (6, 11)):
+            Rc = Zc.copy()
+            Rc[V[0]] = (rng.standard_normal(h) + 1j * rng.standard_normal(h)) * mag * scale
+            if len(V) > 1:
+                Rc[V[1]] += 10.0 * scale * rng.standard_normal(h)          # an ordinary lie behind it
+            gamma = o.project(Rc, f)
+            mask, _, st = plan.cyclic_locate(gamma, tau=tau)
+            omask, _, ost = o.phi_from_projection(gamma, s, tau)
+            assert st == B.OK == ost, (mag, V)
+            assert sorted(np.flatnonzero(mask)) == sorted(V) == sorted(np.flatnonzero(omask)), (mag, V)
+    Rc = Zc.copy()
+    for j in (1, 5, 9):
+        Rc[j] *= 1e28
+    gamma = o.project(Rc, f)
+    mask, _, st = plan.cyclic_locate(gamma, tau=tau)
+    _, _, ost = o.phi_from_projection(gamma, s, tau)
+    assert st == B.LOCATE_FAILED == ost
+
+
 @pytest.mark.parametrize("P,s", [(4, 1), (7, 2), (9, 4)])
 def test_recombination_vector_every_honest_set(P, s):
     plan = B.Plan(B.CODE_CYCLIC, P, s, 8)
