@@ -423,9 +423,11 @@ def _unexplained(hk: np.ndarray, P: int, s: int, V: list) -> float:
     return float(np.max(np.abs(hk - M @ np.linalg.lstsq(M, hk, rcond=None)[0])))
 
 
-# A projection this many times tau_h * rho in size is beyond what fp64 syndromes resolve: its own
-# rounding (2^-53 of it) then reaches the zero threshold tau_h * rho.  See phi_from_projection.
-HUGE_OVER_TAU = 2.0 ** 48
+# A projection more than this many times rho in size is "enormous": its fp64 rounding (2^-53 of
+# it), times the error growth of the s-error locator (1e3 - 1e5 at P = 45), comes within reach of
+# the zero thresholds.  Lies of a hundred times an honest message stay below it.  See
+# phi_from_projection.
+ENORMOUS = 2.0 ** 10
 
 
 def _phi_attempt(gamma: np.ndarray, s: int, tau_h: float):
@@ -489,11 +491,13 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     above to account for like any other.  A finite projection can still be so
     large that its own fp64 rounding drowns the zero threshold, or swallows a
     smaller lie whole (the adversary may send 1e30).  Call a projection
-    enormous when it exceeds HUGE_OVER_TAU * tau_h * rho.  After the steps
-    above, the enormous nodes among those they located -- or, if they found no
-    set, all enormous nodes -- are treated like broken ones (flagged,
-    projection 0) and the steps run once more, provided that keeps the flagged
-    nodes within s; otherwise the first result stands.  Nodes that phi did not
+    enormous when it exceeds ENORMOUS * rho.  After the steps above, the
+    enormous nodes among those they located are treated like broken ones
+    (flagged, projection 0); if the steps found no set, the top layer of the
+    enormous nodes is (those within a factor ENORMOUS of the largest).  Then
+    the steps run again, provided the flagged nodes stay within s; this
+    repeats (lies of 1e30, 1e20 and 1e10 come off one layer at a time) until a
+    pass sets nothing aside, whose result stands.  Nodes that phi did not
     locate are never set aside while phi succeeds, so an honest batch with a
     heavy tail flags nobody.  (The paper's n_j are arbitrary reals and its
     arithmetic exact; this is what keeps Definition 2 for them.)
@@ -508,17 +512,21 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
         return mask, np.zeros(P, dtype=np.complex128), (LOCATE_FAILED if broken.any() else OK)
     if int(broken.sum()) > s:
         return mask, np.zeros(P, dtype=np.complex128), LOCATE_FAILED
-    located, t, found = _phi_attempt(gamma, s, tau_h)
-    rho = float(np.median(np.abs(gamma)))
-    aside = np.abs(gamma) > HUGE_OVER_TAU * tau_h * rho
-    if found:
-        among = np.zeros(P, dtype=bool)
-        among[located] = True
-        aside &= among
-    if aside.any() and int((mask | aside).sum()) <= s:
+    while True:          # every pass but the last flags at least one more node: at most s + 1 passes
+        located, t, found = _phi_attempt(gamma, s, tau_h)
+        rho = float(np.median(np.abs(gamma)))
+        size = np.abs(gamma)
+        aside = (size > ENORMOUS * rho) & ~mask
+        if found:
+            among = np.zeros(P, dtype=bool)
+            among[located] = True
+            aside &= among
+        elif aside.any():
+            aside &= size * ENORMOUS > size[aside].max()
+        if not aside.any() or int((mask | aside).sum()) > s:
+            break
         gamma[aside] = 0.0
         mask |= aside
-        located, t, found = _phi_attempt(gamma, s, tau_h)
     mask[located] = True
     return mask, t, (OK if found and int(mask.sum()) <= s else LOCATE_FAILED)
 

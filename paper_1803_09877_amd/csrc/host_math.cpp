@@ -224,29 +224,36 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
     if (s == 0) return broken == 0;
     if (broken > s) return false;
     std::vector<uint8_t> located;
-    bool found = locate_attempt(P, s, tau, clean.data(), located, t_out);
-    {
-        // A finite projection can be so large that its own fp64 rounding drowns the zero threshold
-        // or swallows a smaller lie whole (an adversary may send 1e30).  The enormous nodes among
-        // those phi located -- or all enormous nodes, if it found no set -- are set aside like
-        // broken ones and phi runs once more, provided the flagged nodes stay within s.  Nodes phi
-        // did not locate are never set aside while it succeeds: heavy-tailed honest batches flag nobody.
-        const double limit = kHugeOverTau * tau * median_size(P, clean.data());
+    bool found = false;
+    // A finite projection can be so large that its own fp64 rounding drowns the zero threshold
+    // or swallows a smaller lie whole (an adversary may send 1e30): "enormous" is more than
+    // kEnormous times the median.  After a pass of phi the enormous nodes among those it located
+    // -- or, if it found no set, the top layer of the enormous nodes (within a factor kEnormous of
+    // the largest) -- are set aside like broken ones and phi runs again, provided the flagged nodes
+    // stay within s; the result of the first pass that sets nothing aside stands (at most s + 1
+    // passes).  Nodes phi did not locate are never set aside while it succeeds: heavy-tailed honest
+    // batches flag nobody.
+    for (;;) {
+        found = locate_attempt(P, s, tau, clean.data(), located, t_out);
+        const double limit = kEnormous * median_size(P, clean.data());
+        double top = 0.0;
+        for (int j = 0; j < P; ++j)
+            if (!mask[j] && std::abs(clean[j]) > limit) top = std::max(top, std::abs(clean[j]));
         std::vector<uint8_t> aside(P, 0);
         int count = 0;
         for (int j = 0; j < P; ++j) {
-            aside[j] = (std::abs(clean[j]) > limit && (!found || located[j])) ? 1 : 0;
+            const double size = std::abs(clean[j]);
+            aside[j] = (!mask[j] && size > limit && (found ? located[j] != 0 : size * kEnormous > top)) ? 1 : 0;
             count += aside[j];
         }
-        if (count > 0 && broken + count <= s) {
-            for (int j = 0; j < P; ++j) {
-                if (aside[j]) {
-                    clean[j] = 0;
-                    mask[j] = 1;
-                }
+        if (count == 0 || broken + count > s) break;
+        for (int j = 0; j < P; ++j) {
+            if (aside[j]) {
+                clean[j] = 0;
+                mask[j] = 1;
             }
-            found = locate_attempt(P, s, tau, clean.data(), located, t_out);
         }
+        broken += count;
     }
     int total = 0;
     for (int j = 0; j < P; ++j) {

@@ -44,9 +44,10 @@ constexpr double kTauHBf16 = 32.0 / 8589934592.0;
 // And with an 8-bit second word (the residual in 254ths of the first word's spacing).
 constexpr double kTauHI8 = 32.0 / 4294967296.0;
 
-// A projection more than kHugeOverTau * tau * (median projection) in size is beyond what fp64
-// syndromes resolve (its rounding reaches the zero threshold): see cyclic_locate.
-constexpr double kHugeOverTau = 281474976710656.0;   // 2^48
+// A projection more than kEnormous times the median projection in size: its fp64 rounding,
+// times the error growth of the s-error locator, comes within reach of the zero thresholds
+// (see cyclic_locate).  Lies of a hundred times an honest message stay below it.
+constexpr double kEnormous = 1024.0;
 
 // phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns

@@ -236,14 +236,15 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     const int broken = (int)group_sum<kW>((double)my_broken);
 
     if (broken > s) status = 2;  // DRACO_LOCATE_FAILED: more broken messages than tolerated
-    // At most two passes of phi.  A projection beyond what fp64 syndromes resolve (more than
-    // kHugeOverTau * tau * rho in size: its rounding alone reaches the zero threshold or swallows a
-    // smaller lie whole; an adversary may send 1e30) is "enormous".  After the first pass the
-    // enormous nodes among those it located -- or all enormous nodes, if it found no set -- are set
-    // aside like broken ones and phi runs once more, provided the flagged nodes stay within s.
-    // Every branch below is taken by all 64 lanes together.
+    // Passes of phi.  A projection more than kEnormous * rho in size is "enormous": its fp64
+    // rounding can reach the zero threshold or swallow a smaller lie whole (an adversary may send
+    // 1e30).  After a pass the enormous nodes among those it located -- or, if it found no set,
+    // the top layer of the enormous nodes (within a factor kEnormous of the largest) -- are set
+    // aside like broken ones and phi runs again, provided the flagged nodes stay within s; the
+    // first pass that sets nothing aside is the last.  Every other pass flags at least one more node, so there are at
+    // most s + 1.  Every branch below is taken by all 64 lanes together.
     int aside = broken;  // nodes flagged outright so far
-    for (int pass = 0; pass < 2 && s > 0 && broken <= s; ++pass) {
+    for (int pass = 0; pass <= s && s > 0 && broken <= s; ++pass) {
         for (int j = lane; j < P; j += kW) sm.mag[j] = sqrt(cnorm2(sm.gam[j]));
         __syncthreads();
         // rho = median |gamma_j| by rank counting
@@ -421,12 +422,19 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             located = found != 0;
             fitted = found;
         }
-        bool last = pass == 1;
+        bool last = pass == s;   // (never reached with something left to set aside: aside <= s)
         if (!last) {
-            const double limit = kHugeOverTau * tau * rho;
-            auto set_aside = [&](int j) {   // enormous, not flagged yet, and located if anything was
-                if (sm.mask[j] != 0 || !(sqrt(cnorm2(sm.gam[j])) > limit)) return false;
-                if (!located) return true;
+            const double limit = kEnormous * rho;
+            double top = 0.0;   // the largest enormous projection not flagged yet
+            for (int j = lane; j < P; j += kW) {
+                const double size = sqrt(cnorm2(sm.gam[j]));
+                if (sm.mask[j] == 0 && size > limit) top = fmax(top, size);
+            }
+            top = group_max<kW>(top);
+            auto set_aside = [&](int j) {   // enormous, not flagged yet; located, or else in the top layer
+                const double size = sqrt(cnorm2(sm.gam[j]));
+                if (sm.mask[j] != 0 || !(size > limit)) return false;
+                if (!located) return size * kEnormous > top;
                 for (int i = 0; i < found; ++i)
                     if (sm.order[i] == j) return true;
                 return false;
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
             for (int j = lane; j < P; j += kW) mine += set_aside(j) ? 1 : 0;
             const int huge = (int)group_sum<kW>((double)mine);
             if (huge == 0 || aside + huge > s) {
-                last = true;   // nothing to set aside, or too many: the first pass stands
+                last = true;   // nothing to set aside, or too many: this pass stands
             } else {
                 bool go[(kMaxNodes + kW - 1) / kW];
                 for (int j = lane, k = 0; j < P; j += kW, ++k) go[k] = set_aside(j);

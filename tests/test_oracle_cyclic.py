@@ -822,7 +822,7 @@ def test_a_heavy_tailed_honest_batch_is_not_mistaken_for_lies():
     Z = o.encode_cyclic(G32, s)
     f = _f(d // 2, 5)
     gamma = o.project(o.wire_to_complex(Z), f)
-    big = np.abs(gamma) > o.HUGE_OVER_TAU * o.TAU_H * np.median(np.abs(gamma))
+    big = np.abs(gamma) > o.ENORMOUS * np.median(np.abs(gamma))
     assert big.sum() > s                                                # holders of that sample: more than s of them
     u, mask, st = o.decode_cyclic(Z, f, s, d)                           # exact messages: nothing to find
     assert st == o.OK and not mask.any()
