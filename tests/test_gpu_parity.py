@@ -426,6 +426,49 @@ def test_cyc_speculative_single_pass_decode():
         ref.close()
 
 
+@pytest.mark.parametrize("second", [False, "i8", "bf16", "f32"])
+def test_cyc_speculation_over_a_random_run_of_steps(second):
+    """Twenty steps on one plan with the adversaries changing at random (none, some, enormous
+    ones that cost the locator extra passes, a broken message): the speculating plan and one
+    that never speculates write the same bits, masks and statuses at every step, on every wire."""
+    P, s, d = 33, 3, 150_001
+    w = wl("cyc", P, s, d, (), "any", 1e-2)
+    c = Case(w, wide=second)
+    ref = Case(w, wide=second)
+    ref.plan.set_speculation(False)
+    rng = np.random.default_rng(77)
+    try:
+        c.encode()
+        ref.Z, ref.Zlo = c.Z, c.Zlo
+        for step in range(20):
+            c.receive()
+            k = int(rng.choice([0, 0, 0, 1, 2, 3]))
+            liars = sorted(rng.choice(P, size=k, replace=False).tolist())
+            for j in liars:
+                kind = int(rng.integers(0, 4))
+                if kind == 0:
+                    c.R[j, :c.mlen] *= -100.0
+                elif kind == 1:
+                    c.R[j, :c.mlen] *= float(10.0 ** rng.integers(3, 30))
+                elif kind == 2:
+                    c.R[j, :c.mlen] += 1e3
+                else:
+                    c.R[j, int(rng.integers(0, c.mlen))] = float("nan")
+            ref.R, ref.Rlo = c.R, c.Rlo
+            c.u.fill_(float("nan"))
+            ref.u.fill_(float("nan"))
+            mask, status = c.decode()
+            mask_ref, status_ref = ref.decode()
+            torch.cuda.synchronize()
+            assert status == status_ref == 0, (step, liars)
+            assert np.array_equal(mask, mask_ref) and sorted(np.flatnonzero(mask)) == liars, (step, liars)
+            assert torch.equal(c.u[:d].view(torch.int32), ref.u[:d].view(torch.int32)), (step, liars)
+            assert torch.isfinite(c.u[:d]).all() and torch.isnan(c.u[d:]).all()
+    finally:
+        c.close()
+        ref.close()
+
+
 @pytest.mark.parametrize("P,s,d,attacks,sigma,seed", [
     (15, 2, 10_007, ("offset", "noise"), 1.0, 0),
     (45, 3, 70_002, ("signflip", "noise", "noise"), 1e-2, 0x9E3779B97F4A7C15),
