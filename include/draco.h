@@ -261,11 +261,12 @@ int draco_decode_repetition_static(int P, int s, int64_t d, const float* message
  *   mask_host    as above: the located set V
  * A node whose message holds NaN or Inf is flagged outright (it is one of the
  * at most s adversaries) and the sum is still recovered.  So is a node whose
- * projection is enormous (more than 1024 times the median projection: an
- * adversary may send 1e30, and the fp64 rounding of such a value would drown
- * the syndromes of everything else), once phi has located it or has found no
- * set: phi then runs again without such nodes, layer by layer, so a smaller
- * lie cannot hide in the rounding of an enormous one.
+ * projection is enormous (an adversary may send 1e30, and the fp64 rounding
+ * of such a value would drown the syndromes of everything else): a located
+ * node beyond max(1024, tau * 2^44) times the median projection, or, when phi
+ * finds no set, the largest nodes beyond 1024 times the median.  phi then runs
+ * again without such nodes, layer by layer, so a smaller lie cannot hide in
+ * the rounding of an enormous one.
  * Returns DRACO_LOCATE_FAILED if no set of at most s nodes explains the
  * syndromes.  For s <= 16 the small linear
  * algebra of phi and b runs in one fp64 wavefront between the two streaming

@@ -428,6 +428,9 @@ def _unexplained(hk: np.ndarray, P: int, s: int, V: list) -> float:
 # the zero thresholds.  Lies of a hundred times an honest message stay below it.  See
 # phi_from_projection.
 ENORMOUS = 2.0 ** 10
+# A node that phi HAS located needs setting aside only when the rounding of its projection
+# (2^-53 of it, summed over up to 256 nodes) could pass for a syndrome: beyond tau_h * 2^44 * rho.
+LOCATED_ENORMOUS_OVER_TAU = 2.0 ** 44
 
 
 def _phi_attempt(gamma: np.ndarray, s: int, tau_h: float):
@@ -492,9 +495,11 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
     large that its own fp64 rounding drowns the zero threshold, or swallows a
     smaller lie whole (the adversary may send 1e30).  Call a projection
     enormous when it exceeds ENORMOUS * rho.  After the steps above, the
-    enormous nodes among those they located are treated like broken ones
-    (flagged, projection 0); if the steps found no set, the top layer of the
-    enormous nodes is (those within a factor ENORMOUS of the largest).  Then
+    located nodes whose projection is enormous and beyond tau_h * 2^44 * rho
+    (so large that its rounding could pass for a syndrome) are treated like
+    broken ones (flagged, projection 0); if the steps found no set, the top
+    layer of the enormous nodes is (those within a factor ENORMOUS of the
+    largest).  Then
     the steps run again, provided the flagged nodes stay within s; this
     repeats (lies of 1e30, 1e20 and 1e10 come off one layer at a time) until a
     pass sets nothing aside, whose result stands.  Nodes that phi did not
@@ -520,7 +525,7 @@ def phi_from_projection(gamma: np.ndarray, s: int, tau_h: float = TAU_H):
         if found:
             among = np.zeros(P, dtype=bool)
             among[located] = True
-            aside &= among
+            aside &= among & (size > LOCATED_ENORMOUS_OVER_TAU * tau_h * rho)
         elif aside.any():
             aside &= size * ENORMOUS > size[aside].max()
         if not aside.any() or int((mask | aside).sum()) > s:

@@ -227,7 +227,8 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
     bool found = false;
     // A finite projection can be so large that its own fp64 rounding drowns the zero threshold
     // or swallows a smaller lie whole (an adversary may send 1e30): "enormous" is more than
-    // kEnormous times the median.  After a pass of phi the enormous nodes among those it located
+    // kEnormous times the median.  After a pass of phi the located nodes whose projection is
+    // enormous and large enough for its rounding to pass for a syndrome (kLocatedEnormousOverTau)
     // -- or, if it found no set, the top layer of the enormous nodes (within a factor kEnormous of
     // the largest) -- are set aside like broken ones and phi runs again, provided the flagged nodes
     // stay within s; the result of the first pass that sets nothing aside stands (at most s + 1
@@ -235,7 +236,9 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
     // batches flag nobody.
     for (;;) {
         found = locate_attempt(P, s, tau, clean.data(), located, t_out);
-        const double limit = kEnormous * median_size(P, clean.data());
+        const double rho = median_size(P, clean.data());
+        const double limit = kEnormous * rho;
+        const double located_limit = std::max(limit, kLocatedEnormousOverTau * tau * rho);
         double top = 0.0;
         for (int j = 0; j < P; ++j)
             if (!mask[j] && std::abs(clean[j]) > limit) top = std::max(top, std::abs(clean[j]));
@@ -243,7 +246,8 @@ bool cyclic_locate(int P, int s, double tau, const std::complex<double>* gamma_i
         int count = 0;
         for (int j = 0; j < P; ++j) {
             const double size = std::abs(clean[j]);
-            aside[j] = (!mask[j] && size > limit && (found ? located[j] != 0 : size * kEnormous > top)) ? 1 : 0;
+            aside[j] = (!mask[j] && size > limit &&
+                        (found ? (located[j] != 0 && size > located_limit) : size * kEnormous > top)) ? 1 : 0;
             count += aside[j];
         }
         if (count == 0 || broken + count > s) break;

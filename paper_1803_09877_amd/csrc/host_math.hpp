@@ -48,6 +48,10 @@ constexpr double kTauHI8 = 32.0 / 4294967296.0;
 // times the error growth of the s-error locator, comes within reach of the zero thresholds
 // (see cyclic_locate).  Lies of a hundred times an honest message stay below it.
 constexpr double kEnormous = 1024.0;
+// A node that phi HAS located is set aside only when the rounding of its projection (2^-53 of it,
+// summed over up to 256 nodes) could pass for a syndrome: beyond tau * kLocatedEnormousOverTau
+// times the median (and kEnormous times it).
+constexpr double kLocatedEnormousOverTau = 17592186044416.0;   // 2^44
 
 // phi steps 2-4 on the projections gamma (length P); tau: relative zero threshold (kTauH...).  mask[j] = 1 for located
 // nodes; t (length P) receives the reconstructed error projections.  Returns

@@ -238,9 +238,10 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
     if (broken > s) status = 2;  // DRACO_LOCATE_FAILED: more broken messages than tolerated
     // Passes of phi.  A projection more than kEnormous * rho in size is "enormous": its fp64
     // rounding can reach the zero threshold or swallow a smaller lie whole (an adversary may send
-    // 1e30).  After a pass the enormous nodes among those it located -- or, if it found no set,
-    // the top layer of the enormous nodes (within a factor kEnormous of the largest) -- are set
-    // aside like broken ones and phi runs again, provided the flagged nodes stay within s; the
+    // 1e30).  After a pass the located nodes whose projection is enormous and large enough for its
+    // rounding to pass for a syndrome (kLocatedEnormousOverTau) -- or, if it found no set, the top
+    // layer of the enormous nodes (within a factor kEnormous of the largest) -- are set aside like
+    // broken ones and phi runs again, provided the flagged nodes stay within s; the
     // first pass that sets nothing aside is the last.  Every other pass flags at least one more node, so there are at
     // most s + 1.  Every branch below is taken by all 64 lanes together.
     int aside = broken;  // nodes flagged outright so far
@@ -425,6 +426,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
         bool last = pass == s;   // (never reached with something left to set aside: aside <= s)
         if (!last) {
             const double limit = kEnormous * rho;
+            const double located_limit = fmax(limit, kLocatedEnormousOverTau * tau * rho);
             double top = 0.0;   // the largest enormous projection not flagged yet
             for (int j = lane; j < P; j += kW) {
                 const double size = sqrt(cnorm2(sm.gam[j]));
@@ -435,6 +437,7 @@ __global__ __launch_bounds__(kW) void cyc_locate_kernel(const double2* __restric
                 const double size = sqrt(cnorm2(sm.gam[j]));
                 if (sm.mask[j] != 0 || !(size > limit)) return false;
                 if (!located) return size * kEnormous > top;
+                if (!(size > located_limit)) return false;
                 for (int i = 0; i < found; ++i)
                     if (sm.order[i] == j) return true;
                 return false;
