@@ -909,7 +909,7 @@ def test_encode_node_on_the_two_word_wires(P, s, d, second):
         c.encode()
         torch.cuda.synchronize()
         r = 2 * s + 1
-        for node in (0, 1, P - 2 * s, P - 1):
+        for node in (0, 1 % P, (P - 2 * s) % P, P - 1):
             Gn = c.G[[(node + t) % P for t in range(r)]].contiguous()
             z = torch.full((c.ld_m,), float("nan"), dtype=torch.float32, device=c.device)
             zl = torch.full((c.ld_m,), 77 if second == "i8" else float("nan"), dtype=c.Zlo.dtype, device=c.device)
