@@ -46,9 +46,6 @@ hipError_t launch_decode_rep_static(const float* R, int64_t ldm, float* u, uint6
 // B > P: the gradient slab holds m = B/P per-sample rows per unit gradient (rows k*m .. k*m+m-1).
 hipError_t launch_encode_rep_samples(const float* G, int64_t ldg, int m, float* Z, int64_t ldm, int P,
                                      int s, int64_t d, hipStream_t stream);
-struct CycTaps;
-hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo,
-                                     int64_t ldm, const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream);
 
 // ---- cyclic code ----
 // coef[n*(2s+1) + t] = W[(n+t) mod P][n]: the weight node n gives its t-th assigned gradient
@@ -65,6 +62,9 @@ struct CycTaps {
 // kSecondWordI8 (a slab of 8-bit residual codes), each with the same row stride counted in
 // ELEMENTS.  Ignored when the pointer is null.
 constexpr int kSecondWordF32 = 1, kSecondWordBf16 = 2, kSecondWordI8 = 3;
+// B > P on the cyclic code (rows as for launch_encode_rep_samples).
+hipError_t launch_encode_cyc_samples(const float* G, int64_t ldg, int m, float* Z, float* Zlo, int lo,
+                                     int64_t ldm, const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream);
 hipError_t launch_encode_cyc(const float* G, int64_t ldg, float* Z, float* Zlo, int lo, int64_t ldm,
                              const CycTaps& tab, int P, int s, int64_t d, hipStream_t stream);
 // Unpacked wire: real gradients [P][d] in, messages of d complex entries (2d floats) out.
