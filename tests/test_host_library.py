@@ -288,3 +288,36 @@ def test_device_entry_points_fail_loudly_without_a_gpu():
     with pytest.raises(B.DracoError) as e:
         plan.prepare()
     assert e.value.status == B.EHIP
+
+
+def test_thresholds_and_formats_agree_across_header_binding_and_oracle():
+    """The zero thresholds and second-word formats are numbers shared by the header, the binding and
+    the oracle (each writes them out itself): read the header's macros and enumerators and compare."""
+    import re
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "draco.h")).read()
+
+    def macro(name):
+        m = re.search(r"#define\s+%s\s+\(([^)]*)\)" % name, text)
+        assert m, name
+        return float(eval(m.group(1), {"__builtins__": {}}))
+
+    assert macro("DRACO_TAU") == B.TAU == o.TAU_H
+    assert macro("DRACO_TAU_WIDE") == B.TAU_WIDE == o.TAU_H_WIDE
+    assert macro("DRACO_TAU_BF16") == B.TAU_BF16 == o.TAU_H_BF16
+    assert macro("DRACO_TAU_I8") == B.TAU_I8 == o.TAU_H_I8
+    for name, value in (("DRACO_SECOND_WORD_F32", B.SECOND_WORD_F32), ("DRACO_SECOND_WORD_BF16", B.SECOND_WORD_BF16),
+                        ("DRACO_SECOND_WORD_I8", B.SECOND_WORD_I8)):
+        m = re.search(r"%s\s*=\s*(\d+)" % name, text)
+        assert m and int(m.group(1)) == value, name
+    # the host locator's notion of an enormous projection is the oracle's
+    P, s = 9, 2
+    plan = B.Plan(B.CODE_CYCLIC, P, s, 40)
+    rng = np.random.default_rng(1)
+    gamma = rng.standard_normal(P) + 1j * rng.standard_normal(P)
+    for factor in (o.ENORMOUS * 0.5, o.ENORMOUS * 4, 1e12, 1e25):
+        g = gamma.copy()
+        g[4] *= factor
+        g[7] += 3.0
+        mask, _, st = plan.cyclic_locate(g)
+        omask, _, ost = o.phi_from_projection(g, s)
+        assert st == ost and np.array_equal(mask, omask), factor
