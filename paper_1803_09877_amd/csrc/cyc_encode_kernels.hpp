@@ -137,10 +137,11 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_kernel(const float* __restr
 // taps in the same order as encode_cyc_body: identical bits.  Registers hold the window of
 // C lanes' worth (R*C*8 doubles), so this form is for narrow windows.
 // Measured at (P, s, d) = (45, 3, 25.6 M), one word per float: C = 4, D = 2 runs at 6.1 TB/s
-// against 5.9 for encode_cyc_body on the same footprint window (and 5.65 contiguous).
-template <int S, int C, int D, bool FULL>
+// against 5.9 for encode_cyc_body on the same footprint window (and 5.65 contiguous); with an
+// 8-bit second word 1750 us against 1770; with a 16- or 32-bit second word it gains nothing.
+template <int S, int C, int D, bool FULL, int LO>
 __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ G, int64_t ldg,
-                                                      float* __restrict__ Z, int64_t ldm,
+                                                      float* __restrict__ Z, float* __restrict__ Zlo, int64_t ldm,
                                                       const CycTaps tab, int P, int64_t d,
                                                       float4* head /* LDS [2S][C][kBlock] */,
                                                       const int64_t (&cq)[C]) {
@@ -195,18 +196,25 @@ __device__ __forceinline__ void encode_cyc_strip_body(const float* __restrict__ 
                 for (int q = 0; q < C; ++q) {
                     double are0, aim0, are1, aim1;
                     tap_sum<R>(tab, n, wre[q], wim[q], uu % R, are0, aim0, are1, aim1);
-                    if (FULL || nout[q] > 0)
-                        stx<FULL>(Z + (int64_t)n * ldm + cq[q],
-                                  make_float4((float)are0, (float)aim0, (float)are1, (float)aim1), nout[q]);
+                    if (FULL || nout[q] > 0) {
+                        const float4 hi = make_float4((float)are0, (float)aim0, (float)are1, (float)aim1);
+                        stx<FULL>(Z + (int64_t)n * ldm + cq[q], hi, nout[q]);
+                        if constexpr (LO != kLoNone) {
+                            const float4 lo = make_float4((float)(are0 - (double)hi.x), (float)(aim0 - (double)hi.y),
+                                                          (float)(are1 - (double)hi.z), (float)(aim1 - (double)hi.w));
+                            st_lo<FULL, LO>(Zlo, (int64_t)n * ldm + cq[q], hi, lo, nout[q]);
+                        }
+                    }
                 }
             }
         }
     }
 }
 
-template <int S, int C, int D>
+template <int S, int C, int D, int LO>
 __global__ __launch_bounds__(kBlock) void encode_cyc_strip_kernel(const float* __restrict__ G, int64_t ldg,
-                                                                  float* __restrict__ Z, int64_t ldm,
+                                                                  float* __restrict__ Z, float* __restrict__ Zlo,
+                                                                  int64_t ldm,
                                                                   const CycTaps tab, int P,
                                                                   int64_t d) {
     extern __shared__ float4 head[];  // [2S][C][kBlock]
@@ -216,8 +224,8 @@ __global__ __launch_bounds__(kBlock) void encode_cyc_strip_kernel(const float* _
     int64_t cq[C];
 #pragma unroll
     for (int q = 0; q < C; ++q) cq[q] = base + ((threadIdx.x >> 6) + 4 * q) * u + (threadIdx.x & 63) * 4;
-    if (base + (4 * C - 1) * u + 256 <= d) encode_cyc_strip_body<S, C, D, true>(G, ldg, Z, ldm, tab, P, d, head, cq);
-    else encode_cyc_strip_body<S, C, D, false>(G, ldg, Z, ldm, tab, P, d, head, cq);
+    if (base + (4 * C - 1) * u + 256 <= d) encode_cyc_strip_body<S, C, D, true, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head, cq);
+    else encode_cyc_strip_body<S, C, D, false, LO>(G, ldg, Z, Zlo, ldm, tab, P, d, head, cq);
 }
 // Workgroups of encode_cyc_strip_kernel<S, C, D> for messages of mlen floats.
 template <int C>
